@@ -1,0 +1,218 @@
+/*
+ * CPU oracle for block-sparse prefill attention.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call this file.  It shares no code with the HIP library and is deliberately
+ * plain: straight loops, fp64 accumulation, no blocking, no fusion.
+ *
+ * What it computes follows the two-stage scheme of the paper's sparse
+ * attention framework (Sec. 4.1.1, "A Versatile Library of Sparse Attention
+ * Patterns": dynamic sparsity first does a pattern computation that locates
+ * the sparse regions, then runs sparse attention on them), with
+ *   - the static part of the mask = the "A-shape" pattern (attention sinks +
+ *     a causal local window; Introduction and Sec. 4.1.1),
+ *   - the dynamic part = the uniform top-k budget per query position that
+ *     Sec. 4.1.2 describes as the common baseline (Fig. "Stem" (a)),
+ *   - the union of both (the "hybrid of static patterns and dynamic token
+ *     selection" of the abstract).
+ * The paper gives no formula for any step.  The concrete readings taken here:
+ * block granularity, arithmetic-mean pooling, raw pooled logit as the ranking
+ * score, top-k drawn from the causal candidates that are not already static,
+ * ties to the lowest block index, NaN ranked below every number, -0 == +0.
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py to
+ * textbook special cases (dense causal attention via a library routine, brute
+ * force masked softmax, closed forms, a full sort).  Against the paper itself
+ * the whole pipeline is "parity unpinned": the paper prints no value for it.
+ *
+ * Layouts: all tensors contiguous.  Q [B,Hq,S,D], K/V [B,Hkv,S,D] as bf16 bit
+ * patterns (uint16).  NB = S/Bs.  T = min(NB, ns+nl+k).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double bf16_to_f64(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Step 1 (pattern computation, pooling): xp[n,i,d] = mean over the Bs tokens
+ * of block i of x[n,i*Bs+t,d].  fp64 sum, one rounding to fp32 on export.
+ * x: [n_heads_total, S, D] bf16; xp: [n_heads_total, NB, D] fp32. */
+int oracle_pool(const uint16_t *x, int64_t n_heads_total, int64_t S, int64_t D,
+                int64_t Bs, float *xp) {
+    if (Bs <= 0 || S % Bs) return -1;
+    int64_t NB = S / Bs;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < n_heads_total; ++n)
+        for (int64_t i = 0; i < NB; ++i)
+            for (int64_t d = 0; d < D; ++d) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < Bs; ++t)
+                    acc += bf16_to_f64(x[(n * S + i * Bs + t) * D + d]);
+                xp[(n * NB + i) * D + d] = (float)(acc / (double)Bs);
+            }
+    return 0;
+}
+
+/* Step 2 (pattern computation, scoring): sp[b,h,i,j] = scale * <qp[b,h,i,:],
+ * kp[b,h/G,j,:]> for j <= i, from the fp32 pooled values, fp64 accumulate, one
+ * rounding to fp32.  Entries with j > i are set to -inf. */
+int oracle_scores(const float *qp, const float *kp, int64_t B, int64_t Hq,
+                  int64_t Hkv, int64_t NB, int64_t D, float scale, float *sp) {
+    if (Hkv <= 0 || Hq % Hkv) return -1;
+    int64_t G = Hq / Hkv;
+#pragma omp parallel for collapse(3) schedule(static)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < Hq; ++h)
+            for (int64_t i = 0; i < NB; ++i) {
+                const float *qrow = qp + ((b * Hq + h) * NB + i) * D;
+                float *srow = sp + ((b * Hq + h) * NB + i) * NB;
+                for (int64_t j = 0; j < NB; ++j) {
+                    if (j > i) { srow[j] = -INFINITY; continue; }
+                    const float *krow = kp + ((b * Hkv + h / G) * NB + j) * D;
+                    double acc = 0.0;
+                    for (int64_t d = 0; d < D; ++d)
+                        acc += (double)qrow[d] * (double)krow[d];
+                    srow[j] = (float)((double)scale * acc);
+                }
+            }
+    return 0;
+}
+
+/* Ranking order of two candidates: larger score first; equal scores (and
+ * -0 vs +0) by lower block index; NaN after every number. */
+static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
+    int na = isnan(sa), nb = isnan(sb);
+    if (na != nb) return nb;
+    if (!na && sa != sb) return sa > sb;
+    return ja < jb;
+}
+
+/* Steps 3+4 (top-k and merge with the static pattern) for every query block:
+ *   Static_i = {j < ns, j <= i} U {max(0,i-nl+1) .. i}
+ *   C_i      = {0..i} \ Static_i
+ *   TopK_i   = the min(k,|C_i|) best-ranked members of C_i
+ *   Sel_i    = Static_i U TopK_i, written ascending, padded with -1.
+ * sp: [n_rows_total = B*Hq, NB, NB] fp32; idx: [B*Hq, NB, T]; cnt: [B*Hq, NB]. */
+int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
+                int64_t nl, int64_t k, int32_t *idx, int32_t *cnt) {
+    if (ns < 0 || nl < 1 || k < 0) return -1;
+    int64_t T = ns + nl + k;
+    if (T > NB) T = NB;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int64_t n = 0; n < n_heads_total; ++n)
+        for (int64_t i = 0; i < NB; ++i) {
+            const float *srow = sp + (n * NB + i) * NB;
+            int32_t *orow = idx + (n * NB + i) * T;
+            /* state[j]: 0 = candidate, 1 = selected */
+            unsigned char *sel = (unsigned char *)calloc((size_t)NB, 1);
+            if (!sel) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
+            for (int64_t j = 0; j <= i; ++j) {
+                int is_sink = j < ns;
+                int is_local = j >= i - nl + 1;
+                sel[j] = (unsigned char)(is_sink || is_local);
+            }
+            for (int64_t pick = 0; pick < k; ++pick) {
+                int64_t best = -1;
+                for (int64_t j = 0; j <= i; ++j) {
+                    if (sel[j]) continue;
+                    if (best < 0 || ranks_before(srow[j], j, srow[best], best)) best = j;
+                }
+                if (best < 0) break; /* candidates exhausted */
+                sel[best] = 1;
+            }
+            int64_t c = 0;
+            for (int64_t j = 0; j <= i; ++j)
+                if (sel[j]) orow[c++] = (int32_t)j;
+            cnt[n * NB + i] = (int32_t)c;
+            for (; c < T; ++c) orow[c] = -1;
+            free(sel);
+        }
+    return fail ? -2 : 0;
+}
+
+/* Step 5 (sparse attention on the located regions).  For query token t in
+ * block i: keys = { s : s/Bs in Sel_i, s <= t }, logits x_s = scale * q_t.k_s,
+ * m = max x_s, p_s = exp(x_s - m), out_t = sum p_s v_s / sum p_s,
+ * lse_t = m + log sum p_s.  Everything in fp64; results rounded once to fp32.
+ *
+ * rows: optional [n_rows,3] list of (b,h,i) query blocks to compute; NULL means
+ * all of them in (b,h,i) order, so out is then laid out [B,Hq,S,D].
+ * out: [n_rows, Bs, D] fp32; lse: [n_rows, Bs] fp32 (may be NULL). */
+int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                int64_t B, int64_t Hq, int64_t Hkv, int64_t S, int64_t D,
+                int64_t Bs, int64_t T, float scale, const int32_t *idx,
+                const int32_t *cnt, const int32_t *rows, int64_t n_rows,
+                float *out, float *lse) {
+    if (Hkv <= 0 || Hq % Hkv || Bs <= 0 || S % Bs) return -1;
+    int64_t G = Hq / Hkv, NB = S / Bs;
+    if (!rows) n_rows = B * Hq * NB;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 4)
+    for (int64_t r = 0; r < n_rows; ++r)
+        for (int64_t tq = 0; tq < Bs; ++tq) {
+            int64_t b, h, i;
+            if (rows) { b = rows[3 * r]; h = rows[3 * r + 1]; i = rows[3 * r + 2]; }
+            else { b = r / (Hq * NB); h = (r / NB) % Hq; i = r % NB; }
+            int64_t t = i * Bs + tq;
+            const uint16_t *qt = q + ((b * Hq + h) * S + t) * D;
+            const uint16_t *kh = k + ((b * Hkv + h / G) * S) * D;
+            const uint16_t *vh = v + ((b * Hkv + h / G) * S) * D;
+            const int32_t *sel = idx + ((b * Hq + h) * NB + i) * T;
+            int64_t c = cnt[(b * Hq + h) * NB + i];
+            double *x = (double *)malloc(sizeof(double) * (size_t)(c * Bs + 1));
+            int64_t *key = (int64_t *)malloc(sizeof(int64_t) * (size_t)(c * Bs + 1));
+            double *acc = (double *)calloc((size_t)D, sizeof(double));
+            if (!x || !key || !acc) {
+#pragma omp atomic write
+                fail = 1;
+                free(x); free(key); free(acc);
+                continue;
+            }
+            int64_t n = 0;
+            for (int64_t e = 0; e < c; ++e)
+                for (int64_t u = 0; u < Bs; ++u) {
+                    int64_t s = (int64_t)sel[e] * Bs + u;
+                    if (s > t) continue; /* causal */
+                    double dot = 0.0;
+                    for (int64_t d = 0; d < D; ++d)
+                        dot += bf16_to_f64(qt[d]) * bf16_to_f64(kh[s * D + d]);
+                    x[n] = (double)scale * dot;
+                    key[n] = s;
+                    ++n;
+                }
+            double m = -INFINITY;
+            for (int64_t e = 0; e < n; ++e) if (x[e] > m) m = x[e];
+            double l = 0.0;
+            for (int64_t e = 0; e < n; ++e) {
+                double p = exp(x[e] - m);
+                l += p;
+                for (int64_t d = 0; d < D; ++d)
+                    acc[d] += p * bf16_to_f64(vh[key[e] * D + d]);
+            }
+            float *orow = out + (r * Bs + tq) * D;
+            for (int64_t d = 0; d < D; ++d) orow[d] = (float)(acc[d] / l);
+            if (lse) lse[r * Bs + tq] = (float)(m + log(l));
+            free(x); free(key); free(acc);
+        }
+    return fail ? -2 : 0;
+}
+
+int oracle_num_threads(void) {
+    int n = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    n = omp_get_max_threads();
+#endif
+    return n;
+}

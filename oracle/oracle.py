@@ -1,0 +1,141 @@
+"""ctypes front end of the CPU oracle (oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this.
+It shares nothing with the HIP library or its binding.  Tensors are torch CPU
+tensors; bf16 inputs are passed as their bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile oracle.c with gcc.  No -march (the .so must run on another host),
+    no fast-math, no fp contraction: the arithmetic is what the source says."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, f32, vp = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+        lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
+        lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, f32, vp]
+        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp]
+        lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, f32,
+                                    vp, vp, vp, i64, vp, vp]
+        for f in (lib.oracle_pool, lib.oracle_scores, lib.oracle_topk, lib.oracle_attn,
+                  lib.oracle_num_threads):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def default_scale(head_dim: int) -> float:
+    """1/sqrt(D) evaluated in fp32 (the value both sides use when none is given)."""
+    return float(np.float32(1.0) / np.sqrt(np.float32(head_dim)))
+
+
+def row_capacity(n_blocks: int, ns: int, nl: int, k: int) -> int:
+    return min(n_blocks, ns + nl + k)
+
+
+def _bits(x: torch.Tensor) -> torch.Tensor:
+    assert x.dtype == torch.bfloat16 and x.device.type == "cpu"
+    return x.contiguous().view(torch.int16)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def pool(x: torch.Tensor, block_size: int) -> torch.Tensor:
+    """x [B,H,S,D] bf16 -> [B,H,S/Bs,D] fp32 block means."""
+    B, H, S, D = x.shape
+    xb = _bits(x)
+    out = torch.empty((B, H, S // block_size, D), dtype=torch.float32)
+    _check(_load().oracle_pool(xb.data_ptr(), B * H, S, D, block_size, out.data_ptr()), "pool")
+    return out
+
+
+def scores(qp: torch.Tensor, kp: torch.Tensor, scale: float) -> torch.Tensor:
+    """qp [B,Hq,NB,D], kp [B,Hkv,NB,D] fp32 -> [B,Hq,NB,NB] fp32 (j>i: -inf)."""
+    B, Hq, NB, D = qp.shape
+    Hkv = kp.shape[1]
+    qp, kp = qp.contiguous(), kp.contiguous()
+    assert qp.dtype == torch.float32 and kp.dtype == torch.float32
+    sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32)
+    _check(_load().oracle_scores(qp.data_ptr(), kp.data_ptr(), B, Hq, Hkv, NB, D, scale,
+                                 sp.data_ptr()), "scores")
+    return sp
+
+
+def topk(sp: torch.Tensor, ns: int, nl: int, k: int):
+    """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32."""
+    B, Hq, NB, _ = sp.shape
+    sp = sp.contiguous()
+    assert sp.dtype == torch.float32
+    T = row_capacity(NB, ns, nl, k)
+    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32)
+    cnt = torch.empty((B, Hq, NB), dtype=torch.int32)
+    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, idx.data_ptr(),
+                               cnt.data_ptr()), "topk")
+    return idx, cnt
+
+
+def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
+           scale: float | None = None):
+    """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp)."""
+    scale = default_scale(q.shape[-1]) if scale is None else scale
+    qp, kp = pool(q, block_size), pool(k, block_size)
+    sp = scores(qp, kp, scale)
+    idx, cnt = topk(sp, ns, nl, topk_blocks)
+    return idx, cnt, sp, qp, kp
+
+
+def attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cnt: torch.Tensor,
+         block_size: int, scale: float | None = None, rows=None):
+    """Block-sparse causal attention.  rows=None: out [B,Hq,S,D], lse [B,Hq,S];
+    rows=[(b,h,i),...]: out [n,Bs,D], lse [n,Bs].  fp32 results of fp64 math."""
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    T = idx.shape[-1]
+    scale = default_scale(D) if scale is None else scale
+    qb, kb, vb = _bits(q), _bits(k), _bits(v)
+    idx = idx.contiguous().to(torch.int32)
+    cnt = cnt.contiguous().to(torch.int32)
+    if rows is None:
+        n = B * Hq * (S // block_size)
+        out = torch.empty((B, Hq, S, D), dtype=torch.float32)
+        lse = torch.empty((B, Hq, S), dtype=torch.float32)
+        rows_ptr = None
+    else:
+        rows_t = torch.tensor(rows, dtype=torch.int32).reshape(-1, 3).contiguous()
+        n = rows_t.shape[0]
+        out = torch.empty((n, block_size, D), dtype=torch.float32)
+        lse = torch.empty((n, block_size), dtype=torch.float32)
+        rows_ptr = rows_t.data_ptr()
+    _check(_load().oracle_attn(qb.data_ptr(), kb.data_ptr(), vb.data_ptr(), B, Hq, Hkv, S, D,
+                               block_size, T, scale, idx.data_ptr(), cnt.data_ptr(), rows_ptr, n,
+                               out.data_ptr(), lse.data_ptr()), "attn")
+    return out, lse

@@ -1,0 +1,124 @@
+"""Pins for the oracle's top-k + static merge (uniform top-k budget of
+Sec. 4.1.2 united with the A-shape static pattern of Sec. 4.1.1): a full
+Python sort as brute force, row invariants, tie and special-value cases, and a
+hand-worked fixture."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def brute_force_row(srow, i, ns, nl, k):
+    """Independent definition: full sort of the non-static causal candidates."""
+    static = {j for j in range(0, i + 1) if j < ns or j >= i - nl + 1}
+    cand = [j for j in range(0, i + 1) if j not in static]
+
+    def key(j):
+        s = float(srow[j])
+        if math.isnan(s):
+            return (1, 0.0, j)
+        return (0, -s if s != 0 else 0.0, j)     # -0.0 and +0.0 tie
+
+    chosen = sorted(cand, key=key)[:k]
+    return sorted(static | set(chosen))
+
+
+def check_rows(sp, idx, cnt, ns, nl, k):
+    B, H, NB, _ = sp.shape
+    T = idx.shape[-1]
+    assert T == min(NB, ns + nl + k)
+    for b in range(B):
+        for h in range(H):
+            for i in range(NB):
+                c = int(cnt[b, h, i])
+                row = idx[b, h, i].tolist()
+                want = brute_force_row(sp[b, h, i].numpy(), i, ns, nl, k)
+                assert row[:c] == want, (b, h, i)
+                assert all(x == -1 for x in row[c:])
+                # invariants
+                assert c == min(i + 1, ns + nl + k)
+                assert row[c - 1] == i
+                assert all(row[a] < row[a + 1] for a in range(c - 1))
+                assert all(j in row[:c] for j in range(min(ns, i + 1)))
+                assert all(j in row[:c] for j in range(max(0, i - nl + 1), i + 1))
+
+
+@pytest.mark.parametrize("ns,nl,k", [(1, 2, 2), (0, 1, 3), (2, 3, 0), (1, 1, 40), (3, 4, 5)])
+def test_topk_vs_full_sort(oracle, ns, nl, k):
+    g = torch.Generator().manual_seed(10 * ns + nl + 100 * k)
+    NB = 19
+    sp = torch.randn((2, 3, NB, NB), generator=g)
+    idx, cnt = oracle.topk(sp, ns, nl, k)
+    check_rows(sp, idx, cnt, ns, nl, k)
+
+
+def test_topk_ties_pick_lowest_index(oracle):
+    NB = 12
+    sp = torch.zeros((1, 1, NB, NB))
+    idx, cnt = oracle.topk(sp, 1, 2, 3)
+    # row 10: static {0} U {9,10}; candidates 1..8 all equal -> 1,2,3
+    assert idx[0, 0, 10].tolist() == [0, 1, 2, 3, 9, 10]
+    check_rows(sp, idx, cnt, 1, 2, 3)
+    # few distinct values
+    g = torch.Generator().manual_seed(5)
+    spq = torch.randint(0, 3, (1, 2, NB, NB), generator=g).float()
+    idx, cnt = oracle.topk(spq, 1, 2, 3)
+    check_rows(spq, idx, cnt, 1, 2, 3)
+
+
+def test_topk_special_values(oracle):
+    NB = 10
+    sp = torch.zeros((1, 1, NB, NB))
+    row = torch.tensor([0.0, float("nan"), -0.0, float("-inf"), 0.0, float("inf"), float("nan"), -1.0, 0.0, 0.0])
+    sp[0, 0, 9] = row
+    idx, cnt = oracle.topk(sp, 1, 1, 4)
+    # static {0, 9}; candidates 1..8 ranked: inf(5), then -0.0(2) == 0.0(4) == 0.0(8) by index,
+    # then -1(7), -inf(3), NaN(1), NaN(6)
+    assert idx[0, 0, 9].tolist() == [0, 2, 4, 5, 8, 9]
+    idx, cnt = oracle.topk(sp, 1, 1, 7)
+    assert idx[0, 0, 9].tolist() == [0, 1, 2, 3, 4, 5, 7, 8, 9]   # the first NaN beats the second
+    check_rows(sp, idx, cnt, 1, 1, 7)
+
+
+def test_topk_budget_edges(oracle):
+    g = torch.Generator().manual_seed(7)
+    NB = 9
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    idx, cnt = oracle.topk(sp, 1, 2, 0)          # k = 0: the pure A-shape
+    for i in range(NB):
+        want = sorted({0} | set(range(max(0, i - 1), i + 1)))
+        assert idx[0, 0, i, : cnt[0, 0, i]].tolist() == want
+    idx, cnt = oracle.topk(sp, 1, 2, NB)         # k >= NB: every causal block
+    assert idx.shape[-1] == NB
+    for i in range(NB):
+        assert idx[0, 1, i, : cnt[0, 1, i]].tolist() == list(range(i + 1))
+
+
+def test_topk_scale_invariance(oracle):
+    g = torch.Generator().manual_seed(8)
+    sp = torch.randn((1, 2, 17, 17), generator=g)
+    a = oracle.topk(sp, 1, 2, 4)
+    b = oracle.topk(sp * 8.0, 1, 2, 4)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_topk_hand_worked_fixture(oracle):
+    """tests/golden/topk_hand_worked.txt: a 6-block example ranked by hand."""
+    rows, want = [], []
+    with open(os.path.join(GOLDEN, "topk_hand_worked.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            left, right = line.split("->")
+            rows.append([float(x) for x in left.split()])
+            want.append([int(x) for x in right.split()])
+    NB = len(rows)
+    sp = torch.tensor(rows, dtype=torch.float32).reshape(1, 1, NB, NB)
+    idx, cnt = oracle.topk(sp, 1, 2, 2)
+    for i in range(NB):
+        assert idx[0, 0, i, : cnt[0, 0, i]].tolist() == want[i]
