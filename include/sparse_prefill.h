@@ -1,0 +1,143 @@
+/*
+ * sparse_prefill.h — C ABI of the MI355X (gfx950) block-sparse prefill
+ * attention library.
+ *
+ * The library implements the hot path of the training-free sparse attention
+ * framework of the AngelSlim technical report (arXiv 2602.21233, Sec. 4.1):
+ * long-context prefill attention ("KV Cache Generation stage", Sec. 4.1) over
+ * a block mask that unites
+ *   - a static pattern: the "A-shape" of Sec. 4.1.1 (attention-sink blocks plus
+ *     a causal local window), and
+ *   - a dynamic pattern: per query block, the top-k key blocks under a uniform
+ *     budget (the baseline scheme of Sec. 4.1.2 / Fig. "Stem" (a)), ranked by
+ *     the scaled dot product of block-mean-pooled queries and keys,
+ * followed by online-softmax attention that visits only the selected blocks.
+ * The two stages are the paper's "pattern computation" and "sparse attention
+ * kernel" (Sec. 4.1.1, dynamic sparsity).
+ *
+ * Conventions (all entry points)
+ *   - `p` is a HOST pointer.  Every other pointer is a DEVICE pointer into
+ *     memory the CALLER owns; the library never allocates, frees or
+ *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and completes asynchronously.
+ *   - Q is [batch, n_q_heads, seq_len, head_dim], K and V are
+ *     [batch, n_kv_heads, seq_len, head_dim], OUT has Q's shape; bf16.  The
+ *     strides (in elements) of the batch, head and token axes come from
+ *     `*_stride`; the head_dim axis is contiguous.  Base pointers must be
+ *     16-byte aligned and every stride a multiple of 8 elements.
+ *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - NB = seq_len / block_size query blocks and key blocks.  Row capacity
+ *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks).
+ *   - block_idx is [batch, n_q_heads, NB, T] int32, contiguous: for query
+ *     block i the selected key blocks in ascending order, then -1 padding.
+ *     block_cnt is [batch, n_q_heads, NB] int32: the number of valid entries,
+ *     always min(i + 1, n_sink + n_local + top_k); the last valid entry is
+ *     always i (the diagonal block).
+ *   - Return value: SPA_OK (0) or a negative SPA_ERR_* code.  Arguments are
+ *     validated on the host before anything is enqueued, so a failed call has
+ *     no effect on the device.  Results are deterministic run to run.
+ */
+#ifndef SPARSE_PREFILL_H
+#define SPARSE_PREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SPA_OK = 0,
+    SPA_ERR_NULLPTR = -1,             /* a required pointer is NULL                         */
+    SPA_ERR_BAD_SHAPE = -2,           /* unsupported sizes, see spa_params                  */
+    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1 or top_k < 0               */
+    SPA_ERR_BAD_STRIDE = -4,          /* stride not a multiple of 8 / pointer not 16-B aligned */
+    SPA_ERR_WORKSPACE_TOO_SMALL = -5, /* ws_bytes < spa_workspace_bytes()                   */
+    SPA_ERR_LAUNCH = -6               /* the HIP runtime rejected a launch                  */
+};
+
+typedef struct spa_params {
+    int32_t batch;          /* >= 1                                                   */
+    int32_t n_q_heads;      /* >= 1, multiple of n_kv_heads                           */
+    int32_t n_kv_heads;     /* >= 1                                                   */
+    int32_t seq_len;        /* multiple of block_size; seq_len / block_size <= 4096   */
+    int32_t head_dim;       /* 64 or 128                                              */
+    int32_t block_size;     /* 64 or 128 tokens                                       */
+    int32_t n_sink_blocks;  /* >= 0: key blocks 0 .. n_sink-1 are always selected     */
+    int32_t n_local_blocks; /* >= 1: key blocks i-n_local+1 .. i (the diagonal counts)*/
+    int32_t top_k_blocks;   /* >= 0: budget drawn from the causal blocks that are not
+                               already static; fewer if fewer exist                   */
+    float softmax_scale;    /* 0 selects 1/sqrt(head_dim)                             */
+    int64_t q_stride[3];    /* elements: batch, head, token                           */
+    int64_t k_stride[3];
+    int64_t v_stride[3];
+    int64_t o_stride[3];
+} spa_params;
+
+/* Human-readable text for a return code.  Never NULL. */
+const char *spa_strerror(int code);
+
+/* Row capacity T of block_idx for these parameters.  Host only. */
+int spa_row_capacity(const spa_params *p, int32_t *row_capacity);
+
+/* Bytes of device scratch that sparse_prefill_select / sparse_prefill_fused
+ * need in `ws` (pooled Q and K, and for the fused call the block lists when
+ * the caller does not ask for them).  Host only. */
+int spa_workspace_bytes(const spa_params *p, size_t *bytes);
+
+/* Pattern computation, step 1 (Sec. 4.1.1): block mean pooling.
+ *   q_pooled[b,h,i,:] = mean over the block's tokens of Q[b,h,i*Bs+t,:]   (fp32)
+ *   k_pooled likewise.  q_pooled is [batch, n_q_heads, NB, head_dim] and
+ *   k_pooled [batch, n_kv_heads, NB, head_dim], contiguous fp32.
+ * Either of (q, q_pooled) or (k, k_pooled) may be NULL as a pair to skip it. */
+int sparse_prefill_pool(const spa_params *p, const void *q, const void *k,
+                        float *q_pooled, float *k_pooled, void *hip_stream);
+
+/* Pattern computation, all steps (Sec. 4.1.1 dynamic sparsity; budget rule of
+ * Sec. 4.1.2 Fig. "Stem" (a); static A-shape of Sec. 4.1.1): pool Q and K,
+ * score every causal (query block, key block) pair with
+ *   score[b,h,i,j] = scale * <q_pooled[b,h,i,:], k_pooled[b,h/G,j,:]>   (fp32),
+ * take per row the top_k_blocks best non-static causal blocks (ties: lowest
+ * block index; NaN ranks below every number; -0 equals +0) and unite them with
+ * the static blocks.  Writes block_idx / block_cnt.
+ * pooled_scores_or_null: if not NULL, [batch, n_q_heads, NB, NB] fp32 receives
+ * the scores (entries with j > i are written as -inf).
+ * ws: spa_workspace_bytes() bytes of scratch, 256-byte aligned. */
+int sparse_prefill_select(const spa_params *p, const void *q, const void *k,
+                          int32_t *block_idx, int32_t *block_cnt,
+                          float *pooled_scores_or_null, void *ws, size_t ws_bytes,
+                          void *hip_stream);
+
+/* The top-k + static-merge step alone, on caller-supplied scores
+ * [batch, n_q_heads, NB, NB] fp32 (entries with j > i are ignored).  Given the
+ * same scores this produces the same lists as sparse_prefill_select, bit for
+ * bit.  Uses of p: shape, pattern. */
+int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_scores,
+                                    int32_t *block_idx, int32_t *block_cnt,
+                                    void *hip_stream);
+
+/* Sparse attention kernel (Sec. 4.1.1): for query token t of block i,
+ *   out[t] = softmax over { s <= t : block(s) in block_idx[b,h,i,:cnt] } of
+ *            scale * q_t . k_s, applied to v_s,
+ * bf16 MFMA with fp32 accumulation and fp32 online softmax; out is bf16.
+ * lse_or_null: if not NULL, [batch, n_q_heads, seq_len] fp32 receives the
+ * natural-log sum of exponentials of the scaled logits of each row.
+ * block_idx / block_cnt must satisfy the layout rules at the top of this file
+ * (ascending, unique, 0 <= entry <= i, last valid entry == i, 1 <= cnt <= T);
+ * lists produced by the select calls always do.  They are NOT validated. */
+int sparse_prefill_attn(const spa_params *p, const void *q, const void *k, const void *v,
+                        const int32_t *block_idx, const int32_t *block_cnt,
+                        void *out, float *lse_or_null, void *hip_stream);
+
+/* select followed by attn on one stream.  block_idx_or_null / block_cnt_or_null:
+ * pass both to receive the lists, or both NULL to keep them in the workspace. */
+int sparse_prefill_fused(const spa_params *p, const void *q, const void *k, const void *v,
+                         void *out, float *lse_or_null,
+                         int32_t *block_idx_or_null, int32_t *block_cnt_or_null,
+                         void *ws, size_t ws_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_PREFILL_H */

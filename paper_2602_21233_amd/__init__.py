@@ -1,0 +1,11 @@
+"""MI355X (gfx950) block-sparse prefill attention: thin Python binding over the
+C-ABI library `libsparse_prefill.so` (hand-written HIP kernels).
+
+The binding only marshals arguments: every step of the path runs in the HIP
+kernels.  PyTorch supplies device memory and the current stream.
+"""
+from .binding import (SpaError, attn, fused, library_path, load_library, pool, row_capacity, select,
+                      topk_from_scores, workspace_bytes)
+
+__all__ = ["SpaError", "attn", "fused", "library_path", "load_library", "pool", "row_capacity",
+           "select", "topk_from_scores", "workspace_bytes"]

@@ -1,0 +1,201 @@
+"""ctypes binding of include/sparse_prefill.h.  Same names, argument marshalling
+only.  There is no fallback: without the built HIP library every call raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so both share one HIP runtime
+
+from . import build as _build
+
+_lib = None
+
+EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_prefill_pool",
+           "sparse_prefill_select", "sparse_prefill_topk_from_scores", "sparse_prefill_attn",
+           "sparse_prefill_fused")
+
+
+class SpaError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sparse_prefill error {code}: {text}")
+        self.code = code
+
+
+class SpaParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("seq_len", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("n_sink_blocks", ctypes.c_int32), ("n_local_blocks", ctypes.c_int32),
+                ("top_k_blocks", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
+                ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Load the built library; build it first only if nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, pp = ctypes.c_void_p, ctypes.POINTER(SpaParams)
+    lib.spa_strerror.restype = ctypes.c_char_p
+    lib.spa_strerror.argtypes = [ctypes.c_int]
+    lib.spa_row_capacity.argtypes = [pp, ctypes.POINTER(ctypes.c_int32)]
+    lib.spa_workspace_bytes.argtypes = [pp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.sparse_prefill_pool.argtypes = [pp, vp, vp, vp, vp, vp]
+    lib.sparse_prefill_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
+    lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.sparse_prefill_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    for name in EXPORTS[1:]:
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SpaError(rc, load_library().spa_strerror(rc).decode())
+
+
+def _strides(t):
+    if t is None:
+        return (ctypes.c_int64 * 3)(0, 0, 0)
+    assert t.dim() == 4 and t.stride(3) == 1, "head_dim axis must be contiguous"
+    return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, n_sink_blocks,
+                n_local_blocks, top_k_blocks, softmax_scale=None, q=None, k=None, v=None, out=None) -> SpaParams:
+    p = SpaParams()
+    p.batch, p.n_q_heads, p.n_kv_heads = batch, n_q_heads, n_kv_heads
+    p.seq_len, p.head_dim, p.block_size = seq_len, head_dim, block_size
+    p.n_sink_blocks, p.n_local_blocks, p.top_k_blocks = n_sink_blocks, n_local_blocks, top_k_blocks
+    p.softmax_scale = 0.0 if softmax_scale is None else float(softmax_scale)
+    p.q_stride, p.k_stride, p.v_stride, p.o_stride = _strides(q), _strides(k), _strides(v), _strides(out)
+    return p
+
+
+def _params_from(q, k, block_size, ns, nl, topk, scale, v=None, out=None) -> SpaParams:
+    B, Hq, S, D = q.shape
+    return make_params(batch=B, n_q_heads=Hq, n_kv_heads=k.shape[1], seq_len=S, head_dim=D,
+                       block_size=block_size, n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=topk,
+                       softmax_scale=scale, q=q, k=k, v=v, out=out)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(ref):
+    return ctypes.c_void_p(torch.cuda.current_stream(ref.device).cuda_stream)
+
+
+def _dev_bf16(*ts):
+    for t in ts:
+        if t.dtype != torch.bfloat16 or not t.is_cuda:
+            raise TypeError("expected bf16 tensors on the GPU")
+
+
+def row_capacity(p: SpaParams) -> int:
+    t = ctypes.c_int32()
+    _check(load_library().spa_row_capacity(ctypes.byref(p), ctypes.byref(t)))
+    return t.value
+
+
+def workspace_bytes(p: SpaParams) -> int:
+    n = ctypes.c_size_t()
+    _check(load_library().spa_workspace_bytes(ctypes.byref(p), ctypes.byref(n)))
+    return n.value
+
+
+def _workspace(p: SpaParams, device):
+    return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
+
+
+def pool(q, k, block_size):
+    """sparse_prefill_pool: returns (q_pooled, k_pooled) fp32."""
+    _dev_bf16(q, k)
+    p = _params_from(q, k, block_size, 0, 1, 0, None)
+    B, Hq, S, D = q.shape
+    NB = S // block_size
+    qp = torch.empty((B, Hq, NB, D), dtype=torch.float32, device=q.device)
+    kp = torch.empty((B, k.shape[1], NB, D), dtype=torch.float32, device=q.device)
+    _check(load_library().sparse_prefill_pool(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(qp), _ptr(kp), _stream(q)))
+    return qp, kp
+
+
+def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
+           return_scores=False, workspace=None):
+    """sparse_prefill_select: returns (block_idx, block_cnt[, pooled_scores])."""
+    _dev_bf16(q, k)
+    p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale)
+    B, Hq, S, _ = q.shape
+    NB, T = S // block_size, row_capacity(p)
+    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
+    cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
+    sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
+    ws = _workspace(p, q.device) if workspace is None else workspace
+    _check(load_library().sparse_prefill_select(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(idx), _ptr(cnt),
+                                                _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
+    return (idx, cnt, sp) if return_scores else (idx, cnt)
+
+
+def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks):
+    """sparse_prefill_topk_from_scores on [B,Hq,NB,NB] fp32 device scores."""
+    if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
+        raise TypeError("expected contiguous fp32 scores on the GPU")
+    B, Hq, NB, _ = scores.shape
+    p = make_params(batch=B, n_q_heads=Hq, n_kv_heads=Hq, seq_len=NB * 64, head_dim=64, block_size=64,
+                    n_sink_blocks=n_sink_blocks, n_local_blocks=n_local_blocks, top_k_blocks=top_k_blocks)
+    T = row_capacity(p)
+    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
+    cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
+    _check(load_library().sparse_prefill_topk_from_scores(ctypes.byref(p), _ptr(scores), _ptr(idx), _ptr(cnt),
+                                                          _stream(scores)))
+    return idx, cnt
+
+
+def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None):
+    """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S])."""
+    _dev_bf16(q, k, v)
+    B, Hq, S, D = q.shape
+    out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
+    T = block_idx.shape[-1]
+    # the pattern fields only fix T here; the lists themselves carry the selection
+    p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out)
+    if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
+            or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
+        raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
+    _check(load_library().sparse_prefill_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(block_idx),
+                                              _ptr(block_cnt), _ptr(out), _ptr(lse), _stream(q)))
+    return (out, lse) if return_lse else out
+
+
+def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
+          return_lse=False, return_lists=False, workspace=None, out=None):
+    """sparse_prefill_fused: select + attn on the current stream."""
+    _dev_bf16(q, k, v)
+    B, Hq, S, D = q.shape
+    out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
+    p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v, out=out)
+    NB, T = S // block_size, row_capacity(p)
+    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device) if return_lists else None
+    cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
+    ws = _workspace(p, q.device) if workspace is None else workspace
+    _check(load_library().sparse_prefill_fused(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+                                               _ptr(idx), _ptr(cnt), _ptr(ws), ws.numel(), _stream(q)))
+    res = [out]
+    if return_lse:
+        res.append(lse)
+    if return_lists:
+        res += [idx, cnt]
+    return res[0] if len(res) == 1 else tuple(res)

@@ -1,0 +1,173 @@
+// C-ABI entry points: host-side validation, workspace carving, launches.
+// Nothing here allocates, frees or synchronises; see include/sparse_prefill.h.
+#include <math.h>
+
+#include "common.hpp"
+
+using namespace spa;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int check_shape(const spa_params* p) {
+    if (!p) return SPA_ERR_NULLPTR;
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->seq_len < 1) return SPA_ERR_BAD_SHAPE;
+    if (p->n_q_heads % p->n_kv_heads) return SPA_ERR_BAD_SHAPE;
+    if (p->head_dim != 64 && p->head_dim != 128) return SPA_ERR_BAD_SHAPE;
+    if (p->block_size != 64 && p->block_size != 128) return SPA_ERR_BAD_SHAPE;
+    if (p->seq_len % p->block_size) return SPA_ERR_BAD_SHAPE;
+    if (p->seq_len / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
+    if ((int64_t)p->batch * p->n_q_heads * (p->seq_len / p->block_size) > 0x7fffffffLL) return SPA_ERR_BAD_SHAPE;
+    if (p->n_sink_blocks < 0 || p->n_local_blocks < 1 || p->top_k_blocks < 0) return SPA_ERR_BAD_PATTERN;
+    if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return SPA_ERR_BAD_SHAPE;
+    return SPA_OK;
+}
+
+int check_tensor(const void* ptr, const int64_t s[3], int head_dim) {
+    if (!ptr) return SPA_ERR_NULLPTR;
+    if (((uintptr_t)ptr) & 15u) return SPA_ERR_BAD_STRIDE;
+    for (int a = 0; a < 3; ++a)
+        if (s[a] < 0 || (s[a] & 7)) return SPA_ERR_BAD_STRIDE;
+    if (s[2] < head_dim) return SPA_ERR_BAD_STRIDE;
+    return SPA_OK;
+}
+
+Dims resolved(const spa_params* p) {
+    Dims d = dims_of(*p);
+    if (d.scale == 0.0f) d.scale = 1.0f / sqrtf((float)d.D);
+    return d;
+}
+
+struct Workspace {
+    size_t qp_off, kp_off, idx_off, cnt_off, total;
+};
+
+Workspace carve(const Dims& d) {
+    Workspace w;
+    size_t off = 0;
+    w.qp_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.D * sizeof(float));
+    w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
+    w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
+    w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
+    w.total = off;
+    return w;
+}
+
+int launch_code(hipError_t e) { return e == hipSuccess ? SPA_OK : SPA_ERR_LAUNCH; }
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char* spa_strerror(int code) {
+    switch (code) {
+        case SPA_OK: return "ok";
+        case SPA_ERR_NULLPTR: return "a required pointer is NULL";
+        case SPA_ERR_BAD_SHAPE: return "unsupported shape (head_dim and block_size must be 64 or 128, seq_len a multiple of block_size with at most 4096 blocks, n_q_heads a multiple of n_kv_heads)";
+        case SPA_ERR_BAD_PATTERN: return "bad static pattern or budget (need n_sink >= 0, n_local >= 1, top_k >= 0)";
+        case SPA_ERR_BAD_STRIDE: return "strides must be non-negative multiples of 8 elements, token stride >= head_dim, pointers 16-byte aligned";
+        case SPA_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than spa_workspace_bytes()";
+        case SPA_ERR_LAUNCH: return "the HIP runtime rejected a kernel launch";
+        default: return "unknown error code";
+    }
+}
+
+int spa_row_capacity(const spa_params* p, int32_t* row_capacity) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!row_capacity) return SPA_ERR_NULLPTR;
+    *row_capacity = dims_of(*p).T;
+    return SPA_OK;
+}
+
+int spa_workspace_bytes(const spa_params* p, size_t* bytes) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!bytes) return SPA_ERR_NULLPTR;
+    *bytes = carve(dims_of(*p)).total;
+    return SPA_OK;
+}
+
+int sparse_prefill_pool(const spa_params* p, const void* q, const void* k, float* q_pooled,
+                        float* k_pooled, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if ((q == nullptr) != (q_pooled == nullptr) || (k == nullptr) != (k_pooled == nullptr)) return SPA_ERR_NULLPTR;
+    if (!q && !k) return SPA_ERR_NULLPTR;
+    if (q && (rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if (k && (rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    Dims d = resolved(p);
+    return launch_code(launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), q_pooled,
+                                   k_pooled, (hipStream_t)hip_stream));
+}
+
+int sparse_prefill_select(const spa_params* p, const void* q, const void* k, int32_t* block_idx,
+                          int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
+                          void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
+    Dims d = resolved(p);
+    Workspace w = carve(d);
+    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
+    float* qp = (float*)((char*)ws + w.qp_off);
+    float* kp = (float*)((char*)ws + w.kp_off);
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, st);
+    if (e != hipSuccess) return SPA_ERR_LAUNCH;
+    return launch_code(launch_score_topk(d, qp, kp, block_idx, block_cnt, pooled_scores_or_null, st));
+}
+
+int sparse_prefill_topk_from_scores(const spa_params* p, const float* pooled_scores, int32_t* block_idx,
+                                    int32_t* block_cnt, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!pooled_scores || !block_idx || !block_cnt) return SPA_ERR_NULLPTR;
+    Dims d = resolved(p);
+    return launch_code(launch_topk_from_scores(d, pooled_scores, block_idx, block_cnt, (hipStream_t)hip_stream));
+}
+
+int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const void* v,
+                        const int32_t* block_idx, const int32_t* block_cnt, void* out,
+                        float* lse_or_null, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
+    Dims d = resolved(p);
+    return launch_code(launch_attn(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), v,
+                                   strides_of(p->v_stride), block_idx, block_cnt, out,
+                                   strides_of(p->o_stride), lse_or_null, (hipStream_t)hip_stream));
+}
+
+int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
+                         float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null,
+                         void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if ((block_idx_or_null == nullptr) != (block_cnt_or_null == nullptr)) return SPA_ERR_NULLPTR;
+    if (!ws) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
+    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
+    Dims d = resolved(p);
+    Workspace w = carve(d);
+    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
+    int32_t* idx = block_idx_or_null ? block_idx_or_null : (int32_t*)((char*)ws + w.idx_off);
+    int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
+    rc = sparse_prefill_select(p, q, k, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
+    if (rc) return rc;
+    return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, hip_stream);
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

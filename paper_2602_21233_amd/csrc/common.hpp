@@ -1,0 +1,44 @@
+// Shared declarations of the sparse-prefill HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sparse_prefill.h"
+
+namespace spa {
+
+constexpr int kMaxBlocks = 4096;  // NB limit: one score row must fit a wave's LDS slice
+
+// Derived sizes every launcher needs.
+struct Dims {
+    int B, Hq, Hkv, G, S, D, Bs, NB, T;
+    int ns, nl, k;
+    float scale;
+};
+
+inline Dims dims_of(const spa_params& p) {
+    Dims d;
+    d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
+    d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = p.seq_len / p.block_size;
+    d.ns = p.n_sink_blocks; d.nl = p.n_local_blocks; d.k = p.top_k_blocks;
+    int64_t t = (int64_t)d.ns + d.nl + d.k;
+    d.T = (int)(t < d.NB ? t : d.NB);
+    d.scale = p.softmax_scale;
+    return d;
+}
+
+struct Strides { int64_t b, h, t; };
+inline Strides strides_of(const int64_t s[3]) { return Strides{s[0], s[1], s[2]}; }
+
+// Launchers (one per kernel file).  Each returns a hipError_t from the launch.
+hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                       float* qp, float* kp, hipStream_t st);
+hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, int32_t* idx,
+                             int32_t* cnt, float* scores_or_null, hipStream_t st);
+hipError_t launch_topk_from_scores(const Dims& d, const float* scores, int32_t* idx, int32_t* cnt,
+                                   hipStream_t st);
+hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                       const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
+                       void* out, Strides os, float* lse, hipStream_t st);
+
+}  // namespace spa

@@ -1,0 +1,92 @@
+// Block mean pooling of Q and K (pattern computation, step 1; Sec. 4.1.1 of the
+// AngelSlim report: the dynamic regime first locates the sparse regions).
+//
+// Pure HBM stream: every bf16 element of Q and K is read exactly once with
+// 16-byte loads, one workgroup per (head, block).  A row of head_dim elements is
+// covered by head_dim/8 adjacent lanes, so each wave instruction reads whole
+// contiguous rows.  Partial sums are fp32; the 16 (or 32) row groups of a
+// workgroup are combined through LDS in a fixed order, so results are
+// deterministic.
+#include "common.hpp"
+
+namespace spa {
+namespace {
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int D, int BS>
+__global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ q, Strides qs,
+                                                   int n_q_rows /* B*Hq or 0 */, int Hq,
+                                                   const uint16_t* __restrict__ k, Strides ks, int Hkv,
+                                                   float* __restrict__ qp, float* __restrict__ kp, int NB) {
+    constexpr int TPR = D / 8;          // lanes per token row
+    constexpr int RPP = 256 / TPR;      // token rows per pass
+    constexpr int PASSES = BS / RPP;
+    __shared__ float part[RPP][D];
+
+    const int blk = blockIdx.x;
+    int hy = blockIdx.y;
+    const uint16_t* src;
+    float* dst;
+    if (hy < n_q_rows) {
+        int b = hy / Hq, h = hy % Hq;
+        src = q + b * qs.b + h * qs.h + (int64_t)blk * BS * qs.t;
+        dst = qp + ((int64_t)hy * NB + blk) * D;
+        k = nullptr;
+    } else {
+        hy -= n_q_rows;
+        int b = hy / Hkv, h = hy % Hkv;
+        src = k + b * ks.b + h * ks.h + (int64_t)blk * BS * ks.t;
+        dst = kp + ((int64_t)hy * NB + blk) * D;
+        qs = ks;
+    }
+    const int tid = threadIdx.x;
+    const int row0 = tid / TPR, chunk = tid % TPR;
+
+    uint4 raw[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+        raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * qs.t + chunk * 8);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        acc[0] += bf16_lo(raw[p].x); acc[1] += bf16_hi(raw[p].x);
+        acc[2] += bf16_lo(raw[p].y); acc[3] += bf16_hi(raw[p].y);
+        acc[4] += bf16_lo(raw[p].z); acc[5] += bf16_hi(raw[p].z);
+        acc[6] += bf16_lo(raw[p].w); acc[7] += bf16_hi(raw[p].w);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[row0][chunk * 8 + e] = acc[e];
+    __syncthreads();
+    if (tid < D) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r) s += part[r][tid];
+        dst[tid] = s * (1.0f / (float)BS);
+    }
+}
+
+template <int D, int BS>
+hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, float* qp,
+                  float* kp, hipStream_t st) {
+    int nq = q ? d.B * d.Hq : 0, nk = k ? d.B * d.Hkv : 0;
+    if (nq + nk == 0) return hipSuccess;
+    dim3 grid(d.NB, nq + nk);
+    hipLaunchKernelGGL((pool_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)q, qs, nq, d.Hq,
+                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                       float* qp, float* kp, hipStream_t st) {
+    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, qp, kp, st);
+    if (d.D == 128 && d.Bs == 64) return launch<128, 64>(d, q, qs, k, ks, qp, kp, st);
+    if (d.D == 64 && d.Bs == 128) return launch<64, 128>(d, q, qs, k, ks, qp, kp, st);
+    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, qp, kp, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace spa

@@ -1,0 +1,88 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2602_21233_amd as m
+    return m.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sparse_prefill.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spa_[a-z_]+|sparse_prefill_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert {"sparse_prefill_select", "sparse_prefill_attn", "sparse_prefill_fused",
+            "sparse_prefill_topk_from_scores", "sparse_prefill_pool", "spa_workspace_bytes",
+            "spa_row_capacity", "spa_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2602_21233_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def _params(**kw):
+    from paper_2602_21233_amd import binding
+    base = dict(batch=1, n_q_heads=4, n_kv_heads=2, seq_len=1024, head_dim=128, block_size=128,
+                n_sink_blocks=1, n_local_blocks=2, top_k_blocks=3)
+    base.update(kw)
+    p = binding.make_params(**base)
+    for f in ("q_stride", "k_stride", "v_stride", "o_stride"):
+        setattr(p, f, (ctypes.c_int64 * 3)(0, base["seq_len"] * base["head_dim"], base["head_dim"]))
+    return p
+
+
+def test_row_capacity_and_workspace(lib):
+    import paper_2602_21233_amd as m
+    assert m.row_capacity(_params()) == 6
+    assert m.row_capacity(_params(top_k_blocks=100)) == 8          # clipped to NB
+    assert m.row_capacity(_params(top_k_blocks=0)) == 3
+    ws = m.workspace_bytes(_params())
+    # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists, each 256-byte aligned
+    assert ws >= 4 * 8 * 128 * 4 + 2 * 8 * 128 * 4 + 4 * 8 * 6 * 4 + 4 * 8 * 4 and ws % 256 == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(seq_len=1000), -2),
+    (dict(n_q_heads=5), -2), (dict(batch=0), -2), (dict(seq_len=128 * 4097), -2),
+    (dict(n_local_blocks=0), -3), (dict(n_sink_blocks=-1), -3), (dict(top_k_blocks=-2), -3),
+    (dict(softmax_scale=-1.0), -2),
+])
+def test_bad_params_rejected_on_host(lib, kw, code):
+    p = _params(**kw)
+    t = ctypes.c_int32()
+    assert lib.spa_row_capacity(ctypes.byref(p), ctypes.byref(t)) == code
+    n = ctypes.c_size_t()
+    assert lib.spa_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == code
+    assert lib.spa_strerror(code).decode() not in ("ok", "unknown error code")
+
+
+def test_null_and_misaligned_pointers_rejected_before_launch(lib):
+    p = _params()
+    fake = ctypes.c_void_p(0x10000)            # never dereferenced on the host
+    assert lib.sparse_prefill_attn(ctypes.byref(p), None, fake, fake, fake, fake, fake, None, None) == -1
+    assert lib.sparse_prefill_attn(ctypes.byref(p), fake, fake, fake, None, fake, fake, None, None) == -1
+    assert lib.sparse_prefill_attn(ctypes.byref(p), ctypes.c_void_p(0x10008), fake, fake, fake, fake, fake,
+                                   None, None) == -4
+    assert lib.sparse_prefill_select(ctypes.byref(p), fake, fake, fake, fake, None, None, 1 << 30, None) == -1
+    assert lib.sparse_prefill_select(ctypes.byref(p), fake, fake, fake, fake, None, fake, 16, None) == -5
+    assert lib.sparse_prefill_fused(ctypes.byref(p), fake, fake, fake, fake, None, fake, None, fake, 1 << 30,
+                                    None) == -1
+    assert lib.sparse_prefill_topk_from_scores(ctypes.byref(p), None, fake, fake, None) == -1
+    assert lib.sparse_prefill_pool(ctypes.byref(p), fake, None, None, None, None) == -1
+    bad = _params()
+    bad.q_stride = (ctypes.c_int64 * 3)(0, 1024 * 128, 100)
+    assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, None) == -4
+    assert lib.spa_strerror(0).decode() == "ok"
+    assert lib.spa_strerror(-99).decode() == "unknown error code"
