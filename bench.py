@@ -100,7 +100,7 @@ def main():
         idx, cnt = spa.select(dq, dk, Bs, ns, nl, tk, workspace=ws)
         if events:
             events[1].record()
-        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out)
+        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out, workspace=ws)
         if events:
             events[2].record()
         return idx, cnt

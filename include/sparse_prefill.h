@@ -81,9 +81,10 @@ const char *spa_strerror(int code);
 /* Row capacity T of block_idx for these parameters.  Host only. */
 int spa_row_capacity(const spa_params *p, int32_t *row_capacity);
 
-/* Bytes of device scratch that sparse_prefill_select / sparse_prefill_fused
- * need in `ws` (pooled Q and K, and for the fused call the block lists when
- * the caller does not ask for them).  Host only. */
+/* Bytes of device scratch that sparse_prefill_select, sparse_prefill_attn and
+ * sparse_prefill_fused need in `ws` (pooled Q and K; the block lists of a fused
+ * call whose caller does not ask for them; for head_dim 128 a per-block
+ * transposed copy of V).  One size serves all three calls.  Host only. */
 int spa_workspace_bytes(const spa_params *p, size_t *bytes);
 
 /* Pattern computation, step 1 (Sec. 4.1.1): block mean pooling.
@@ -125,10 +126,13 @@ int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_sco
  * natural-log sum of exponentials of the scaled logits of each row.
  * block_idx / block_cnt must satisfy the layout rules at the top of this file
  * (ascending, unique, 0 <= entry <= i, last valid entry == i, 1 <= cnt <= T);
- * lists produced by the select calls always do.  They are NOT validated. */
+ * lists produced by the select calls always do.  They are NOT validated.
+ * ws: spa_workspace_bytes() bytes of scratch, 256-byte aligned; its contents
+ * need not survive between calls. */
 int sparse_prefill_attn(const spa_params *p, const void *q, const void *k, const void *v,
                         const int32_t *block_idx, const int32_t *block_cnt,
-                        void *out, float *lse_or_null, void *hip_stream);
+                        void *out, float *lse_or_null, void *ws, size_t ws_bytes,
+                        void *hip_stream);
 
 /* select followed by attn on one stream.  block_idx_or_null / block_cnt_or_null:
  * pass both to receive the lists, or both NULL to keep them in the workspace. */

@@ -51,7 +51,7 @@ def load_library():
     lib.sparse_prefill_pool.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.sparse_prefill_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
-    lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
@@ -162,7 +162,8 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks):
     return idx, cnt
 
 
-def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None):
+def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
+         workspace=None):
     """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S])."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
@@ -174,8 +175,10 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
             or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
         raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
+    ws = _workspace(p, q.device) if workspace is None else workspace
     _check(load_library().sparse_prefill_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(block_idx),
-                                              _ptr(block_cnt), _ptr(out), _ptr(lse), _stream(q)))
+                                              _ptr(block_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+                                              _stream(q)))
     return (out, lse) if return_lse else out
 
 

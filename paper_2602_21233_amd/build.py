@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparse_prefill.so")
-SOURCES = ("api.hip", "pool.hip", "select.hip", "attn.hip")
+SOURCES = ("api.hip", "pool.hip", "select.hip", "attn.hip", "attn_d128.hip")
 HEADERS = ("common.hpp", os.path.join("..", "..", "include", "sparse_prefill.h"))
 
 # Packed-FP32 VALU forms are switched off for device code on purpose.

@@ -41,7 +41,7 @@ Dims resolved(const spa_params* p) {
 }
 
 struct Workspace {
-    size_t qp_off, kp_off, idx_off, cnt_off, total;
+    size_t qp_off, kp_off, idx_off, cnt_off, vt_off, total;
 };
 
 Workspace carve(const Dims& d) {
@@ -51,6 +51,8 @@ Workspace carve(const Dims& d) {
     w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
     w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
+    w.vt_off = off;
+    if (d.D == 128) off = align_up(off + (size_t)d.B * d.Hkv * d.S * d.D * sizeof(uint16_t));
     w.total = off;
     return w;
 }
@@ -135,18 +137,26 @@ int sparse_prefill_topk_from_scores(const spa_params* p, const float* pooled_sco
 
 int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const void* v,
                         const int32_t* block_idx, const int32_t* block_cnt, void* out,
-                        float* lse_or_null, void* hip_stream) {
+                        float* lse_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
-    if (!block_idx || !block_cnt) return SPA_ERR_NULLPTR;
+    if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
     if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
     if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
     if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
     if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
+    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
     Dims d = resolved(p);
+    Workspace w = carve(d);
+    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (d.D == 128)
+        return launch_code(launch_attn_d128(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), v,
+                                            strides_of(p->v_stride), block_idx, block_cnt, out,
+                                            strides_of(p->o_stride), lse_or_null, (char*)ws + w.vt_off, st));
     return launch_code(launch_attn(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), v,
                                    strides_of(p->v_stride), block_idx, block_cnt, out,
-                                   strides_of(p->o_stride), lse_or_null, (hipStream_t)hip_stream));
+                                   strides_of(p->o_stride), lse_or_null, st));
 }
 
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
@@ -166,7 +176,7 @@ int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, cons
     int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
     rc = sparse_prefill_select(p, q, k, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
     if (rc) return rc;
-    return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, hip_stream);
+    return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, ws, ws_bytes, hip_stream);
 }
 
 }  // extern "C"

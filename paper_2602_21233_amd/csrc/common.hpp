@@ -40,5 +40,9 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, int32_t* 
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
                        void* out, Strides os, float* lse, hipStream_t st);
+// head_dim 128 fast path; vt is scratch for V transposed per block, B*Hkv*S*D bf16.
+hipError_t launch_attn_d128(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                            const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
+                            void* out, Strides os, float* lse, void* vt, hipStream_t st);
 
 }  // namespace spa

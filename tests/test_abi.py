@@ -49,8 +49,9 @@ def test_row_capacity_and_workspace(lib):
     assert m.row_capacity(_params(top_k_blocks=100)) == 8          # clipped to NB
     assert m.row_capacity(_params(top_k_blocks=0)) == 3
     ws = m.workspace_bytes(_params())
-    # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists, each 256-byte aligned
-    assert ws >= 4 * 8 * 128 * 4 + 2 * 8 * 128 * 4 + 4 * 8 * 6 * 4 + 4 * 8 * 4 and ws % 256 == 0
+    # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists + transposed V (2*1024*128 bf16),
+    # each 256-byte aligned
+    assert ws >= 4 * 8 * 128 * 4 + 2 * 8 * 128 * 4 + 4 * 8 * 6 * 4 + 4 * 8 * 4 + 2 * 1024 * 128 * 2 and ws % 256 == 0
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -71,10 +72,11 @@ def test_bad_params_rejected_on_host(lib, kw, code):
 def test_null_and_misaligned_pointers_rejected_before_launch(lib):
     p = _params()
     fake = ctypes.c_void_p(0x10000)            # never dereferenced on the host
-    assert lib.sparse_prefill_attn(ctypes.byref(p), None, fake, fake, fake, fake, fake, None, None) == -1
-    assert lib.sparse_prefill_attn(ctypes.byref(p), fake, fake, fake, None, fake, fake, None, None) == -1
+    assert lib.sparse_prefill_attn(ctypes.byref(p), None, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -1
+    assert lib.sparse_prefill_attn(ctypes.byref(p), fake, fake, fake, None, fake, fake, None, fake, 1 << 30, None) == -1
     assert lib.sparse_prefill_attn(ctypes.byref(p), ctypes.c_void_p(0x10008), fake, fake, fake, fake, fake,
-                                   None, None) == -4
+                                   None, fake, 1 << 30, None) == -4
+    assert lib.sparse_prefill_attn(ctypes.byref(p), fake, fake, fake, fake, fake, fake, None, fake, 64, None) == -5
     assert lib.sparse_prefill_select(ctypes.byref(p), fake, fake, fake, fake, None, None, 1 << 30, None) == -1
     assert lib.sparse_prefill_select(ctypes.byref(p), fake, fake, fake, fake, None, fake, 16, None) == -5
     assert lib.sparse_prefill_fused(ctypes.byref(p), fake, fake, fake, fake, None, fake, None, fake, 1 << 30,
@@ -83,6 +85,6 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
     assert lib.sparse_prefill_pool(ctypes.byref(p), fake, None, None, None, None) == -1
     bad = _params()
     bad.q_stride = (ctypes.c_int64 * 3)(0, 1024 * 128, 100)
-    assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, None) == -4
+    assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -4
     assert lib.spa_strerror(0).decode() == "ok"
     assert lib.spa_strerror(-99).decode() == "unknown error code"

@@ -156,13 +156,18 @@ def test_attn_parity_small(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k):
 
 
 def test_attn_scale_and_large_logits(spa, oracle):
+    """Peaked softmax (logit std ~5.7): exercises the running-maximum updates.  The weights are
+    rounded to bf16 before the second product while the denominator sums them unrounded, so a
+    dominant weight w carries a relative error up to 2^-9 that does not cancel:
+    |dO| <= 2^-9 (|v_dom| + |O|) + bf16 rounding of O  ~  2^-9 * 2 * 4.5 + 2^-9 * 4.5 = 2.6e-2."""
     q, kk, v = _qkv(1, 2, 1, 4 * 128, 128, 41)
-    q = (q.float() * 4).to(torch.bfloat16)           # logits with |x| up to ~20: exercises the running max
+    q = (q.float() * 4).to(torch.bfloat16)
     idx, cnt = _oracle_lists(oracle, q, kk, 128, 1, 1, 1)
     want, want_lse = oracle.attn(q, kk, v, idx, cnt, 128, scale=0.125)
     out, lse = spa.attn(q.cuda(), kk.cuda(), v.cuda(), idx.cuda(), cnt.cuda(), 128, softmax_scale=0.125,
                         return_lse=True)
-    _assert_attn_close(out, want)
+    diff = (out.float().cpu() - want).abs()
+    assert diff.max().item() <= 2.6e-2 and diff.mean().item() <= MEAN_ABS
     assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
 
 
