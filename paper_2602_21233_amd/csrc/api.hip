@@ -30,7 +30,7 @@ int check_tensor(const void* ptr, const int64_t s[3], int head_dim) {
     if (((uintptr_t)ptr) & 15u) return SPA_ERR_BAD_STRIDE;
     for (int a = 0; a < 3; ++a)
         if (s[a] < 0 || (s[a] & 7)) return SPA_ERR_BAD_STRIDE;
-    if (s[2] < head_dim) return SPA_ERR_BAD_STRIDE;
+    if (s[2] < head_dim || s[2] > (1 << 22)) return SPA_ERR_BAD_STRIDE;   // 32-bit byte offsets inside a block
     return SPA_OK;
 }
 

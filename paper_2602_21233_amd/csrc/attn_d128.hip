@@ -40,6 +40,13 @@ constexpr int TILE = KT * D;           // elements of one K (or V^T) sub-tile: 1
 
 __device__ __forceinline__ int swz_k(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }   // 256-B rows
 __device__ __forceinline__ int swz_v(int row) { return (row >> 1) & 7; }                        // 128-B rows
+// value held by lane ^ 32, via v_permlane32_swap (no LDS round trip)
+__device__ __forceinline__ float other_half(float x) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+    u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    // r[0]: lanes 32..63 now hold lanes 0..31's value; r[1]: lanes 0..31 hold lanes 32..63's value
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
 __device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
 // ---------------------------------------------------------------------------
@@ -117,27 +124,32 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
 
     // Direct global->LDS loads: instruction `inst` of a sub-tile fills 1 KB of LDS in lane order
     // (4 K rows of 256 B, or 8 V^T rows of 128 B); the lane picks the global 16-byte chunk whose
-    // swizzled position it is writing.
-    const int k_lrow = lane >> 4, k_lchunk = lane & 15;
-    const int v_lrow = lane >> 3, v_lchunk = lane & 7;
-    auto issue_loads = [&](int st, int buf) {
-        const int blk = sel[st / NSUB];
+    // swizzled position it is writing.  Per-lane byte offsets are fixed for the whole kernel; the
+    // tile base is wave-uniform, so each load is base (SGPRs) + 32-bit lane offset.
+    uint32_t k_offb[LPW], v_offb[LPW];
+#pragma unroll
+    for (int x = 0; x < LPW; ++x) {
+        const int inst = wave * LPW + x;
+        const int krow = 4 * inst + (lane >> 4);
+        const int vrow = 8 * inst + (lane >> 3);
+        k_offb[x] = 2u * ((uint32_t)krow * (uint32_t)ks.t + (uint32_t)(((lane & 15) ^ swz_k(krow)) << 3));
+        v_offb[x] = 2u * (uint32_t)(vrow * BS + (((lane & 7) ^ swz_v(vrow)) << 3));
+    }
+    auto issue_loads = [&](int st, int buf, int blk) {
         const int sub = st % NSUB;
-        const uint16_t* kt = kb + ((int64_t)blk * BS + sub * KT) * ks.t;
-        const uint16_t* vtt = vtb + (int64_t)blk * D * BS + sub * KT;
+        const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + sub * KT) * ks.t);
+        const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + sub * KT);
 #pragma unroll
         for (int x = 0; x < LPW; ++x) {
             const int inst = wave * LPW + x;
-            const int krow = 4 * inst + k_lrow;
-            const int vrow = 8 * inst + v_lrow;
-            const uint16_t* ksrc = kt + (int64_t)krow * ks.t + ((k_lchunk ^ swz_k(krow)) << 3);
-            const uint16_t* vsrc = vtt + vrow * BS + ((v_lchunk ^ swz_v(vrow)) << 3);
-            __builtin_amdgcn_global_load_lds((gbl_void*)ksrc, (lds_void*)&smem[buf][0][inst * 512], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gbl_void*)vsrc, (lds_void*)&smem[buf][1][inst * 512], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_void*)(kt + k_offb[x]), (lds_void*)&smem[buf][0][inst * 512], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_void*)(vtt + v_offb[x]), (lds_void*)&smem[buf][1][inst * 512], 16, 0, 0);
         }
     };
 
-    issue_loads(0, 0);
+    issue_loads(0, 0, sel[0]);
+    // key block of the sub-tile after next, fetched one iteration early (scalar load latency)
+    int blk_next = sel[(1 / NSUB) < n_sel ? (1 / NSUB) : 0];
 
     // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
     bf16x8 qf[8];
@@ -177,7 +189,11 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     for (int st = 0; st < n_st; ++st, buf ^= 1) {
         __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's share of sub-tile st has landed
         __syncthreads();                           // ... and everybody's; buffer buf^1 is free again
-        if (st + 1 < n_st) issue_loads(st + 1, buf ^ 1);
+        if (st + 1 < n_st) {
+            issue_loads(st + 1, buf ^ 1, blk_next);
+            const int e2 = (st + 2) / NSUB;
+            blk_next = sel[e2 < n_sel ? e2 : n_sel - 1];
+        }
 
         const bool diag = st >= n_st - NSUB;       // sub-tile of the diagonal block (always last)
         const int sub = st % NSUB;
@@ -211,7 +227,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sacc[0][r], sacc[1][r]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = fmaxf(mx, other_half(mx));
         if (__any((mx - m_run) * c > 8.0f)) {      // wave-uniform; true on the first sub-tile
             const float m_new = fmaxf(m_run, mx);
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
@@ -253,7 +269,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     }
 
     // ---- epilogue ----------------------------------------------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
     uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
 #pragma unroll
