@@ -21,6 +21,8 @@
 //   * the running maximum is only raised when a row's new maximum exceeds it by
 //     more than 2^8 in the exp2 domain, so the O^T rescale is rare; the final
 //     normalisation makes the result independent of this.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace spa {
@@ -135,21 +137,30 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         k_offb[x] = 2u * ((uint32_t)krow * (uint32_t)ks.t + (uint32_t)(((lane & 15) ^ swz_k(krow)) << 3));
         v_offb[x] = 2u * (uint32_t)(vrow * BS + (((lane & 7) ^ swz_v(vrow)) << 3));
     }
-    auto issue_loads = [&](int st, int buf, int blk) {
-        const int sub = st % NSUB;
-        const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + sub * KT) * ks.t);
-        const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + sub * KT);
+    // K and V^T sub-tiles are staged separately: K runs one sub-tile ahead of V^T because the
+    // logits of sub-tile n+1 are computed while the softmax of sub-tile n is in progress.
+    auto issue_k = [&](int st, int blk) {
+        const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + (st % NSUB) * KT) * ks.t);
 #pragma unroll
-        for (int x = 0; x < LPW; ++x) {
-            const int inst = wave * LPW + x;
-            __builtin_amdgcn_global_load_lds((gbl_void*)(kt + k_offb[x]), (lds_void*)&smem[buf][0][inst * 512], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gbl_void*)(vtt + v_offb[x]), (lds_void*)&smem[buf][1][inst * 512], 16, 0, 0);
-        }
+        for (int x = 0; x < LPW; ++x)
+            __builtin_amdgcn_global_load_lds((gbl_void*)(kt + k_offb[x]),
+                                             (lds_void*)&smem[st & 1][0][(wave * LPW + x) * 512], 16, 0, 0);
+    };
+    auto issue_v = [&](int st, int blk) {
+        const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + (st % NSUB) * KT);
+#pragma unroll
+        for (int x = 0; x < LPW; ++x)
+            __builtin_amdgcn_global_load_lds((gbl_void*)(vtt + v_offb[x]),
+                                             (lds_void*)&smem[st & 1][1][(wave * LPW + x) * 512], 16, 0, 0);
+    };
+    auto blk_of = [&](int st) {        // key block of sub-tile st (clamped: never read past the list)
+        const int e = st / NSUB;
+        return sel[e < n_sel ? e : n_sel - 1];
     };
 
-    issue_loads(0, 0, sel[0]);
-    // key block of the sub-tile after next, fetched one iteration early (scalar load latency)
-    int blk_next = sel[(1 / NSUB) < n_sel ? (1 / NSUB) : 0];
+    issue_k(0, sel[0]);
+    issue_v(0, sel[0]);
+    if (n_st > 1) issue_k(1, blk_of(1));
 
     // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
     bf16x8 qf[8];
@@ -159,8 +170,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
     }
     // LDS read offsets (elements within a tile)
-    int k_rd[2];        // K row of this lane for key chunk kc, before the per-slice chunk XOR
-    int k_sw[2];
+    int k_rd[2], k_sw[2];
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc) {
         const int row = swap_bits23(32 * kc + l32);
@@ -174,7 +184,6 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         v_rd[dc] = row * KT;
         v_sw[dc] = swz_v(row);
     }
-
     f32x16 oacc[4];
 #pragma unroll
     for (int dc = 0; dc < 4; ++dc)
@@ -185,50 +194,42 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const float c = scale * 1.44269504088896340736f;
     const int q_in_blk = 32 * wave + l32;
 
-    int buf = 0;
-    for (int st = 0; st < n_st; ++st, buf ^= 1) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's share of sub-tile st has landed
-        __syncthreads();                           // ... and everybody's; buffer buf^1 is free again
-        if (st + 1 < n_st) {
-            issue_loads(st + 1, buf ^ 1, blk_next);
-            const int e2 = (st + 2) / NSUB;
-            blk_next = sel[e2 < n_sel ? e2 : n_sel - 1];
-        }
+    // One K fragment (A operand of S^T = K Q^T): 8 dims of the lane's key row.
+    auto k_frag = [&](const uint16_t* sK, int kc, int s) {
+        return *reinterpret_cast<const bf16x8*>(sK + k_rd[kc] + (((2 * s + half) ^ k_sw[kc]) << 3));
+    };
 
-        const bool diag = st >= n_st - NSUB;       // sub-tile of the diagonal block (always last)
-        const int sub = st % NSUB;
-        if (diag && KT * sub > 32 * wave + 31) continue;   // nothing visible for this wave's queries
-        const uint16_t* sK = smem[buf][0];
-        const uint16_t* sV = smem[buf][1];
-
-        // ---- S^T = K Q^T ---------------------------------------------------
-        f32x16 sacc[2];
+    // The pipeline step.  Works on 32-key chunks: while the VALU turns the logits of the current
+    // chunk (s_cur) into probabilities and the MFMA pipe accumulates them into O^T, the same MFMA
+    // pipe also produces the logits of a later chunk (s_nxt, the same chunk position of the next
+    // sub-tile), so MFMA and VALU work always come from independent dependency chains.
+    //   KCN / KCC: chunk index (0/1) inside its 64-key sub-tile of the produced / current chunk.
+    auto step = [&](auto kcn_tag, auto kcc_tag, f32x16& s_cur, f32x16& s_nxt, const uint16_t* sKn,
+                    const uint16_t* sV, bool diag, int sub) {
+        constexpr int KCN = decltype(kcn_tag)::value, KCC = decltype(kcc_tag)::value;
+        // causal mask on the diagonal block: register r of a chunk holds key
+        // 32*chunk + 16*(r>>3) + 8*half + (r&7) of the sub-tile
+        if (diag && KT * sub + 32 * KCC + 31 > 32 * wave) {
 #pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kc][r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + k_rd[kc] + (((2 * s + half) ^ k_sw[kc]) << 3));
-                sacc[kc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc[kc], 0, 0, 0);
+            for (int r = 0; r < 16; ++r) {
+                int kpos = KT * sub + 32 * KCC + 16 * (r >> 3) + 8 * half + (r & 7);
+                if (kpos > q_in_blk) s_cur[r] = -INFINITY;
             }
         }
-        // register r of chunk kc holds key 32*kc + 16*(r>>3) + 8*half + (r&7) of the sub-tile
-        if (diag && KT * sub + KT - 1 > 32 * wave) {
+        f32x16 acc;
 #pragma unroll
-            for (int kc = 0; kc < 2; ++kc)
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int kpos = KT * sub + 32 * kc + 16 * (r >> 3) + 8 * half + (r & 7);
-                    if (kpos > q_in_blk) sacc[kc][r] = -INFINITY;
-                }
-        }
-        // ---- online softmax --------------------------------------------------
-        float mx = fmaxf(sacc[0][0], sacc[1][0]);
+        for (int sidx = 0; sidx < 4; ++sidx)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sKn, KCN, sidx), qf[sidx], acc, 0, 0, 0);
+        float mx = fmaxf(s_cur[0], s_cur[1]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sacc[0][r], sacc[1][r]));
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
         mx = fmaxf(mx, other_half(mx));
-        if (__any((mx - m_run) * c > 8.0f)) {      // wave-uniform; true on the first sub-tile
+        // Raise the reference maximum only when some row outgrew it by more than 2^8 (exp2
+        // domain); wave-uniform; always true on the first chunk.  A fully masked chunk
+        // (mx = -inf) never triggers it and contributes exact zeros.
+        if (__any((mx - m_run) * c > 8.0f)) {
             const float m_new = fmaxf(m_run, mx);
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
             m_run = m_new;
@@ -238,34 +239,72 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
         }
+#pragma unroll
+        for (int sidx = 4; sidx < 8; ++sidx)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sKn, KCN, sidx), qf[sidx], acc, 0, 0, 0);
+        s_nxt = acc;
         const float mc = m_run * c;
         float psum = 0.f;
 #pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
+        for (int u = 0; u < 2; ++u) {
+            f32x8 pf;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float pv = __builtin_amdgcn_exp2f(fmaf(sacc[kc][r], c, -mc));
-                sacc[kc][r] = pv;
-                psum += pv;
+            for (int x = 0; x < 8; ++x) {
+                pf[x] = __builtin_amdgcn_exp2f(fmaf(s_cur[8 * u + x], c, -mc));
+                psum += pf[x];
             }
+            const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+            const int chunk = 2 * (2 * KCC + u) + half;          // 8 keys = one 16-byte chunk of a V^T row
+#pragma unroll
+            for (int dc = 0; dc < 4; ++dc) {
+                bf16x8 a = *reinterpret_cast<const bf16x8*>(sV + v_rd[dc] + ((chunk ^ v_sw[dc]) << 3));
+                oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[dc], 0, 0, 0);
+            }
+        }
         l_run += psum;
+    };
 
-        // ---- O^T += V^T P^T ---------------------------------------------------
+    // ---- prologue: logits of the two chunks of sub-tile 0 ------------------------------
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+    __syncthreads();
+    f32x16 s0, s1, s2;                             // logits: two chunks waiting/current + one being produced
 #pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                f32x8 pf;
-#pragma unroll
-                for (int x = 0; x < 8; ++x) pf[x] = sacc[kc][8 * u + x];
-                const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-                const int chunk = 2 * (2 * kc + u) + half;          // 8 keys = one 16-byte chunk of a V^T row
-#pragma unroll
-                for (int dc = 0; dc < 4; ++dc) {
-                    bf16x8 a = *reinterpret_cast<const bf16x8*>(sV + v_rd[dc] + ((chunk ^ v_sw[dc]) << 3));
-                    oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[dc], 0, 0, 0);
-                }
-            }
+    for (int sidx = 0; sidx < 8; ++sidx) {
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(smem[0][0], 0, sidx), qf[sidx], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(smem[0][0], 1, sidx), qf[sidx], s1, 0, 0, 0);
+    }
+    int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles n+1 and n+2
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+
+    // One 64-key sub-tile n: its two chunks are current (a = chunk 0, b = chunk 1, both computed
+    // during sub-tile n-1); the logits of sub-tile n+1 are produced into c and then a.  Only K(n+1)
+    // and V^T(n) are read, so each operand needs just two LDS buffers.
+    auto sub_tile = [&](int n, f32x16& a, f32x16& b, f32x16& cnext) {
+        // K(n+1) and V(n) have been requested; make them visible and retire the previous
+        // sub-tile's readers of the buffers refilled below.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (n + 2 < n_st) issue_k(n + 2, blk2);
+        if (n + 1 < n_st) issue_v(n + 1, blk1);
+        blk1 = blk2;
+        blk2 = blk_of(n + 3);
+        const uint16_t* sKn = smem[(n + 1) & 1][0];   // on the last sub-tile: idle buffer, result dropped
+        const uint16_t* sV = smem[n & 1][1];
+        const bool diag = n >= n_st - NSUB;           // the diagonal block is always the last of the list
+        const int sub = n % NSUB;
+        step(I0{}, I0{}, a, cnext, sKn, sV, diag, sub);
+        step(I1{}, I1{}, b, a, sKn, sV, diag, sub);
+    };
+    for (int n = 0;;) {                               // register roles rotate with period 3
+        sub_tile(n, s0, s1, s2);
+        if (++n == n_st) break;
+        sub_tile(n, s2, s0, s1);
+        if (++n == n_st) break;
+        sub_tile(n, s1, s2, s0);
+        if (++n == n_st) break;
     }
 
     // ---- epilogue ----------------------------------------------------------------
