@@ -2,13 +2,24 @@
 // (pattern computation, steps 2-4; Sec. 4.1.1 dynamic sparsity, uniform top-k
 // budget of Sec. 4.1.2 Fig. "Stem" (a), static A-shape of Sec. 4.1.1).
 //
-// One 64-lane wavefront owns one row (b, h, i).  Lane l scores key blocks
-// j = l, l+64, ... and turns each fp32 score into an order-preserving uint32 key
-// kept in the wave's LDS slice.  The k-th largest key is found exactly by a
-// bitwise descent (ballot + popcount per step), ties at the threshold are
-// resolved by block index with a running prefix count, and because the final
-// pass walks j in ascending order the emitted list is already sorted, with the
-// static blocks simply forced on.
+// score_topk_mfma_kernel: one 512-thread workgroup owns R consecutive query
+// blocks of one query head.
+//   Phase 1 - scores on the matrix cores.  The fp32 pooled vectors are split
+//   into a bf16 head and a bf16 tail (x = hi + lo, |x - hi - lo| <= 2^-18 |x|)
+//   and each 32x32 tile of Qp Kp^T is accumulated in fp32 from three
+//   v_mfma_f32_32x32x16_bf16 products (hi.hi + hi.lo + lo.hi); the dropped
+//   lo.lo term is below 2^-17 of a product.  The 8 wavefronts take the key-block
+//   tiles round robin, reading Kp straight from L2 in operand layout.  The scores
+//   of the R rows stay in LDS; the NB x NB matrix never exists in memory unless
+//   the caller asks for it.
+//   Phase 2 - exact selection.  A wavefront owns a row: lane l holds the keys of
+//   blocks l, l+64, ... in registers as order-preserving uint32, finds the k-th
+//   largest by a bitwise descent (ballot + popcount per step, early exit when a
+//   prefix isolates exactly k), resolves ties at the threshold by block index
+//   with a running prefix count, and, because the last pass walks the blocks in
+//   ascending order, emits static U top-k already sorted.
+// topk_from_scores_kernel applies the same rule to caller-supplied scores (one
+// wavefront per row, keys in LDS).
 #include "common.hpp"
 
 namespace spa {
@@ -116,52 +127,166 @@ __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
     select_row(keys, i, ns, nl, k, T, idx + row * T, cnt + row);
 }
 
-// scores computed here: lane j does the full dot product <qp[row], kp[j]>.
-template <int D>
-__global__ __launch_bounds__(kWaves * 64) void score_topk_kernel(
-    const float* __restrict__ qp, const float* __restrict__ kp, int64_t n_rows, int Hq, int G, int NB,
-    int ns, int nl, int k, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-    float* __restrict__ scores_out) {
-    extern __shared__ uint32_t lds_keys[];
-    __shared__ float qrow[kWaves][D];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
-    if (row >= n_rows) return;
-    const int i = (int)(row % NB);
-    const int64_t bh = row / NB;                            // b*Hq + h
-    const int64_t b = bh / Hq;
-    const int h = (int)(bh % Hq);
-    const int Hkv = Hq / G;
-    const float* kbase = kp + ((b * Hkv + h / G) * NB) * D;
-    const int padded = ((NB + 63) >> 6) << 6;
-    uint32_t* keys = lds_keys + wave * padded;
-    for (int d = lane; d < D; d += 64) qrow[wave][d] = qp[row * D + d];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();             // qrow is read across lanes of this wave only
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// x = hi + lo with both parts bf16 (round to nearest even twice)
+__device__ __forceinline__ void split_bf16(const float* __restrict__ src, bf16x8& hi, bf16x8& lo) {
+    const float4 a = *reinterpret_cast<const float4*>(src);
+    const float4 b = *reinterpret_cast<const float4*>(src + 4);
+    f32x8 x = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    hi = __builtin_convertvector(x, bf16x8);
+    f32x8 back = __builtin_convertvector(hi, f32x8);
+    lo = __builtin_convertvector(x - back, bf16x8);
+}
+
+// Same selection as select_row, with the row's keys in registers: key[m] belongs to
+// block 64*m + lane (0 for static blocks, blocks beyond i, and unused chunks).
+template <int MAXC>
+__device__ __forceinline__ void select_row_regs(const uint32_t (&key)[MAXC], int i, int ns, int nl, int k, int T,
+                                                int32_t* __restrict__ idx_row, int32_t* __restrict__ cnt_out) {
+    const int lane = threadIdx.x & 63;
+    const int n = i + 1;
+    const int chunks = (n + 63) >> 6;
     const int lo = i - nl + 1;
-    const int chunks = (i + 64) >> 6;
-    for (int m = 0; m < chunks; ++m) {
-        int j = (m << 6) + lane;
-        uint32_t key = 0u;
-        if (j <= i) {
-            const float4* kr = reinterpret_cast<const float4*>(kbase + (int64_t)j * D);
-            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
-            for (int d4 = 0; d4 < D / 4; ++d4) {
-                float4 kv = kr[d4];
-                float4 qv = *reinterpret_cast<const float4*>(&qrow[wave][d4 * 4]);
-                a0 = fmaf(qv.x, kv.x, a0); a1 = fmaf(qv.y, kv.y, a1);
-                a2 = fmaf(qv.z, kv.z, a2); a3 = fmaf(qv.w, kv.w, a3);
+    int n_sink = ns < n ? ns : n;
+    int n_local = nl < n ? nl : n;
+    int first_local = lo > 0 ? lo : 0;
+    int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
+    const int n_cand = n - (n_sink + n_local - overlap);
+    const int kk = k < n_cand ? k : n_cand;
+
+    uint32_t thr = 0xffffffffu;
+    int need_eq = 0;
+    if (kk > 0) {
+        if (kk == n_cand) {
+            thr = 0u;
+        } else {
+            uint32_t p = 0u;
+            int c_at_p = n_cand;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = p | (1u << bit);
+                int c = 0;
+#pragma unroll
+                for (int m = 0; m < MAXC; ++m)
+                    if (m < chunks) c += __popcll(__ballot(key[m] >= trial));
+                if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
             }
-            float s = scale * ((a0 + a1) + (a2 + a3));
-            if (scores_out) scores_out[row * NB + j] = s;
-            if (!(j < ns || j >= lo)) key = rank_key(s);
+            if (c_at_p == kk) {
+                thr = p - 1u;
+            } else {
+                int gt = 0;
+#pragma unroll
+                for (int m = 0; m < MAXC; ++m)
+                    if (m < chunks) gt += __popcll(__ballot(key[m] > p));
+                thr = p;
+                need_eq = kk - gt;
+            }
         }
-        keys[j] = key;
     }
-    if (scores_out)
-        for (int j = i + 1 + lane; j < NB; j += 64) scores_out[row * NB + j] = -INFINITY;
-    select_row(keys, i, ns, nl, k, T, idx + row * T, cnt + row);
+    int eq_seen = 0, out_pos = 0;
+#pragma unroll
+    for (int m = 0; m < MAXC; ++m) {
+        if (m < chunks) {
+            const int j = (m << 6) + lane;
+            const uint32_t kv = key[m];
+            const bool is_static = j < n && (j < ns || j >= lo);
+            const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
+            const uint64_t eq_mask = __ballot(is_eq);
+            const bool take = is_static || (kv != 0u && kv > thr) ||
+                              (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
+            const uint64_t take_mask = __ballot(take);
+            if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = j;
+            eq_seen += __popcll(eq_mask);
+            out_pos += __popcll(take_mask);
+        }
+    }
+    for (int t = out_pos + lane; t < T; t += 64) idx_row[t] = -1;
+    if (lane == 0) *cnt_out = out_pos;
+}
+
+constexpr int kMfmaWaves = 8;
+
+template <int D, int R, int MAXC>
+__global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
+    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int ns, int nl, int k,
+    int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
+    constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
+    constexpr int DS = D / 16;
+    extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
+
+    const int tile = gridDim.x - 1 - blockIdx.x;          // long rows first
+    const int i0 = tile * R;
+    const int bh = blockIdx.y;                            // b * Hq + h
+    const int b = bh / Hq, h = bh % Hq;
+    const int Hkv = Hq / G;
+    const float* qbase = qp + (int64_t)bh * NB * D;
+    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * NB * D;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
+    const int n_jt = (i_last >> 5) + 1;                   // 32-wide key-block tiles with some j <= i_last
+
+    // ---- phase 1 ---------------------------------------------------------------------
+    bf16x8 q_hi[DS], q_lo[DS];
+    {
+        int row = i0 + (l32 % R);
+        if (row > NB - 1) row = NB - 1;                   // rows past the end are computed but never used
+        const float* src = qbase + (int64_t)row * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) split_bf16(src + 16 * s, q_hi[s], q_lo[s]);
+    }
+    for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
+        const int j = 32 * jt + l32;
+        const float* src = kbase + (int64_t)(j < NB ? j : NB - 1) * D + 8 * half;
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            bf16x8 k_hi, k_lo;
+            split_bf16(src + 16 * s, k_hi, k_lo);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_lo[s], k_hi, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_lo, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_hi, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int mrow = 8 * (r >> 2) + 4 * half + (r & 3);     // row of the 32x32 result held in acc[r]
+            if (mrow < R) {
+                const float sc = scale * acc[r];
+                S[mrow * LD + j] = sc;
+                const int i = i0 + mrow;
+                if (scores_out != nullptr && i < NB && j < NB)
+                    scores_out[((int64_t)bh * NB + i) * NB + j] = j <= i ? sc : -INFINITY;
+            }
+        }
+    }
+    if (scores_out != nullptr) {                          // key blocks past the last computed tile
+        const int j_first = 32 * n_jt;
+        for (int r = 0; r < R && i0 + r < NB; ++r)
+            for (int j = j_first + (int)threadIdx.x; j < NB; j += kMfmaWaves * 64)
+                scores_out[((int64_t)bh * NB + i0 + r) * NB + j] = -INFINITY;
+    }
+    __syncthreads();
+
+    // ---- phase 2 ---------------------------------------------------------------------
+    for (int r = wave; r < R; r += kMfmaWaves) {
+        const int i = i0 + r;
+        if (i >= NB) break;                               // wave-uniform
+        const int lo = i - nl + 1;
+        uint32_t key[MAXC];
+#pragma unroll
+        for (int m = 0; m < MAXC; ++m) {
+            const int j = (m << 6) + lane;
+            uint32_t kv = 0u;
+            if (j <= i && !(j < ns || j >= lo)) kv = rank_key(S[r * LD + j]);
+            key[m] = kv;
+        }
+        const int64_t row = (int64_t)bh * NB + i;
+        select_row_regs<MAXC>(key, i, ns, nl, k, T, idx + row * T, cnt + row);
+    }
 }
 
 // Dynamic LDS above the default cap has to be requested per kernel.
@@ -185,22 +310,34 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, int32_t* 
     return hipGetLastError();
 }
 
+template <int D, int R, int MAXC>
+hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, int32_t* idx, int32_t* cnt,
+                       float* scores_or_null, hipStream_t st) {
+    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
+    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC>, lds);
+    if (e != hipSuccess) return e;
+    dim3 grid((d.NB + R - 1) / R, d.B * d.Hq);
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
+                       d.G, d.NB, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, int32_t* idx, int32_t* cnt,
+                         float* scores_or_null, hipStream_t st) {
+    // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
+    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, idx, cnt, scores_or_null, st);
+    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, idx, cnt, scores_or_null, st);
+    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, idx, cnt, scores_or_null, st);
+    return launch_mfma<D, 8, 64>(d, qp, kp, idx, cnt, scores_or_null, st);
+}
+
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, int32_t* idx,
                              int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
-    unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
-    size_t lds = keys_lds_bytes(d.NB);
-    hipError_t e = allow_lds(d.D == 128 ? (const void*)score_topk_kernel<128> : (const void*)score_topk_kernel<64>, lds);
-    if (e != hipSuccess) return e;
-    if (d.D == 128)
-        hipLaunchKernelGGL((score_topk_kernel<128>), dim3(grid), dim3(kWaves * 64), lds, st, qp, kp, n_rows,
-                           d.Hq, d.G, d.NB, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
-    else if (d.D == 64)
-        hipLaunchKernelGGL((score_topk_kernel<64>), dim3(grid), dim3(kWaves * 64), lds, st, qp, kp, n_rows,
-                           d.Hq, d.G, d.NB, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (d.B * d.Hq > 65535) return hipErrorInvalidValue;
+    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, idx, cnt, scores_or_null, st);
+    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, idx, cnt, scores_or_null, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace spa
