@@ -35,8 +35,9 @@ __device__ __forceinline__ uint32_t rank_key(float s) {
     return u + 1u;                                            // max finite/inf key is 0xff800000, no wrap
 }
 
-__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
-    return __popcll(mask & ((1ull << lane) - 1ull));
+// number of set bits of `mask` that belong to lanes below the calling lane
+__device__ __forceinline__ int lanes_below(uint64_t mask, int /*lane*/) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 // keys[0 .. 64*ceil((i+1)/64)): rank_key of candidates, 0 for static blocks and padding.
@@ -132,9 +133,7 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // x = hi + lo with both parts bf16 (round to nearest even twice)
-__device__ __forceinline__ void split_bf16(const float* __restrict__ src, bf16x8& hi, bf16x8& lo) {
-    const float4 a = *reinterpret_cast<const float4*>(src);
-    const float4 b = *reinterpret_cast<const float4*>(src + 4);
+__device__ __forceinline__ void split_bf16(const float4 a, const float4 b, bf16x8& hi, bf16x8& lo) {
     f32x8 x = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
     hi = __builtin_convertvector(x, bf16x8);
     f32x8 back = __builtin_convertvector(hi, f32x8);
@@ -143,82 +142,54 @@ __device__ __forceinline__ void split_bf16(const float* __restrict__ src, bf16x8
 
 // Same selection as select_row, with the row's keys in registers: key[m] belongs to
 // block 64*m + lane (0 for static blocks, blocks beyond i, and unused chunks).
+// Threshold search of select_row with the row's keys in registers: key[m] belongs to block
+// 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks (0 never counts,
+// every trial value is >= 1).  Returns thr / need_eq: take key > thr, plus the first need_eq
+// keys equal to thr in block order.
 template <int MAXC>
-__device__ __forceinline__ void select_row_regs(const uint32_t (&key)[MAXC], int i, int ns, int nl, int k, int T,
-                                                int32_t* __restrict__ idx_row, int32_t* __restrict__ cnt_out) {
-    const int lane = threadIdx.x & 63;
-    const int n = i + 1;
-    const int chunks = (n + 63) >> 6;
-    const int lo = i - nl + 1;
-    int n_sink = ns < n ? ns : n;
-    int n_local = nl < n ? nl : n;
-    int first_local = lo > 0 ? lo : 0;
-    int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
-    const int n_cand = n - (n_sink + n_local - overlap);
-    const int kk = k < n_cand ? k : n_cand;
-
-    uint32_t thr = 0xffffffffu;
-    int need_eq = 0;
-    if (kk > 0) {
-        if (kk == n_cand) {
-            thr = 0u;
-        } else {
-            uint32_t p = 0u;
-            int c_at_p = n_cand;
-            for (int bit = 31; bit >= 0; --bit) {
-                const uint32_t trial = p | (1u << bit);
-                int c = 0;
+__device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC], int kk, int n_cand,
+                                                    uint32_t& thr, int& need_eq) {
+    thr = 0xffffffffu;
+    need_eq = 0;
+    if (kk <= 0) return;
+    if (kk == n_cand) { thr = 0u; return; }
+    uint32_t p = 0u;
+    int c_at_p = n_cand;
+#pragma nounroll
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = p | (1u << bit);
+        int c = 0;
 #pragma unroll
-                for (int m = 0; m < MAXC; ++m)
-                    if (m < chunks) c += __popcll(__ballot(key[m] >= trial));
-                if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
-            }
-            if (c_at_p == kk) {
-                thr = p - 1u;
-            } else {
-                int gt = 0;
-#pragma unroll
-                for (int m = 0; m < MAXC; ++m)
-                    if (m < chunks) gt += __popcll(__ballot(key[m] > p));
-                thr = p;
-                need_eq = kk - gt;
-            }
-        }
+        for (int m = 0; m < MAXC; ++m) c += __popcll(__ballot(key[m] >= trial));
+        if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
     }
-    int eq_seen = 0, out_pos = 0;
+    if (c_at_p == kk) { thr = p - 1u; return; }
+    int gt = 0;
 #pragma unroll
-    for (int m = 0; m < MAXC; ++m) {
-        if (m < chunks) {
-            const int j = (m << 6) + lane;
-            const uint32_t kv = key[m];
-            const bool is_static = j < n && (j < ns || j >= lo);
-            const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
-            const uint64_t eq_mask = __ballot(is_eq);
-            const bool take = is_static || (kv != 0u && kv > thr) ||
-                              (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
-            const uint64_t take_mask = __ballot(take);
-            if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = j;
-            eq_seen += __popcll(eq_mask);
-            out_pos += __popcll(take_mask);
-        }
-    }
-    for (int t = out_pos + lane; t < T; t += 64) idx_row[t] = -1;
-    if (lane == 0) *cnt_out = out_pos;
+    for (int m = 0; m < MAXC; ++m) gt += __popcll(__ballot(key[m] > p));
+    thr = p;
+    need_eq = kk - gt;
 }
 
 constexpr int kMfmaWaves = 8;
 
 template <int D, int R, int MAXC>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
-    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int ns, int nl, int k,
-    int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
+    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, int ns, int nl,
+    int k, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
+    float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
     extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
 
-    const int tile = gridDim.x - 1 - blockIdx.x;          // long rows first
+    // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
+    // (b, head, row tile) order so that one L2 serves few KV heads and their Kp stays resident.
+    const int nwg = gridDim.x;
+    int wg = blockIdx.x;
+    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
     const int i0 = tile * R;
-    const int bh = blockIdx.y;                            // b * Hq + h
+    const int bh = wg / n_tiles;                          // b * Hq + h
     const int b = bh / Hq, h = bh % Hq;
     const int Hkv = Hq / G;
     const float* qbase = qp + (int64_t)bh * NB * D;
@@ -235,18 +206,36 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         if (row > NB - 1) row = NB - 1;                   // rows past the end are computed but never used
         const float* src = qbase + (int64_t)row * D + 8 * half;
 #pragma unroll
-        for (int s = 0; s < DS; ++s) split_bf16(src + 16 * s, q_hi[s], q_lo[s]);
+        for (int s = 0; s < DS; ++s)
+            split_bf16(*reinterpret_cast<const float4*>(src + 16 * s), *reinterpret_cast<const float4*>(src + 16 * s + 4),
+                       q_hi[s], q_lo[s]);
     }
-    for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
+    // The Kp rows of a tile are fetched as one batch of 16-byte loads, and the next tile's batch
+    // is requested before the current one is consumed, so L2 latency is paid once per tile pair
+    // instead of once per 16-dim slice.
+    float4 kraw[2 * DS];
+    auto fetch_tile = [&](int jt, float4 (&dst)[2 * DS]) {
         const int j = 32 * jt + l32;
         const float* src = kbase + (int64_t)(j < NB ? j : NB - 1) * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            dst[2 * s] = *reinterpret_cast<const float4*>(src + 16 * s);
+            dst[2 * s + 1] = *reinterpret_cast<const float4*>(src + 16 * s + 4);
+        }
+    };
+    if (wave < n_jt) fetch_tile(wave, kraw);
+    for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
+        const int j = 32 * jt + l32;
+        float4 knext[2 * DS];
+        const bool more = jt + kMfmaWaves < n_jt;             // wave-uniform
+        if (more) fetch_tile(jt + kMfmaWaves, knext);
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             bf16x8 k_hi, k_lo;
-            split_bf16(src + 16 * s, k_hi, k_lo);
+            split_bf16(kraw[2 * s], kraw[2 * s + 1], k_hi, k_lo);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_lo[s], k_hi, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_lo, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_hi, acc, 0, 0, 0);
@@ -262,6 +251,10 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
                     scores_out[((int64_t)bh * NB + i) * NB + j] = j <= i ? sc : -INFINITY;
             }
         }
+        if (more) {
+#pragma unroll
+            for (int x = 0; x < 2 * DS; ++x) kraw[x] = knext[x];
+        }
     }
     if (scores_out != nullptr) {                          // key blocks past the last computed tile
         const int j_first = 32 * n_jt;
@@ -272,20 +265,51 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     __syncthreads();
 
     // ---- phase 2 ---------------------------------------------------------------------
+#pragma nounroll
     for (int r = wave; r < R; r += kMfmaWaves) {
         const int i = i0 + r;
         if (i >= NB) break;                               // wave-uniform
+        const int n = i + 1;
         const int lo = i - nl + 1;
+        const float* srow = S + r * LD;
         uint32_t key[MAXC];
 #pragma unroll
         for (int m = 0; m < MAXC; ++m) {
-            const int j = (m << 6) + lane;
-            uint32_t kv = 0u;
-            if (j <= i && !(j < ns || j >= lo)) kv = rank_key(S[r * LD + j]);
-            key[m] = kv;
+            const int j = (m << 6) + lane;                // < MAXC*64 <= LD: always inside the row
+            const uint32_t kv = rank_key(srow[j]);        // columns past the computed tiles hold junk: masked next
+            key[m] = (j <= i && !(j < ns || j >= lo)) ? kv : 0u;
         }
+        int n_sink = ns < n ? ns : n;
+        int n_local = nl < n ? nl : n;
+        int first_local = lo > 0 ? lo : 0;
+        int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
+        const int n_cand = n - (n_sink + n_local - overlap);
+        const int kk = k < n_cand ? k : n_cand;
+        uint32_t thr;
+        int need_eq;
+        find_threshold_regs<MAXC>(key, kk, n_cand, thr, need_eq);
+
+        // emit static U top-k in ascending block order (keys recomputed from LDS: a rolled loop)
         const int64_t row = (int64_t)bh * NB + i;
-        select_row_regs<MAXC>(key, i, ns, nl, k, T, idx + row * T, cnt + row);
+        int32_t* idx_row = idx + row * T;
+        const int chunks = (n + 63) >> 6;
+        int eq_seen = 0, out_pos = 0;
+#pragma nounroll
+        for (int m = 0; m < chunks; ++m) {
+            const int j = (m << 6) + lane;
+            const bool is_static = j < n && (j < ns || j >= lo);
+            const uint32_t kv = (j <= i && !is_static) ? rank_key(srow[j]) : 0u;
+            const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
+            const uint64_t eq_mask = __ballot(is_eq);
+            const bool take = is_static || (kv != 0u && kv > thr) ||
+                              (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
+            const uint64_t take_mask = __ballot(take);
+            if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = j;
+            eq_seen += __popcll(eq_mask);
+            out_pos += __popcll(take_mask);
+        }
+        for (int t = out_pos + lane; t < T; t += 64) idx_row[t] = -1;
+        if (lane == 0) cnt[row] = out_pos;
     }
 }
 
@@ -316,9 +340,10 @@ hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, int32_t*
     constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
     hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC>, lds);
     if (e != hipSuccess) return e;
-    dim3 grid((d.NB + R - 1) / R, d.B * d.Hq);
+    const int n_tiles = (d.NB + R - 1) / R;
+    dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
+                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
@@ -327,6 +352,7 @@ hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, int32_
                          float* scores_or_null, hipStream_t st) {
     // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
     if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, idx, cnt, scores_or_null, st);
+    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, idx, cnt, scores_or_null, st);
     if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, idx, cnt, scores_or_null, st);
     if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, idx, cnt, scores_or_null, st);
     return launch_mfma<D, 8, 64>(d, qp, kp, idx, cnt, scores_or_null, st);
@@ -334,7 +360,6 @@ hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, int32_
 
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, int32_t* idx,
                              int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    if (d.B * d.Hq > 65535) return hipErrorInvalidValue;
     if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, idx, cnt, scores_or_null, st);
     if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, idx, cnt, scores_or_null, st);
     return hipErrorInvalidValue;
