@@ -97,18 +97,21 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
     __shared__ __attribute__((aligned(1024))) uint16_t smem[2][2][TILE];   // [buffer][K | V^T]
 
-    // Workgroup -> (b, kv head, query block, head in group); each XCD (round-robin
-    // over workgroup ids) gets one contiguous slice of that order.
-    const int nwg = gridDim.x;
+    // Workgroup -> (b, kv head, query block, head in group).  Workgroup ids go round robin over
+    // the 8 XCDs.  In time, the whole chip works through one KV head after the other, so that the
+    // K and V^T of the current head (tens of MB) stay in the memory-side cache; in space, each XCD
+    // takes a contiguous range of that head's query blocks with all G heads of the group, which
+    // share most of their key blocks in that XCD's L2.
+    const int per_head = NB * G;
     int wg = blockIdx.x;
-    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
-    const int g = wg % G;
-    int rest = wg / G;
-    const int i = rest % NB;
-    rest /= NB;
+    const int head_slot = wg / per_head;                  // b * Hkv + kv head
+    int local = wg % per_head;
+    if ((per_head & 7) == 0) local = (local & 7) * (per_head >> 3) + (local >> 3);
+    const int g = local % G;
+    const int i = local / G;
     const int Hkv = Hq / G;
-    const int kvh = rest % Hkv;
-    const int b = rest / Hkv;
+    const int kvh = head_slot % Hkv;
+    const int b = head_slot / Hkv;
     const int h = kvh * G + g;
 
     const int tid = threadIdx.x;
