@@ -141,7 +141,7 @@ def main():
                        "bytes": w.select_bytes},
         "roofline": {"bound": "mfma", "kernel": "attn_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": read_traffic_note("attn_kernel")},
+                     "traffic": read_traffic_note("attn_kernel"), "traffic_unit": "bytes/launch"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, idx.cpu(), cnt.cpu(), args.cpu_rows)
