@@ -267,6 +267,31 @@ def test_fused_sampled_16k_workload(spa, oracle):
     _sampled_workload_check(spa, oracle, 1, n_random=6)
 
 
+def test_fused_sampled_32k_workload(spa, oracle):
+    _sampled_workload_check(spa, oracle, 2, n_random=4)
+
+
+def test_fused_sampled_256k_workload(spa, oracle):
+    """262144 tokens, 40/8 heads (GQA 5:1), heavy-tailed keys: 2048 blocks per row."""
+    _sampled_workload_check(spa, oracle, 4, n_random=2)
+
+
+def test_select_max_block_count(spa, oracle):
+    """4096 blocks per row (the library limit) through the full select call."""
+    NB, Bs, D = 4096, 64, 64
+    q, kk, _ = _qkv(1, 2, 1, NB * Bs, D, 77)
+    idx, cnt, sp = spa.select(q.cuda(), kk.cuda(), Bs, 2, 3, 50, return_scores=True)
+    o_idx, o_cnt, o_sp, _, _ = oracle.select(q, kk, Bs, 2, 3, 50)
+    sp = sp.cpu()
+    rows = [0, 1, 54, 55, 56, 63, 64, 1000, 2047, 2048, 4095]
+    for i in rows:
+        torch.testing.assert_close(sp[0, :, i, : i + 1], o_sp[0, :, i, : i + 1], rtol=1e-4, atol=1e-5)
+        assert torch.isneginf(sp[0, :, i, i + 1:]).all()
+    g_idx, g_cnt = oracle.topk(sp, 2, 3, 50)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    assert torch.equal(cnt.cpu(), o_cnt)
+
+
 def test_fused_sampled_128k_headline_workload(spa, oracle):
     """The benchmark's own configuration (131072 tokens, 32/8 heads, block 128)."""
     _sampled_workload_check(spa, oracle, 3, n_random=4)
