@@ -146,6 +146,17 @@ __device__ __forceinline__ void split_bf16(const float4 a, const float4 b, bf16x
 // 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks (0 never counts,
 // every trial value is >= 1).  Returns thr / need_eq: take key > thr, plus the first need_eq
 // keys equal to thr in block order.
+// sum of v over the 64 lanes (DPP row reductions + row broadcasts), returned wave-uniform
+__device__ __forceinline__ int wave_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);   // row_mirror: every lane = its row's sum
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, true);   // row_bcast31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
 template <int MAXC>
 __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC], int kk, int n_cand,
                                                     uint32_t& thr, int& need_eq) {
@@ -158,15 +169,19 @@ __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC],
 #pragma nounroll
     for (int bit = 31; bit >= 0; --bit) {
         const uint32_t trial = p | (1u << bit);
-        int c = 0;
+        // per-lane counts on the vector ALU, one cross-lane sum per step: the scalar unit is
+        // shared by the whole CU and a ballot + popcount per chunk saturates it
+        int cl = 0;
 #pragma unroll
-        for (int m = 0; m < MAXC; ++m) c += __popcll(__ballot(key[m] >= trial));
+        for (int m = 0; m < MAXC; ++m) cl += (key[m] >= trial) ? 1 : 0;
+        const int c = wave_sum(cl);
         if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
     }
     if (c_at_p == kk) { thr = p - 1u; return; }
-    int gt = 0;
+    int gl = 0;
 #pragma unroll
-    for (int m = 0; m < MAXC; ++m) gt += __popcll(__ballot(key[m] > p));
+    for (int m = 0; m < MAXC; ++m) gl += (key[m] > p) ? 1 : 0;
+    const int gt = wave_sum(gl);
     thr = p;
     need_eq = kk - gt;
 }
