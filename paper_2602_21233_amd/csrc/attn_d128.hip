@@ -31,6 +31,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -51,17 +52,18 @@ __device__ __forceinline__ float other_half(float x) {
     return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): the wave's 64
-// lanes fill 1 KB starting at LDS byte address lds_addr, lane l from sbase + voff(l).  Written as
+// lanes fill 1 KB starting at LDS byte address lds_addr + IMM, lane l from sbase + voff(l).  Written as
 // inline assembly on purpose: the compiler models the builtin form as an access whose completion
 // order is unknown, and from then on turns every wait for an LDS read into a wait for all of
 // them, which defeats the read-ahead in the pipeline step.  The kernel waits for these loads
 // itself (s_waitcnt vmcnt(0) before the barrier that publishes a sub-tile).
 #pragma clang diagnostic ignored "-Winline-asm"
+template <int IMM>
 __device__ __forceinline__ void lds_dma16(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+                 : "s"(lds_addr), "v"(voff), "s"(sbase), "i"(IMM)
+                 : "memory", "m0", "scc");
 }
 __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(size_t)(lds_void*)p; }
 __device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
@@ -102,11 +104,22 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
 
 // ---------------------------------------------------------------------------
 // Instruction order inside a pipeline step is written out by hand: every group between two
-// fences holds one MFMA, the LDS read of an operand needed three MFMAs later and a handful of
-// softmax VALU instructions, and the scheduler may not move anything across a fence.  Left to
-// itself the compiler (register pressure is high) sinks each LDS read to just before the MFMA
-// that uses it and clusters the VALU work, so the wave stalls on the LDS latency once per MFMA.
+// fences holds one MFMA, the LDS read of an operand needed three MFMAs later and a few softmax
+// VALU instructions, and the scheduler may not move anything across a fence.  Left to itself the
+// compiler (register pressure is high) sinks each LDS read to just before the MFMA that uses it
+// and clusters the VALU work, so the wave stalls on the LDS latency once per MFMA.
 #define SPA_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int N>
+using IC = std::integral_constant<int, N>;
+// f(IC<0>{}), ..., f(IC<N-1>{})
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(IC<N - 1>{});
+    }
+}
 
 template <int BS>
 __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
@@ -118,11 +131,10 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
     constexpr int TILE_B = TILE * 2;    // bytes of a sub-tile
-    // K sub-tile n lives in buffer n % 3, V^T sub-tile n in buffer n % 2.  Three K buffers make the
-    // buffer index follow the period-3 rotation of the logit registers below, so every K read is a
-    // per-lane base register plus an immediate offset.
-    __shared__ __attribute__((aligned(1024))) uint16_t smemK[3][TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][TILE];
+    constexpr int CHUNK_B = 32 * D * 2; // bytes of a 32-key chunk of a K sub-tile
+    constexpr int DTILE_B = 32 * KT * 2;  // bytes of 32 d rows of a V^T sub-tile
+    __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][TILE];   // K sub-tile t in buffer t % 2
+    __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][TILE];   // V^T likewise
 
     // Workgroup -> (b, kv head, query block, head in group).  Workgroup ids go round robin over
     // the 8 XCDs.  In time, the whole chip works through one KV head after the other, so that the
@@ -168,25 +180,33 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         v_offb[x] = 2u * (uint32_t)(vrow * BS + (((lane & 7) ^ swz_v(vrow)) << 3));
     }
     // K and V^T sub-tiles are staged separately: K runs one sub-tile ahead of V^T because the
-    // logits of sub-tile n+1 are computed while the softmax of sub-tile n is in progress.
-    auto issue_k = [&](int st, int blk, int buf) {
+    // logits are produced two 32-key chunks before the second product consumes them.
+    const uint32_t k_dst = lds_address(&smemK[0][0]) + wave * LPW * 1024;   // this wave's 1-KB slots
+    const uint32_t v_dst = lds_address(&smemV[0][0]) + wave * LPW * 1024;
+    auto issue_k = [&](auto buf_tag, int st, int blk) {
+        constexpr int BUF = decltype(buf_tag)::value;
         const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + (st % NSUB) * KT) * ks.t);
-#pragma unroll
-        for (int x = 0; x < LPW; ++x) lds_dma16(lds_address(&smemK[buf][(wave * LPW + x) * 512]), k_offb[x], kt);
+        static_for<LPW>([&](auto x_tag) {
+            constexpr int X = decltype(x_tag)::value;
+            lds_dma16<BUF * TILE_B + X * 1024>(k_dst, k_offb[X], kt);
+        });
     };
-    auto issue_v = [&](int st, int blk) {
+    auto issue_v = [&](auto buf_tag, int st, int blk) {
+        constexpr int BUF = decltype(buf_tag)::value;
         const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + (st % NSUB) * KT);
-#pragma unroll
-        for (int x = 0; x < LPW; ++x) lds_dma16(lds_address(&smemV[st & 1][(wave * LPW + x) * 512]), v_offb[x], vtt);
+        static_for<LPW>([&](auto x_tag) {
+            constexpr int X = decltype(x_tag)::value;
+            lds_dma16<BUF * TILE_B + X * 1024>(v_dst, v_offb[X], vtt);
+        });
     };
     auto blk_of = [&](int st) {        // key block of sub-tile st (clamped: never read past the list)
         const int e = st / NSUB;
         return sel[e < n_sel ? e : n_sel - 1];
     };
 
-    issue_k(0, sel[0], 0);
-    issue_v(0, sel[0]);
-    if (n_st > 1) issue_k(1, blk_of(1), 1);
+    issue_k(IC<0>{}, 0, sel[0]);
+    issue_v(IC<0>{}, 0, sel[0]);
+    if (n_st > 1) issue_k(IC<1>{}, 1, blk_of(1));
 
     // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
     bf16x8 qf[8];
@@ -209,197 +229,198 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     }
     const char* const ldsK = reinterpret_cast<const char*>(&smemK[0][0]);
     const char* const ldsV = reinterpret_cast<const char*>(&smemV[0][0]);
+    auto lds16 = [](const char* p) { return *reinterpret_cast<const bf16x8*>(p); };
 
     f32x16 oacc[4];
 #pragma unroll
     for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
-    float m_run = -INFINITY;     // reference maximum (raw logits) used for the exponentials
-    float l_run = 0.f;           // this lane's half of the running denominator
+    // Weights are w = 2^(x*c - mcb) with mcb = m_run*c + 7: m_run is the reference maximum (raw
+    // logit) and the 2^-7 bias puts "w >= 2", i.e. "the logit outgrew the reference by 2^8", on
+    // the top exponent bit of the bf16 weight, where one OR over the packed weights finds it.
+    float m_run = -INFINITY;
+    float mcb = 0.f;
+    float l_run = 0.f;           // this lane's half of the running denominator (sum of bf16 weights)
     const float c = scale * 1.44269504088896340736f;
     const int q_in_blk = 32 * wave + l32;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-    // The pipeline step.  Works on 32-key chunks: while the VALU turns the logits of the current
-    // chunk (s_cur) into probabilities and the MFMA pipe accumulates them into O^T, the same MFMA
-    // pipe also produces the logits of a later chunk (s_nxt, the same chunk position of the next
-    // sub-tile), so MFMA and VALU work always come from independent dependency chains.
-    //   KB: K buffer the produced chunk is read from; KC: chunk index (0/1) of both the produced
-    //   and the current chunk inside their 64-key sub-tiles; vb: byte offset of the V^T buffer.
-    //   f0..f3: rotating operand registers; on entry f0..f2 hold K slices 0..2 of the produced
-    //   chunk, on exit (KC == 0) those of the next chunk of the same sub-tile.
-    auto step = [&](auto kb_tag, auto kc_tag, f32x16& s_cur, f32x16& s_nxt, int vb, bool diag, int sub,
-                    bf16x8& f0, bf16x8& f1, bf16x8& f2, bf16x8& f3) {
-        constexpr int KB = decltype(kb_tag)::value, KC = decltype(kc_tag)::value;
-        constexpr int KOFF = KB * TILE_B + KC * 32 * D * 2;
-        auto ldk = [&](int s) { return *reinterpret_cast<const bf16x8*>(ldsK + KOFF + kofs[s]); };
-        const char* const v0 = ldsV + vb + vofs[2 * KC];
-        const char* const v1 = ldsV + vb + vofs[2 * KC + 1];
-        auto ldv = [&](const char* base, int dc) { return *reinterpret_cast<const bf16x8*>(base + dc * 32 * KT * 2); };
-        // causal mask on the diagonal block: register r of a chunk holds key
-        // 32*chunk + 16*(r>>3) + 8*half + (r&7) of the sub-tile
-        if (diag && KT * sub + 32 * KC + 31 > 32 * wave) {
+    // causal mask inside the diagonal block: register r of a chunk holds key
+    // 64*sub + 32*kc + 16*(r>>3) + 8*half + (r&7) of the block
+    auto mask_diag = [&](f32x16& s, int sub, int kc) {
+        if (KT * sub + 32 * kc + 31 > 32 * wave) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int kpos = KT * sub + 32 * KC + 16 * (r >> 3) + 8 * half + (r & 7);
-                if (kpos > q_in_blk) s_cur[r] = -INFINITY;
+                const int kpos = KT * sub + 32 * kc + 16 * (r >> 3) + 8 * half + (r & 7);
+                if (kpos > q_in_blk) s[r] = -INFINITY;
             }
         }
+    };
+    auto weights = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        f32x8 e0, e1;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
+            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
+        }
+        p0 = __builtin_convertvector(e0, bf16x8);
+        p1 = __builtin_convertvector(e1, bf16x8);
+        lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
+        }
+    };
+    // Slow path: raise the reference maximum to cover the chunk `s`, rescale what has been
+    // accumulated and recompute the chunk's weights.  Rare after the first chunk; wave-uniform.
+    // A lane whose chunk is fully masked keeps its reference (alpha = 1).
+    auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+        mx = fmaxf(mx, other_half(mx));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        m_run = m_new;
+        mcb = m_new * c + 7.0f;
+        l_run *= alpha;
+#pragma unroll
+        for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
+        weights(s, p0, p1, lsum);
+    };
+
+    // The pipeline step n (chunk n = 32 keys) runs three independent chains side by side:
+    //   MFMA   s_nxt = logits of chunk n+2 (same chunk position KC of the next sub-tile, K buffer KB)
+    //   VALU   pn    = weights of chunk n+1 from its logits s_cur (produced by step n-1)
+    //   MFMA   O^T  += V^T(chunk n, V buffer VB) pc^T, pc = weights of chunk n (made by step n-1)
+    // f[0..3]: rotating MFMA A operands, read from LDS three MFMAs ahead of their use.  The 16
+    // operands of a step in MFMA order are K slice 0, V^T (keys 0-15, d tile 0), K slice 1,
+    // V^T (0-15, 1), ..., K slice 7, V^T (16-31, 3).  On entry f[0..2] hold operands 0..2; a
+    // KC = 0 step leaves the first three operands of the KC = 1 step behind.
+    auto step = [&](auto kb_tag, auto vb_tag, auto kc_tag, const f32x16& s_cur, f32x16& s_nxt, const bf16x8& pc0,
+                    const bf16x8& pc1, bf16x8& pn0, bf16x8& pn1, bf16x8 (&f)[4]) {
+        constexpr int KB = decltype(kb_tag)::value, VB = decltype(vb_tag)::value, KC = decltype(kc_tag)::value;
+        const char* const kbase = ldsK + KB * TILE_B + KC * CHUNK_B;
+        const char* const vbase = ldsV + VB * TILE_B;
+        auto operand = [&](auto j_tag) {            // operand j of this step (j < 16) or of the next one
+            constexpr int J = decltype(j_tag)::value;
+            constexpr int j = J % 16;
+            constexpr int kc = KC + J / 16;         // only used with J >= 16 when KC == 0
+            const char* const kb2 = ldsK + KB * TILE_B + kc * CHUNK_B;
+            if constexpr (j % 2 == 0) return lds16(kb2 + kofs[j / 2]);
+            else return lds16(vbase + vofs[2 * kc + j / 8] + ((j / 2) % 4) * DTILE_B);
+        };
+        (void)kbase;
         f32x16 zero;
 #pragma unroll
         for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-        SPA_FENCE();
-        // ---- logits of the look-ahead chunk, row maximum of the current chunk ---------------
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, qf[0], zero, 0, 0, 0);
-        f3 = ldk(3);
-        float mx = fmaxf(s_cur[0], s_cur[1]);
-        mx = fmaxf(fmaxf(mx, s_cur[2]), s_cur[3]);
-        mx = fmaxf(fmaxf(mx, s_cur[4]), s_cur[5]);
-        mx = fmaxf(fmaxf(mx, s_cur[6]), s_cur[7]);
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, qf[1], s_nxt, 0, 0, 0);
-        f0 = ldk(4);
-        mx = fmaxf(fmaxf(mx, s_cur[8]), s_cur[9]);
-        mx = fmaxf(fmaxf(mx, s_cur[10]), s_cur[11]);
-        mx = fmaxf(fmaxf(mx, s_cur[12]), s_cur[13]);
-        mx = fmaxf(fmaxf(mx, s_cur[14]), s_cur[15]);
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, qf[2], s_nxt, 0, 0, 0);
-        f1 = ldk(5);
-        // Raise the reference maximum only when some row outgrew it by more than 2^8 (exp2
-        // domain).  The test uses each lane's own half of the keys; the halves are combined only
-        // when it fires.  Always true on the first chunk; a fully masked half (mx = -inf) never
-        // triggers it and contributes exact zeros.
-        const bool grow = (mx - m_run) * c > 8.0f;
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f3, qf[3], s_nxt, 0, 0, 0);
-        f2 = ldk(6);
-        if (__any(grow)) {
-            mx = fmaxf(mx, other_half(mx));
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-            m_run = m_new;
-            l_run *= alpha;
+        f32x8 e;
+        float l_new = l_run;
+        uint32_t ovf = 0u;
+        auto group = [&](auto g_tag) {
+            constexpr int g = decltype(g_tag)::value;
+            if constexpr (g % 2 == 0) {
+                if constexpr (g == 0) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], zero, 0, 0, 0);
+                else s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], s_nxt, 0, 0, 0);
+            } else {
+                constexpr int dc = (g / 2) % 4;
+                if constexpr (g < 8) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc0, oacc[dc], 0, 0, 0);
+                else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc1, oacc[dc], 0, 0, 0);
+            }
+            if constexpr (g + 3 < 16 || KC == 0) f[(g + 3) % 4] = operand(IC<g + 3>{});
+            constexpr int hb = (g / 8) * 8;          // which half of the chunk's 16 logits
+            constexpr int gg = g % 8;
+            if constexpr (gg < 2) {
 #pragma unroll
-            for (int dc = 0; dc < 4; ++dc)
+                for (int x = 4 * gg; x < 4 * gg + 4; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
+            } else if constexpr (gg < 6) {
+                e[2 * (gg - 2)] = __builtin_amdgcn_exp2f(e[2 * (gg - 2)]);
+                e[2 * (gg - 2) + 1] = __builtin_amdgcn_exp2f(e[2 * (gg - 2) + 1]);
+            } else if constexpr (gg == 6) {
+                if constexpr (g < 8) pn0 = __builtin_convertvector(e, bf16x8);
+                else pn1 = __builtin_convertvector(e, bf16x8);
+            } else {
+                const bf16x8 pw = g < 8 ? pn0 : pn1;
+                const u32x4 bits = __builtin_bit_cast(u32x4, pw);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
+                for (int x = 0; x < 4; ++x)
+                    l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
+                ovf |= bits[0] | bits[1] | bits[2] | bits[3];
+                if constexpr (g == 15) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
+            }
+            SPA_FENCE();
+        };
+        SPA_FENCE();
+        group(IC<0>{}); group(IC<1>{}); group(IC<2>{}); group(IC<3>{});
+        group(IC<4>{}); group(IC<5>{}); group(IC<6>{}); group(IC<7>{});
+        group(IC<8>{}); group(IC<9>{}); group(IC<10>{}); group(IC<11>{});
+        group(IC<12>{}); group(IC<13>{}); group(IC<14>{}); group(IC<15>{});
+        // some weight >= 2 (or inf/NaN): the chunk outgrew the reference maximum
+        if (__any((ovf & 0x40004000u) != 0u)) {
+            float lsum;
+            raise_reference(s_cur, pn0, pn1, lsum);
+            l_new = l_run + lsum;
         }
-        SPA_FENCE();
-        // ---- probabilities of the first 16 keys --------------------------------------------
-        const float mc = m_run * c;
-        f32x8 e0, e1;
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, qf[4], s_nxt, 0, 0, 0);
-        f3 = ldk(7);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) e0[x] = fmaf(s_cur[x], c, -mc);
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, qf[5], s_nxt, 0, 0, 0);
-        f0 = ldv(v0, 0);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) e0[x] = __builtin_amdgcn_exp2f(e0[x]);
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, qf[6], s_nxt, 0, 0, 0);
-        f1 = ldv(v0, 1);
-#pragma unroll
-        for (int x = 4; x < 8; ++x) e0[x] = __builtin_amdgcn_exp2f(e0[x]);
-        SPA_FENCE();
-        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f3, qf[7], s_nxt, 0, 0, 0);
-        f2 = ldv(v0, 2);
-        const bf16x8 p0 = __builtin_convertvector(e0, bf16x8);
-        // the denominator sums the bf16-rounded weights, exactly what the second product uses
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-            l_run = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, l_run, false);
-        SPA_FENCE();
-        // ---- O^T += V^T P^T, probabilities of the second 16 keys ---------------------------
-        oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, p0, oacc[0], 0, 0, 0);
-        f3 = ldv(v0, 3);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) e1[x] = fmaf(s_cur[8 + x], c, -mc);
-        SPA_FENCE();
-        oacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, p0, oacc[1], 0, 0, 0);
-        f0 = ldv(v1, 0);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) e1[x] = __builtin_amdgcn_exp2f(e1[x]);
-        SPA_FENCE();
-        oacc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, p0, oacc[2], 0, 0, 0);
-        f1 = ldv(v1, 1);
-#pragma unroll
-        for (int x = 4; x < 8; ++x) e1[x] = __builtin_amdgcn_exp2f(e1[x]);
-        SPA_FENCE();
-        oacc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f3, p0, oacc[3], 0, 0, 0);
-        f2 = ldv(v1, 2);
-        const bf16x8 p1 = __builtin_convertvector(e1, bf16x8);
-#pragma unroll
-        for (int x = 0; x < 4; ++x)
-            l_run = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, l_run, false);
-        SPA_FENCE();
-        oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, p1, oacc[0], 0, 0, 0);
-        f3 = ldv(v1, 3);
-        SPA_FENCE();
-        oacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, p1, oacc[1], 0, 0, 0);
-        if constexpr (KC == 0) f0 = *reinterpret_cast<const bf16x8*>(ldsK + KOFF + 32 * D * 2 + kofs[0]);
-        SPA_FENCE();
-        oacc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, p1, oacc[2], 0, 0, 0);
-        if constexpr (KC == 0) f1 = *reinterpret_cast<const bf16x8*>(ldsK + KOFF + 32 * D * 2 + kofs[1]);
-        SPA_FENCE();
-        oacc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f3, p1, oacc[3], 0, 0, 0);
-        if constexpr (KC == 0) f2 = *reinterpret_cast<const bf16x8*>(ldsK + KOFF + 32 * D * 2 + kofs[2]);
-        SPA_FENCE();
+        l_run = l_new;
     };
 
-    // ---- prologue: logits of the two chunks of sub-tile 0 ------------------------------
+    // ---- prologue: logits of the two chunks of sub-tile 0, weights of chunk 0 -----------
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
     __syncthreads();
-    f32x16 s0, s1, s2;                             // logits: two chunks waiting/current + one being produced
+    f32x16 sA, sB;                                 // logits of even / odd chunks
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { sA[r] = 0.f; sB[r] = 0.f; }
 #pragma unroll
     for (int sidx = 0; sidx < 8; ++sidx) {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(ldsK + kofs[sidx]), qf[sidx], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(ldsK + 32 * D * 2 + kofs[sidx]), qf[sidx], s1, 0, 0, 0);
+        sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + kofs[sidx]), qf[sidx], sA, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + CHUNK_B + kofs[sidx]), qf[sidx], sB, 0, 0, 0);
     }
-    int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles n+1 and n+2
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
+    bf16x8 pA0, pA1, pB0, pB1;                     // weights of even / odd chunks
+    {
+        if (n_st <= NSUB) mask_diag(sA, 0, 0);     // the only block is the diagonal one
+        float lsum;
+        raise_reference(sA, pA0, pA1, lsum);
+        l_run = lsum;
+    }
+    int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles t+1 and t+2
 
-    // One 64-key sub-tile n (R = n % 3): its two chunks are current (a = chunk 0, b = chunk 1, both
-    // computed during sub-tile n-1); the logits of sub-tile n+1 are produced into cnext and then a.
-    // Only K(n+1) and V^T(n) are read; K(n+2) goes to the buffer that K(n-1) left two barriers ago.
-    auto sub_tile = [&](auto r_tag, int n, f32x16& a, f32x16& b, f32x16& cnext) {
-        constexpr int R = decltype(r_tag)::value;
-        using KRD = std::integral_constant<int, (R + 1) % 3>;
-        // K(n+1) and V(n) have been requested; make them visible and retire the previous
-        // sub-tile's readers of the V buffer refilled below.
+    // One 64-key sub-tile t = steps 2t and 2t+1.  Reads K(t+1) (look-ahead logits) and V^T(t).
+    auto sub_tile = [&](auto par_tag, int t) {
+        constexpr int PAR = decltype(par_tag)::value;      // t % 2
+        using KB = IC<1 - PAR>;
+        using VB = IC<PAR>;
+        // K(t+1) and V(t) have been requested; make them visible and retire the previous
+        // sub-tile's readers of the buffers refilled below.
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        bf16x8 f0 = *reinterpret_cast<const bf16x8*>(ldsK + KRD::value * TILE_B + kofs[0]);
-        bf16x8 f1 = *reinterpret_cast<const bf16x8*>(ldsK + KRD::value * TILE_B + kofs[1]);
-        bf16x8 f2 = *reinterpret_cast<const bf16x8*>(ldsK + KRD::value * TILE_B + kofs[2]);
-        bf16x8 f3;
-        if (n + 2 < n_st) issue_k(n + 2, blk2, (R + 2) % 3);
-        if (n + 1 < n_st) issue_v(n + 1, blk1);
+        bf16x8 f[4];
+        f[0] = lds16(ldsK + KB::value * TILE_B + kofs[0]);
+        f[1] = lds16(ldsV + VB::value * TILE_B + vofs[0]);
+        f[2] = lds16(ldsK + KB::value * TILE_B + kofs[1]);
+        if (t + 2 < n_st) issue_k(IC<PAR>{}, t + 2, blk2);
+        if (t + 1 < n_st) issue_v(IC<1 - PAR>{}, t + 1, blk1);
         blk1 = blk2;
-        blk2 = blk_of(n + 3);
-        const int vb = (n & 1) * TILE_B;
-        const bool diag = n >= n_st - NSUB;           // the diagonal block is always the last of the list
-        const int sub = n % NSUB;
-        // on the last sub-tile the look-ahead reads a stale K buffer and its result is dropped
-        step(KRD{}, I0{}, a, cnext, vb, diag, sub, f0, f1, f2, f3);
-        step(KRD{}, I1{}, b, a, vb, diag, sub, f0, f1, f2, f3);
+        blk2 = blk_of(t + 3);
+        // logits about to be turned into weights: chunk 1 of this sub-tile, then chunk 0 of the next
+        if (t >= n_st - NSUB) mask_diag(sB, t % NSUB, 1);          // the diagonal block is the last of the list
+        step(KB{}, VB{}, IC<0>{}, sB, sA, pA0, pA1, pB0, pB1, f);
+        if (t + 1 >= n_st) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sA[r] = -INFINITY;        // past the end: look-ahead of a stale buffer
+        } else if (t + 1 >= n_st - NSUB) {
+            mask_diag(sA, (t + 1) % NSUB, 0);
+        }
+        step(KB{}, VB{}, IC<1>{}, sA, sB, pB0, pB1, pA0, pA1, f);
     };
-    using R0 = std::integral_constant<int, 0>;
-    using R1 = std::integral_constant<int, 1>;
-    using R2 = std::integral_constant<int, 2>;
-    for (int n = 0;;) {                               // register roles rotate with period 3
-        sub_tile(R0{}, n, s0, s1, s2);
-        if (++n == n_st) break;
-        sub_tile(R1{}, n, s2, s0, s1);
-        if (++n == n_st) break;
-        sub_tile(R2{}, n, s1, s2, s0);
-        if (++n == n_st) break;
+    for (int t = 0;;) {
+        sub_tile(IC<0>{}, t);
+        if (++t == n_st) break;
+        sub_tile(IC<1>{}, t);
+        if (++t == n_st) break;
     }
 
     // ---- epilogue ----------------------------------------------------------------
@@ -416,7 +437,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
             *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
         }
     if (lse != nullptr && half == 0)
-        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = m_run * scale + __logf(l_tot);
+        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
 }
 
 template <int BS>
