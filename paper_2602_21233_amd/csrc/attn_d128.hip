@@ -110,6 +110,34 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
 // and clusters the VALU work, so the wave stalls on the LDS latency once per MFMA.
 #define SPA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Query-block ranges of the 8 XCDs: XCD x owns blocks first[x] .. first[x+1]-1 of every head;
+// seq_len = workgroups per (head, XCD) in the grid = the longest range times G.
+struct XcdSplit {
+    int first[9];
+    int seq_len;
+};
+
+// Ranges with equal work; row i visits min(i + 1, T) key blocks.
+XcdSplit balanced_split(int NB, int T, int G) {
+    XcdSplit sp;
+    int64_t total = 0;
+    for (int i = 0; i < NB; ++i) total += (i + 1 < T ? i + 1 : T);
+    int64_t acc = 0;
+    int x = 1;
+    sp.first[0] = 0;
+    for (int i = 0; i < NB && x < 8; ++i) {
+        acc += (i + 1 < T ? i + 1 : T);
+        while (x < 8 && acc * 8 >= total * x) sp.first[x++] = i + 1;
+    }
+    while (x <= 8) sp.first[x++] = NB;
+    sp.first[8] = NB;
+    int longest = 0;
+    for (int y = 0; y < 8; ++y)
+        if (sp.first[y + 1] - sp.first[y] > longest) longest = sp.first[y + 1] - sp.first[y];
+    sp.seq_len = longest * G;
+    return sp;
+}
+
 template <int N>
 using IC = std::integral_constant<int, N>;
 // f(IC<0>{}), ..., f(IC<N-1>{})
@@ -126,7 +154,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale) {
+    float scale, XcdSplit split) {
     constexpr int NW = BS / 32;         // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
@@ -140,14 +168,16 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     // the 8 XCDs.  In time, the whole chip works through one KV head after the other, so that the
     // K and V^T of the current head (tens of MB) stay in the memory-side cache; in space, each XCD
     // takes a contiguous range of that head's query blocks with all G heads of the group, which
-    // share most of their key blocks in that XCD's L2.
-    const int per_head = NB * G;
-    int wg = blockIdx.x;
-    const int head_slot = wg / per_head;                  // b * Hkv + kv head
-    int local = wg % per_head;
-    if ((per_head & 7) == 0) local = (local & 7) * (per_head >> 3) + (local >> 3);
-    const int g = local % G;
-    const int i = local / G;
+    // share most of their key blocks in that XCD's L2.  The ranges hold equal numbers of visited
+    // block pairs, not of rows (the first rows of a sequence are short), so the XCDs stay in step;
+    // an XCD whose range has fewer rows than the longest one lets the surplus workgroups exit.
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int head_slot = slot / split.seq_len;           // b * Hkv + kv head
+    const int within = slot % split.seq_len;
+    const int i = split.first[xcd] + within / G;
+    if (i >= split.first[xcd + 1]) return;                // the whole workgroup leaves, before any barrier
+    const int g = within % G;
     const int Hkv = Hq / G;
     const int kvh = head_slot % Hkv;
     const int b = head_slot / Hkv;
@@ -448,10 +478,12 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                        (const uint16_t*)v, vs, d.Hkv, d.NB, (uint16_t*)vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    int64_t nwg = (int64_t)d.B * d.Hq * d.NB;
+    const XcdSplit split = balanced_split(d.NB, d.T, d.G);
+    const int64_t nwg = 8ll * split.seq_len * d.B * d.Hkv;
+    if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale);
+                       d.G, d.NB, d.T, d.S, d.scale, split);
     return hipGetLastError();
 }
 
