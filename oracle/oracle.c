@@ -14,7 +14,10 @@
  *   - the dynamic part = the uniform top-k budget per query position that
  *     Sec. 4.1.2 describes as the common baseline (Fig. "Stem" (a)),
  *   - the union of both (the "hybrid of static patterns and dynamic token
- *     selection" of the abstract).
+ *     selection" of the abstract),
+ *   - optionally the position-dependent budget of Stem's Token Position-Decay
+ *     (Sec. 4.1.2, Fig. "Stem" (b)) in place of the uniform one; the schedule
+ *     itself is an input, the paper prints none.
  * The paper gives no formula for any step.  The concrete readings taken here:
  * block granularity, arithmetic-mean pooling, raw pooled logit as the ranking
  * score, top-k drawn from the causal candidates that are not already static,
@@ -96,11 +99,18 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
 /* Steps 3+4 (top-k and merge with the static pattern) for every query block:
  *   Static_i = {j < ns, j <= i} U {max(0,i-nl+1) .. i}
  *   C_i      = {0..i} \ Static_i
- *   TopK_i   = the min(k,|C_i|) best-ranked members of C_i
+ *   TopK_i   = the min(k_i,|C_i|) best-ranked members of C_i
  *   Sel_i    = Static_i U TopK_i, written ascending, padded with -1.
- * sp: [n_rows_total = B*Hq, NB, NB] fp32; idx: [B*Hq, NB, T]; cnt: [B*Hq, NB]. */
+ * Budget k_i: the uniform budget k for every query block (the baseline of
+ * Sec. 4.1.2, Fig. "Stem" (a)) when k_row is NULL; otherwise the position
+ * dependent budget of Token Position-Decay (Sec. 4.1.2, Fig. "Stem" (b)):
+ * k_i = k_row[i] clamped to [0, k], one value per query block, shared by all
+ * heads.  The paper prints no decay schedule, so the schedule is an input.
+ * sp: [n_rows_total = B*Hq, NB, NB] fp32; idx: [B*Hq, NB, T]; cnt: [B*Hq, NB];
+ * T = min(NB, ns+nl+k) also with a schedule (k is its stated maximum). */
 int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
-                int64_t nl, int64_t k, int32_t *idx, int32_t *cnt) {
+                int64_t nl, int64_t k, const int32_t *k_row, int32_t *idx,
+                int32_t *cnt) {
     if (ns < 0 || nl < 1 || k < 0) return -1;
     int64_t T = ns + nl + k;
     if (T > NB) T = NB;
@@ -122,7 +132,13 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
                 int is_local = j >= i - nl + 1;
                 sel[j] = (unsigned char)(is_sink || is_local);
             }
-            for (int64_t pick = 0; pick < k; ++pick) {
+            int64_t k_i = k;
+            if (k_row) {
+                k_i = k_row[i];
+                if (k_i < 0) k_i = 0;
+                if (k_i > k) k_i = k;
+            }
+            for (int64_t pick = 0; pick < k_i; ++pick) {
                 int64_t best = -1;
                 for (int64_t j = 0; j <= i; ++j) {
                     if (sel[j]) continue;

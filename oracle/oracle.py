@@ -36,7 +36,7 @@ def _load():
         i64, f32, vp = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
         lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, f32, vp]
-        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp]
+        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp, vp]
         lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, f32,
                                     vp, vp, vp, i64, vp, vp]
         for f in (lib.oracle_pool, lib.oracle_scores, lib.oracle_topk, lib.oracle_attn,
@@ -90,26 +90,32 @@ def scores(qp: torch.Tensor, kp: torch.Tensor, scale: float) -> torch.Tensor:
     return sp
 
 
-def topk(sp: torch.Tensor, ns: int, nl: int, k: int):
-    """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32."""
+def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | None = None):
+    """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32.
+    k_per_row: optional [NB] int32 position-dependent budget (clamped to [0, k])."""
     B, Hq, NB, _ = sp.shape
     sp = sp.contiguous()
     assert sp.dtype == torch.float32
     T = row_capacity(NB, ns, nl, k)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32)
-    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, idx.data_ptr(),
+    kr_ptr = None
+    if k_per_row is not None:
+        k_per_row = k_per_row.to(torch.int32).contiguous()
+        assert k_per_row.shape == (NB,) and k_per_row.device.type == "cpu"
+        kr_ptr = k_per_row.data_ptr()
+    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, kr_ptr, idx.data_ptr(),
                                cnt.data_ptr()), "topk")
     return idx, cnt
 
 
 def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
-           scale: float | None = None):
+           scale: float | None = None, k_per_row: torch.Tensor | None = None):
     """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp)."""
     scale = default_scale(q.shape[-1]) if scale is None else scale
     qp, kp = pool(q, block_size), pool(k, block_size)
     sp = scores(qp, kp, scale)
-    idx, cnt = topk(sp, ns, nl, topk_blocks)
+    idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row)
     return idx, cnt, sp, qp, kp
 
 

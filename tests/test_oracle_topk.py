@@ -122,3 +122,71 @@ def test_topk_hand_worked_fixture(oracle):
     idx, cnt = oracle.topk(sp, 1, 2, 2)
     for i in range(NB):
         assert idx[0, 0, i, : cnt[0, 0, i]].tolist() == want[i]
+
+
+# ---- position-dependent budget (Token Position-Decay, Sec. 4.1.2, Fig. "Stem" (b)) ----
+
+def _decaying(NB, k_first, k_last):
+    return torch.tensor([round(k_first + (k_last - k_first) * i / max(NB - 1, 1)) for i in range(NB)],
+                        dtype=torch.int32)
+
+
+def test_tpd_constant_schedule_equals_uniform(oracle):
+    g = torch.Generator().manual_seed(5)
+    NB, ns, nl, k = 23, 1, 2, 4
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    idx_u, cnt_u = oracle.topk(sp, ns, nl, k)
+    idx_c, cnt_c = oracle.topk(sp, ns, nl, k, torch.full((NB,), k, dtype=torch.int32))
+    assert torch.equal(idx_u, idx_c) and torch.equal(cnt_u, cnt_c)
+
+
+@pytest.mark.parametrize("ns,nl,k_first,k_last", [(1, 2, 9, 1), (0, 1, 6, 0), (2, 3, 12, 4)])
+def test_tpd_vs_full_sort_per_row(oracle, ns, nl, k_first, k_last):
+    g = torch.Generator().manual_seed(17 + k_first)
+    NB = 29
+    sp = torch.randn((2, 2, NB, NB), generator=g)
+    kr = _decaying(NB, k_first, k_last)
+    k_max = int(kr.max())
+    idx, cnt = oracle.topk(sp, ns, nl, k_max, kr)
+    assert idx.shape[-1] == min(NB, ns + nl + k_max)
+    for b in range(2):
+        for h in range(2):
+            for i in range(NB):
+                c = int(cnt[b, h, i])
+                want = brute_force_row(sp[b, h, i].numpy(), i, ns, nl, int(kr[i]))
+                assert idx[b, h, i, :c].tolist() == want, (b, h, i)
+                assert c == min(i + 1, ns + nl + int(kr[i]))
+                assert all(x == -1 for x in idx[b, h, i, c:].tolist())
+
+
+def test_tpd_budget_is_clamped_to_zero_and_to_the_stated_maximum(oracle):
+    g = torch.Generator().manual_seed(3)
+    NB, ns, nl, k = 17, 1, 2, 3
+    sp = torch.randn((1, 1, NB, NB), generator=g)
+    kr = torch.tensor([(-2 if i % 3 == 0 else (100 if i % 3 == 1 else 2)) for i in range(NB)], dtype=torch.int32)
+    idx, cnt = oracle.topk(sp, ns, nl, k, kr)
+    eff = kr.clamp(0, k)
+    for i in range(NB):
+        c = int(cnt[0, 0, i])
+        assert c == min(i + 1, ns + nl + int(eff[i]))
+        assert idx[0, 0, i, :c].tolist() == brute_force_row(sp[0, 0, i].numpy(), i, ns, nl, int(eff[i]))
+
+
+def test_tpd_lists_are_nested_in_the_budget(oracle):
+    """Top-k sets grow monotonically with k: a row's list under budget k_i is a subset of its
+    list under any larger budget, and the zero budget leaves exactly the static A-shape."""
+    g = torch.Generator().manual_seed(8)
+    NB, ns, nl = 21, 1, 3
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    small = _decaying(NB, 5, 1)
+    big = small + 3
+    idx_s, cnt_s = oracle.topk(sp, ns, nl, 8, small)
+    idx_b, cnt_b = oracle.topk(sp, ns, nl, 8, big)
+    idx_0, cnt_0 = oracle.topk(sp, ns, nl, 8, torch.zeros(NB, dtype=torch.int32))
+    for h in range(2):
+        for i in range(NB):
+            s = set(idx_s[0, h, i, :cnt_s[0, h, i]].tolist())
+            b = set(idx_b[0, h, i, :cnt_b[0, h, i]].tolist())
+            z = set(idx_0[0, h, i, :cnt_0[0, h, i]].tolist())
+            static = {j for j in range(i + 1) if j < ns or j >= i - nl + 1}
+            assert z == static and z <= s <= b
