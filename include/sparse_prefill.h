@@ -31,8 +31,8 @@
  *   - block_idx is [batch, n_q_heads, NB, T] int32, contiguous: for query
  *     block i the selected key blocks in ascending order, then -1 padding.
  *     block_cnt is [batch, n_q_heads, NB] int32: the number of valid entries,
- *     always min(i + 1, n_sink + n_local + top_k); the last valid entry is
- *     always i (the diagonal block).
+ *     always min(i + 1, n_sink + n_local + top_k) (with a budget schedule:
+ *     top_k of that row); the last valid entry is always i (the diagonal block).
  *   - Return value: SPA_OK (0) or a negative SPA_ERR_* code.  Arguments are
  *     validated on the host before anything is enqueued, so a failed call has
  *     no effect on the device.  Results are deterministic run to run.
@@ -140,6 +140,32 @@ int sparse_prefill_fused(const spa_params *p, const void *q, const void *k, cons
                          void *out, float *lse_or_null,
                          int32_t *block_idx_or_null, int32_t *block_cnt_or_null,
                          void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ---- Position-dependent budget: Token Position-Decay (Sec. 4.1.2, Fig. "Stem" (b)) ------------
+ * The three calls below are the select, top-k and fused calls above with the uniform budget
+ * replaced by a schedule: query block i draws k_i = min(max(top_k_per_block[i], 0),
+ * p->top_k_blocks) blocks from its non-static causal candidates, so
+ * block_cnt[b,h,i] = min(i + 1, n_sink + n_local + k_i).  The paper describes a budget that is
+ * highest for the first positions and decays along the sequence but prints no formula, so the
+ * schedule is an input: top_k_per_block is a DEVICE array of NB int32, one value per query block,
+ * shared by all heads and batch entries.  p->top_k_blocks states its maximum and fixes the row
+ * capacity T (and with it the layout of block_idx) exactly as in the uniform calls; larger
+ * entries are clamped to it, negative ones to 0.  Ranking, ties, the static pattern, the output
+ * layout, workspace and error behaviour are those of the uniform calls; a NULL schedule returns
+ * SPA_ERR_NULLPTR. */
+int sparse_prefill_select_tpd(const spa_params *p, const void *q, const void *k,
+                              const int32_t *top_k_per_block, int32_t *block_idx,
+                              int32_t *block_cnt, float *pooled_scores_or_null, void *ws,
+                              size_t ws_bytes, void *hip_stream);
+
+int sparse_prefill_topk_from_scores_tpd(const spa_params *p, const float *pooled_scores,
+                                        const int32_t *top_k_per_block, int32_t *block_idx,
+                                        int32_t *block_cnt, void *hip_stream);
+
+int sparse_prefill_fused_tpd(const spa_params *p, const void *q, const void *k, const void *v,
+                             const int32_t *top_k_per_block, void *out, float *lse_or_null,
+                             int32_t *block_idx_or_null, int32_t *block_cnt_or_null, void *ws,
+                             size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

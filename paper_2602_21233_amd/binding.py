@@ -13,7 +13,8 @@ _lib = None
 
 EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_prefill_pool",
            "sparse_prefill_select", "sparse_prefill_topk_from_scores", "sparse_prefill_attn",
-           "sparse_prefill_fused")
+           "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
+           "sparse_prefill_fused_tpd")
 
 
 class SpaError(RuntimeError):
@@ -53,6 +54,9 @@ def load_library():
     lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
     lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_select_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_topk_from_scores_tpd.argtypes = [pp, vp, vp, vp, vp, vp]
+    lib.sparse_prefill_fused_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -103,6 +107,13 @@ def _dev_bf16(*ts):
             raise TypeError("expected bf16 tensors on the GPU")
 
 
+def _schedule(top_k_per_block, n_blocks, device):
+    t = top_k_per_block
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (n_blocks,):
+        raise TypeError("top_k_per_block must be a contiguous int32 tensor [NB] on the GPU")
+    return t
+
+
 def row_capacity(p: SpaParams) -> int:
     t = ctypes.c_int32()
     _check(load_library().spa_row_capacity(ctypes.byref(p), ctypes.byref(t)))
@@ -132,8 +143,9 @@ def pool(q, k, block_size):
 
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
-           return_scores=False, workspace=None):
-    """sparse_prefill_select: returns (block_idx, block_cnt[, pooled_scores])."""
+           return_scores=False, workspace=None, top_k_per_block=None):
+    """sparse_prefill_select (sparse_prefill_select_tpd when top_k_per_block, an int32 [NB]
+    device tensor, is given): returns (block_idx, block_cnt[, pooled_scores])."""
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale)
     B, Hq, S, _ = q.shape
@@ -142,13 +154,18 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
     sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    _check(load_library().sparse_prefill_select(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(idx), _ptr(cnt),
-                                                _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
+    if top_k_per_block is None:
+        _check(load_library().sparse_prefill_select(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(idx), _ptr(cnt),
+                                                    _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
+    else:
+        kr = _schedule(top_k_per_block, NB, q.device)
+        _check(load_library().sparse_prefill_select_tpd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(kr), _ptr(idx),
+                                                        _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
     return (idx, cnt, sp) if return_scores else (idx, cnt)
 
 
-def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks):
-    """sparse_prefill_topk_from_scores on [B,Hq,NB,NB] fp32 device scores."""
+def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_per_block=None):
+    """sparse_prefill_topk_from_scores (…_tpd with a schedule) on [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
         raise TypeError("expected contiguous fp32 scores on the GPU")
     B, Hq, NB, _ = scores.shape
@@ -157,8 +174,13 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks):
     T = row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
-    _check(load_library().sparse_prefill_topk_from_scores(ctypes.byref(p), _ptr(scores), _ptr(idx), _ptr(cnt),
-                                                          _stream(scores)))
+    if top_k_per_block is None:
+        _check(load_library().sparse_prefill_topk_from_scores(ctypes.byref(p), _ptr(scores), _ptr(idx), _ptr(cnt),
+                                                              _stream(scores)))
+    else:
+        kr = _schedule(top_k_per_block, NB, scores.device)
+        _check(load_library().sparse_prefill_topk_from_scores_tpd(ctypes.byref(p), _ptr(scores), _ptr(kr),
+                                                                  _ptr(idx), _ptr(cnt), _stream(scores)))
     return idx, cnt
 
 
@@ -183,8 +205,8 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
-          return_lse=False, return_lists=False, workspace=None, out=None):
-    """sparse_prefill_fused: select + attn on the current stream."""
+          return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None):
+    """sparse_prefill_fused (…_tpd with a schedule): select + attn on the current stream."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
@@ -194,8 +216,14 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    _check(load_library().sparse_prefill_fused(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
-                                               _ptr(idx), _ptr(cnt), _ptr(ws), ws.numel(), _stream(q)))
+    if top_k_per_block is None:
+        _check(load_library().sparse_prefill_fused(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+                                                   _ptr(idx), _ptr(cnt), _ptr(ws), ws.numel(), _stream(q)))
+    else:
+        kr = _schedule(top_k_per_block, NB, q.device)
+        _check(load_library().sparse_prefill_fused_tpd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
+                                                       _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),
+                                                       ws.numel(), _stream(q)))
     res = [out]
     if return_lse:
         res.append(lse)

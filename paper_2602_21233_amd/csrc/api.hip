@@ -61,6 +61,57 @@ int launch_code(hipError_t e) { return e == hipSuccess ? SPA_OK : SPA_ERR_LAUNCH
 
 }  // namespace
 
+namespace {
+int select_impl(const spa_params* p, const void* q, const void* k, const int32_t* k_rows, int32_t* block_idx,
+                int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
+    Dims d = resolved(p);
+    Workspace w = carve(d);
+    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
+    float* qp = (float*)((char*)ws + w.qp_off);
+    float* kp = (float*)((char*)ws + w.kp_off);
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, st);
+    if (e != hipSuccess) return SPA_ERR_LAUNCH;
+    return launch_code(launch_score_topk(d, qp, kp, k_rows, block_idx, block_cnt, pooled_scores_or_null, st));
+}
+
+int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_rows, int32_t* block_idx,
+              int32_t* block_cnt, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!pooled_scores || !block_idx || !block_cnt) return SPA_ERR_NULLPTR;
+    Dims d = resolved(p);
+    return launch_code(launch_topk_from_scores(d, pooled_scores, k_rows, block_idx, block_cnt,
+                                               (hipStream_t)hip_stream));
+}
+
+int fused_impl(const spa_params* p, const void* q, const void* k, const void* v, const int32_t* k_rows, void* out,
+               float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws,
+               size_t ws_bytes, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if ((block_idx_or_null == nullptr) != (block_cnt_or_null == nullptr)) return SPA_ERR_NULLPTR;
+    if (!ws) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
+    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
+    Dims d = resolved(p);
+    Workspace w = carve(d);
+    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
+    int32_t* idx = block_idx_or_null ? block_idx_or_null : (int32_t*)((char*)ws + w.idx_off);
+    int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
+    rc = select_impl(p, q, k, k_rows, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
+    if (rc) return rc;
+    return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, ws, ws_bytes, hip_stream);
+}
+}  // namespace
+
 #pragma GCC visibility push(default)
 extern "C" {
 
@@ -106,33 +157,31 @@ int sparse_prefill_pool(const spa_params* p, const void* q, const void* k, float
                                    k_pooled, (hipStream_t)hip_stream));
 }
 
+
 int sparse_prefill_select(const spa_params* p, const void* q, const void* k, int32_t* block_idx,
                           int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
                           void* hip_stream) {
-    int rc = check_shape(p);
-    if (rc) return rc;
-    if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
-    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
-    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
-    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
-    Dims d = resolved(p);
-    Workspace w = carve(d);
-    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
-    float* qp = (float*)((char*)ws + w.qp_off);
-    float* kp = (float*)((char*)ws + w.kp_off);
-    hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, st);
-    if (e != hipSuccess) return SPA_ERR_LAUNCH;
-    return launch_code(launch_score_topk(d, qp, kp, block_idx, block_cnt, pooled_scores_or_null, st));
+    return select_impl(p, q, k, nullptr, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes, hip_stream);
+}
+
+int sparse_prefill_select_tpd(const spa_params* p, const void* q, const void* k, const int32_t* top_k_per_block,
+                              int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws,
+                              size_t ws_bytes, void* hip_stream) {
+    if (!top_k_per_block) return SPA_ERR_NULLPTR;
+    return select_impl(p, q, k, top_k_per_block, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
+                       hip_stream);
 }
 
 int sparse_prefill_topk_from_scores(const spa_params* p, const float* pooled_scores, int32_t* block_idx,
                                     int32_t* block_cnt, void* hip_stream) {
-    int rc = check_shape(p);
-    if (rc) return rc;
-    if (!pooled_scores || !block_idx || !block_cnt) return SPA_ERR_NULLPTR;
-    Dims d = resolved(p);
-    return launch_code(launch_topk_from_scores(d, pooled_scores, block_idx, block_cnt, (hipStream_t)hip_stream));
+    return topk_impl(p, pooled_scores, nullptr, block_idx, block_cnt, hip_stream);
+}
+
+int sparse_prefill_topk_from_scores_tpd(const spa_params* p, const float* pooled_scores,
+                                        const int32_t* top_k_per_block, int32_t* block_idx, int32_t* block_cnt,
+                                        void* hip_stream) {
+    if (!top_k_per_block) return SPA_ERR_NULLPTR;
+    return topk_impl(p, pooled_scores, top_k_per_block, block_idx, block_cnt, hip_stream);
 }
 
 int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const void* v,
@@ -162,21 +211,17 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
                          float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null,
                          void* ws, size_t ws_bytes, void* hip_stream) {
-    int rc = check_shape(p);
-    if (rc) return rc;
-    if ((block_idx_or_null == nullptr) != (block_cnt_or_null == nullptr)) return SPA_ERR_NULLPTR;
-    if (!ws) return SPA_ERR_NULLPTR;
-    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
-    if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
-    if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
-    Dims d = resolved(p);
-    Workspace w = carve(d);
-    if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
-    int32_t* idx = block_idx_or_null ? block_idx_or_null : (int32_t*)((char*)ws + w.idx_off);
-    int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
-    rc = sparse_prefill_select(p, q, k, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
-    if (rc) return rc;
-    return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, ws, ws_bytes, hip_stream);
+    return fused_impl(p, q, k, v, nullptr, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws, ws_bytes,
+                      hip_stream);
+}
+
+int sparse_prefill_fused_tpd(const spa_params* p, const void* q, const void* k, const void* v,
+                             const int32_t* top_k_per_block, void* out, float* lse_or_null,
+                             int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+    if (!top_k_per_block) return SPA_ERR_NULLPTR;
+    return fused_impl(p, q, k, v, top_k_per_block, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws,
+                      ws_bytes, hip_stream);
 }
 
 }  // extern "C"

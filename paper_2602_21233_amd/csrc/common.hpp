@@ -33,10 +33,11 @@ inline Strides strides_of(const int64_t s[3]) { return Strides{s[0], s[1], s[2]}
 // Launchers (one per kernel file).  Each returns a hipError_t from the launch.
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        float* qp, float* kp, hipStream_t st);
-hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, int32_t* idx,
-                             int32_t* cnt, float* scores_or_null, hipStream_t st);
-hipError_t launch_topk_from_scores(const Dims& d, const float* scores, int32_t* idx, int32_t* cnt,
-                                   hipStream_t st);
+// k_rows: optional device array of NB per-query-block budgets (clamped to [0, d.k] in the kernel).
+hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
+                             int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st);
+hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows, int32_t* idx,
+                                   int32_t* cnt, hipStream_t st);
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
                        void* out, Strides os, float* lse, hipStream_t st);

@@ -1,6 +1,7 @@
 // Pooled scores, per-row top-k and merge with the static A-shape pattern
 // (pattern computation, steps 2-4; Sec. 4.1.1 dynamic sparsity, uniform top-k
-// budget of Sec. 4.1.2 Fig. "Stem" (a), static A-shape of Sec. 4.1.1).
+// budget of Sec. 4.1.2 Fig. "Stem" (a) or the per-query-block budget schedule of
+// Token Position-Decay, Fig. "Stem" (b); static A-shape of Sec. 4.1.1).
 //
 // score_topk_mfma_kernel: one 512-thread workgroup owns R consecutive query
 // blocks of one query head.
@@ -105,9 +106,16 @@ __device__ void select_row(const uint32_t* keys, int i, int ns, int nl, int k, i
 constexpr int kWaves = 4;
 
 // scores come from memory: [rows_total, NB, NB]
+// budget of query block i: the uniform k, or the schedule's entry clamped to [0, k]
+__device__ __forceinline__ int row_budget(const int32_t* __restrict__ k_rows, int i, int k) {
+    if (k_rows == nullptr) return k;
+    const int v = k_rows[i];
+    return v < 0 ? 0 : (v > k ? k : v);
+}
+
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
-    const float* __restrict__ scores, int64_t n_rows, int NB, int ns, int nl, int k, int T,
-    int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+    const float* __restrict__ scores, int64_t n_rows, int NB, int ns, int nl, int k,
+    const int32_t* __restrict__ k_rows, int T, int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
     extern __shared__ uint32_t lds_keys[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
         keys[j] = key;
     }
     // each wave reads back only its own slice; LDS ops of one wave are ordered
-    select_row(keys, i, ns, nl, k, T, idx + row * T, cnt + row);
+    select_row(keys, i, ns, nl, row_budget(k_rows, i, k), T, idx + row * T, cnt + row);
 }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -191,8 +199,8 @@ constexpr int kMfmaWaves = 8;
 template <int D, int R, int MAXC>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, int ns, int nl,
-    int k, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-    float* __restrict__ scores_out) {
+    int k, const int32_t* __restrict__ k_rows, int T, float scale, int32_t* __restrict__ idx,
+    int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
     extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
@@ -299,7 +307,8 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         int first_local = lo > 0 ? lo : 0;
         int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
         const int n_cand = n - (n_sink + n_local - overlap);
-        const int kk = k < n_cand ? k : n_cand;
+        const int k_i = row_budget(k_rows, i, k);
+        const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
         int need_eq;
         find_threshold_regs<MAXC>(key, kk, n_cand, thr, need_eq);
@@ -338,45 +347,45 @@ size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) 
 
 }  // namespace
 
-hipError_t launch_topk_from_scores(const Dims& d, const float* scores, int32_t* idx, int32_t* cnt,
-                                   hipStream_t st) {
+hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows, int32_t* idx,
+                                   int32_t* cnt, hipStream_t st) {
     int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
     unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
     hipError_t e = allow_lds((const void*)topk_from_scores_kernel, keys_lds_bytes(d.NB));
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(topk_from_scores_kernel, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                       scores, n_rows, d.NB, d.ns, d.nl, d.k, d.T, idx, cnt);
+                       scores, n_rows, d.NB, d.ns, d.nl, d.k, k_rows, d.T, idx, cnt);
     return hipGetLastError();
 }
 
 template <int D, int R, int MAXC>
-hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, int32_t* idx, int32_t* cnt,
-                       float* scores_or_null, hipStream_t st) {
+hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, int32_t* idx,
+                       int32_t* cnt, float* scores_or_null, hipStream_t st) {
     constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
     hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC>, lds);
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, d.T, d.scale, idx, cnt, scores_or_null);
+                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, k_rows, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, int32_t* idx, int32_t* cnt,
-                         float* scores_or_null, hipStream_t st) {
+hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, int32_t* idx,
+                         int32_t* cnt, float* scores_or_null, hipStream_t st) {
     // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
-    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, idx, cnt, scores_or_null, st);
-    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, idx, cnt, scores_or_null, st);
-    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, idx, cnt, scores_or_null, st);
-    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, idx, cnt, scores_or_null, st);
-    return launch_mfma<D, 8, 64>(d, qp, kp, idx, cnt, scores_or_null, st);
+    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
 }
 
-hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, int32_t* idx,
-                             int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, idx, cnt, scores_or_null, st);
-    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, idx, cnt, scores_or_null, st);
+hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
+                             int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
+    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
     return hipErrorInvalidValue;
 }
 

@@ -150,6 +150,18 @@ def make_qkv(w: Workload, device: str | torch.device = "cpu"):
     return tuple(out)
 
 
+def decay_schedule(w: Workload, k_first: int | None = None, k_last: int | None = None) -> torch.Tensor:
+    """A position-decaying top-k budget per query block, int32 [NB] on the CPU: k_first blocks for
+    the first query block falling linearly to k_last for the last one (defaults: the workload's
+    top_k and a quarter of it).  The paper's Token Position-Decay (Sec. 4.1.2, Fig. "Stem" (b))
+    gives early positions the larger budget but prints no schedule; this one is a stand-in input."""
+    k_first = w.top_k_blocks if k_first is None else k_first
+    k_last = max(w.top_k_blocks // 4, 0) if k_last is None else k_last
+    nb = w.n_blocks
+    pos = torch.arange(nb, dtype=torch.float64) / max(nb - 1, 1)
+    return torch.round(k_first + (k_last - k_first) * pos).to(torch.int32)
+
+
 def sample_rows(w: Workload, n_random: int, seed: int = 0):
     """(b, h, i) rows for sampled parity at full size: the structural corner
     rows of a few heads plus seeded random ones."""

@@ -83,6 +83,15 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
                                     None) == -1
     assert lib.sparse_prefill_topk_from_scores(ctypes.byref(p), None, fake, fake, None) == -1
     assert lib.sparse_prefill_pool(ctypes.byref(p), fake, None, None, None, None) == -1
+    # the budget-schedule calls: a missing schedule is an error, the other checks are those of the uniform calls
+    assert lib.sparse_prefill_select_tpd(ctypes.byref(p), fake, fake, None, fake, fake, None, fake, 1 << 30, None) == -1
+    assert lib.sparse_prefill_select_tpd(ctypes.byref(p), fake, fake, fake, fake, fake, None, fake, 16, None) == -5
+    assert lib.sparse_prefill_topk_from_scores_tpd(ctypes.byref(p), fake, None, fake, fake, None) == -1
+    assert lib.sparse_prefill_topk_from_scores_tpd(ctypes.byref(p), None, fake, fake, fake, None) == -1
+    assert lib.sparse_prefill_fused_tpd(ctypes.byref(p), fake, fake, fake, None, fake, None, None, None, fake,
+                                        1 << 30, None) == -1
+    assert lib.sparse_prefill_fused_tpd(ctypes.byref(p), fake, fake, fake, fake, fake, None, fake, None, fake,
+                                        1 << 30, None) == -1
     bad = _params()
     bad.q_stride = (ctypes.c_int64 * 3)(0, 1024 * 128, 100)
     assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -4
