@@ -18,9 +18,12 @@
 //   * K rows are assigned to MFMA rows with bits 2 and 3 of the row index
 //     swapped; the logits a lane ends up holding are then 8 consecutive keys per
 //     16-key slice, which is exactly the B-operand order of the second product.
-//   * the running maximum is only raised when a row's new maximum exceeds it by
-//     more than 2^8 in the exp2 domain, so the O^T rescale is rare; the final
-//     normalisation makes the result independent of this.
+//   * no running maximum: weights are 2^(x*c - m*c - 7) against a reference m that is only
+//     raised when some weight reaches 2 (the logit outgrew m by 2^8), which shows as the top
+//     exponent bit of the bf16 weight; the final normalisation makes the result independent
+//     of m.
+//   * a step (32 keys) overlaps three chains: logits of chunk n+2 (MFMA), weights of chunk
+//     n+1 (VALU), O^T += V^T P^T of chunk n (MFMA); its instruction order is fixed by hand.
 #include <type_traits>
 
 #include "common.hpp"
