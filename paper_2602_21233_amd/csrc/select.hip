@@ -165,7 +165,8 @@ __device__ __forceinline__ int wave_sum(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-template <int MAXC>
+// NC <= MAXC: only key[0 .. NC) can be nonzero for this row (blocks beyond the row hold 0).
+template <int MAXC, int NC>
 __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC], int kk, int n_cand,
                                                     uint32_t& thr, int& need_eq) {
     thr = 0xffffffffu;
@@ -181,14 +182,14 @@ __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC],
         // shared by the whole CU and a ballot + popcount per chunk saturates it
         int cl = 0;
 #pragma unroll
-        for (int m = 0; m < MAXC; ++m) cl += (key[m] >= trial) ? 1 : 0;
+        for (int m = 0; m < NC; ++m) cl += (key[m] >= trial) ? 1 : 0;
         const int c = wave_sum(cl);
         if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
     }
     if (c_at_p == kk) { thr = p - 1u; return; }
     int gl = 0;
 #pragma unroll
-    for (int m = 0; m < MAXC; ++m) gl += (key[m] > p) ? 1 : 0;
+    for (int m = 0; m < NC; ++m) gl += (key[m] > p) ? 1 : 0;
     const int gt = wave_sum(gl);
     thr = p;
     need_eq = kk - gt;
@@ -311,7 +312,12 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
         int need_eq;
-        find_threshold_regs<MAXC>(key, kk, n_cand, thr, need_eq);
+        // rows are causal: a row early in the sequence fills only its first chunks of 64 blocks
+        const int nc4 = 4 * ((i >> 6) + 1);               // wave-uniform
+        if (nc4 <= MAXC) find_threshold_regs<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, thr, need_eq);
+        else if (nc4 <= 2 * MAXC) find_threshold_regs<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, thr, need_eq);
+        else if (nc4 <= 3 * MAXC) find_threshold_regs<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, thr, need_eq);
+        else find_threshold_regs<MAXC, MAXC>(key, kk, n_cand, thr, need_eq);
 
         // emit static U top-k in ascending block order (keys recomputed from LDS: a rolled loop)
         const int64_t row = (int64_t)bh * NB + i;
