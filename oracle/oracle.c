@@ -17,7 +17,9 @@
  *     selection" of the abstract),
  *   - optionally the position-dependent budget of Stem's Token Position-Decay
  *     (Sec. 4.1.2, Fig. "Stem" (b)) in place of the uniform one; the schedule
- *     itself is an input, the paper prints none.
+ *     itself is an input, the paper prints none,
+ *   - optionally the value-aware ranking score of Stem's Output-Aware Metric
+ *     (Sec. 4.1.2, Fig. "Stem" (c)); reading stated at oracle_vnorm.
  * The paper gives no formula for any step.  The concrete readings taken here:
  * block granularity, arithmetic-mean pooling, raw pooled logit as the ranking
  * score, top-k drawn from the causal candidates that are not already static,
@@ -83,6 +85,54 @@ int oracle_scores(const float *qp, const float *kp, int64_t B, int64_t Hq,
                         acc += (double)qrow[d] * (double)krow[d];
                     srow[j] = (float)((double)scale * acc);
                 }
+            }
+    return 0;
+}
+
+/* Output-aware ranking score (Stem's Output-Aware Metric, Sec. 4.1.2, Fig.
+ * "Stem" (c): the selection metric combines the attention score with the
+ * magnitude of the value vectors, so a block whose values are weak is less
+ * likely to be kept).  The paper prints no formula.  Reading taken here: a key
+ * block's contribution to the output is its attention weight times the size
+ * of its values, which in the logit domain is a sum:
+ *   vn[n,j]  = (1/Bs) sum_t || V[n, j*Bs+t, :] ||_2        (fp64, rounded to fp32)
+ *   sp'[b,h,i,j] = sp[b,h,i,j] + ln vn[b,h/G,j]             (j <= i)
+ * from the fp32 score and fp32 vn, added in fp64, rounded once to fp32.  A
+ * block of all-zero values gets -inf.  oracle_vnorm computes vn,
+ * oracle_scores_oam applies the second line in place. */
+int oracle_vnorm(const uint16_t *v, int64_t n_heads_total, int64_t S, int64_t D,
+                 int64_t Bs, float *vn) {
+    if (Bs <= 0 || S % Bs) return -1;
+    int64_t NB = S / Bs;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < n_heads_total; ++n)
+        for (int64_t j = 0; j < NB; ++j) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < Bs; ++t) {
+                double sq = 0.0;
+                for (int64_t d = 0; d < D; ++d) {
+                    double x = bf16_to_f64(v[(n * S + j * Bs + t) * D + d]);
+                    sq += x * x;
+                }
+                acc += sqrt(sq);
+            }
+            vn[n * NB + j] = (float)(acc / (double)Bs);
+        }
+    return 0;
+}
+
+int oracle_scores_oam(float *sp, const float *vn, int64_t B, int64_t Hq, int64_t Hkv,
+                      int64_t NB) {
+    if (Hkv <= 0 || Hq % Hkv) return -1;
+    int64_t G = Hq / Hkv;
+#pragma omp parallel for collapse(3) schedule(static)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < Hq; ++h)
+            for (int64_t i = 0; i < NB; ++i) {
+                float *srow = sp + ((b * Hq + h) * NB + i) * NB;
+                const float *vrow = vn + (b * Hkv + h / G) * NB;
+                for (int64_t j = 0; j <= i; ++j)
+                    srow[j] = (float)((double)srow[j] + log((double)vrow[j]));
             }
     return 0;
 }

@@ -37,10 +37,12 @@ def _load():
         lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, f32, vp]
         lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp, vp]
+        lib.oracle_vnorm.argtypes = [vp, i64, i64, i64, i64, vp]
+        lib.oracle_scores_oam.argtypes = [vp, vp, i64, i64, i64, i64]
         lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, f32,
                                     vp, vp, vp, i64, vp, vp]
         for f in (lib.oracle_pool, lib.oracle_scores, lib.oracle_topk, lib.oracle_attn,
-                  lib.oracle_num_threads):
+                  lib.oracle_num_threads, lib.oracle_vnorm, lib.oracle_scores_oam):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -90,6 +92,26 @@ def scores(qp: torch.Tensor, kp: torch.Tensor, scale: float) -> torch.Tensor:
     return sp
 
 
+def vnorm(v: torch.Tensor, block_size: int) -> torch.Tensor:
+    """v [B,Hkv,S,D] bf16 -> [B,Hkv,S/Bs] fp32: mean L2 norm of each block's value vectors."""
+    B, H, S, D = v.shape
+    vb = _bits(v)
+    out = torch.empty((B, H, S // block_size), dtype=torch.float32)
+    _check(_load().oracle_vnorm(vb.data_ptr(), B * H, S, D, block_size, out.data_ptr()), "vnorm")
+    return out
+
+
+def scores_oam(sp: torch.Tensor, vn: torch.Tensor) -> torch.Tensor:
+    """Output-aware scores: sp[b,h,i,j] + ln vn[b,h/G,j] for j <= i (a copy; j > i untouched)."""
+    B, Hq, NB, _ = sp.shape
+    Hkv = vn.shape[1]
+    out = sp.contiguous().clone()
+    vn = vn.contiguous()
+    assert out.dtype == torch.float32 and vn.dtype == torch.float32 and vn.shape == (B, Hkv, NB)
+    _check(_load().oracle_scores_oam(out.data_ptr(), vn.data_ptr(), B, Hq, Hkv, NB), "scores_oam")
+    return out
+
+
 def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | None = None):
     """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32.
     k_per_row: optional [NB] int32 position-dependent budget (clamped to [0, k])."""
@@ -110,11 +132,14 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
 
 
 def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
-           scale: float | None = None, k_per_row: torch.Tensor | None = None):
-    """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp)."""
+           scale: float | None = None, k_per_row: torch.Tensor | None = None, v: torch.Tensor | None = None):
+    """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp).  With v the ranking score is
+    the output-aware one (scores_oam) and sp is that score."""
     scale = default_scale(q.shape[-1]) if scale is None else scale
     qp, kp = pool(q, block_size), pool(k, block_size)
     sp = scores(qp, kp, scale)
+    if v is not None:
+        sp = scores_oam(sp, vnorm(v, block_size))
     idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row)
     return idx, cnt, sp, qp, kp
 
