@@ -81,10 +81,11 @@ const char *spa_strerror(int code);
 /* Row capacity T of block_idx for these parameters.  Host only. */
 int spa_row_capacity(const spa_params *p, int32_t *row_capacity);
 
-/* Bytes of device scratch that sparse_prefill_select, sparse_prefill_attn and
- * sparse_prefill_fused need in `ws` (pooled Q and K; the block lists of a fused
- * call whose caller does not ask for them; for head_dim 128 a per-block
- * transposed copy of V).  One size serves all three calls.  Host only. */
+/* Bytes of device scratch that the select, attn and fused calls (all variants)
+ * need in `ws` (pooled Q and K; the block lists of a fused call whose caller
+ * does not ask for them; the value norms of the output-aware calls; for
+ * head_dim 128 a per-block transposed copy of V).  One size serves every call.
+ * Host only. */
 int spa_workspace_bytes(const spa_params *p, size_t *bytes);
 
 /* Pattern computation, step 1 (Sec. 4.1.1): block mean pooling.
@@ -166,6 +167,35 @@ int sparse_prefill_fused_tpd(const spa_params *p, const void *q, const void *k, 
                              const int32_t *top_k_per_block, void *out, float *lse_or_null,
                              int32_t *block_idx_or_null, int32_t *block_cnt_or_null, void *ws,
                              size_t ws_bytes, void *hip_stream);
+
+/* ---- Output-aware ranking: Stem's Output-Aware Metric (Sec. 4.1.2, Fig. "Stem" (c)) --------------
+ * The paper ranks key blocks by a metric that combines the attention score with the magnitude of
+ * the value vectors and prints no formula.  Reading implemented here: a block's contribution to
+ * the output is its attention weight times the size of its values, a sum in the logit domain:
+ *   vn[b,hk,j]      = mean over the block's tokens t of || V[b,hk,j*Bs+t,:] ||_2      (fp32)
+ *   rank[b,h,i,j]   = score[b,h,i,j] + ln vn[b,h/G,j]                                 (fp32)
+ * with score as in sparse_prefill_select; a block of all-zero values ranks as -inf.  Only the
+ * ranking changes: budget, ties, static pattern, list layout and the attention itself do not.
+ *
+ * sparse_prefill_value_norms: log_value_norms [batch, n_kv_heads, NB] fp32 <- ln vn.
+ * sparse_prefill_select_stem: select with rank in place of score.  top_k_per_block_or_null: NULL
+ *   for the uniform budget, else the Token Position-Decay schedule of the _tpd calls (both ideas
+ *   together are the paper's Stem).  ranking_scores_or_null receives rank (j > i: -inf).
+ * sparse_prefill_fused_stem: select_stem followed by attn.
+ * V is read once more than in the plain calls (+ batch*n_kv_heads*seq_len*head_dim*2 bytes). */
+int sparse_prefill_value_norms(const spa_params *p, const void *v, float *log_value_norms,
+                               void *hip_stream);
+
+int sparse_prefill_select_stem(const spa_params *p, const void *q, const void *k, const void *v,
+                               const int32_t *top_k_per_block_or_null, int32_t *block_idx,
+                               int32_t *block_cnt, float *ranking_scores_or_null, void *ws,
+                               size_t ws_bytes, void *hip_stream);
+
+int sparse_prefill_fused_stem(const spa_params *p, const void *q, const void *k, const void *v,
+                              const int32_t *top_k_per_block_or_null, void *out,
+                              float *lse_or_null, int32_t *block_idx_or_null,
+                              int32_t *block_cnt_or_null, void *ws, size_t ws_bytes,
+                              void *hip_stream);
 
 #ifdef __cplusplus
 }

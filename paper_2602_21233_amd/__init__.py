@@ -5,7 +5,7 @@ The binding only marshals arguments: every step of the path runs in the HIP
 kernels.  PyTorch supplies device memory and the current stream.
 """
 from .binding import (SpaError, attn, fused, library_path, load_library, pool, row_capacity, select,
-                      topk_from_scores, workspace_bytes)
+                      topk_from_scores, value_norms, workspace_bytes)
 
 __all__ = ["SpaError", "attn", "fused", "library_path", "load_library", "pool", "row_capacity",
-           "select", "topk_from_scores", "workspace_bytes"]
+           "select", "topk_from_scores", "value_norms", "workspace_bytes"]

@@ -14,7 +14,8 @@ _lib = None
 EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_prefill_pool",
            "sparse_prefill_select", "sparse_prefill_topk_from_scores", "sparse_prefill_attn",
            "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
-           "sparse_prefill_fused_tpd")
+           "sparse_prefill_fused_tpd", "sparse_prefill_value_norms", "sparse_prefill_select_stem",
+           "sparse_prefill_fused_stem")
 
 
 class SpaError(RuntimeError):
@@ -57,6 +58,9 @@ def load_library():
     lib.sparse_prefill_select_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_topk_from_scores_tpd.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.sparse_prefill_fused_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_value_norms.argtypes = [pp, vp, vp, vp]
+    lib.sparse_prefill_select_stem.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_fused_stem.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -142,19 +146,37 @@ def pool(q, k, block_size):
     return qp, kp
 
 
+def value_norms(v, block_size):
+    """sparse_prefill_value_norms: ln of the mean value-vector norm per key block, fp32 [B,Hkv,NB]."""
+    _dev_bf16(v)
+    B, Hkv, S, D = v.shape
+    p = make_params(batch=B, n_q_heads=Hkv, n_kv_heads=Hkv, seq_len=S, head_dim=D, block_size=block_size,
+                    n_sink_blocks=0, n_local_blocks=1, top_k_blocks=0, v=v)
+    out = torch.empty((B, Hkv, S // block_size), dtype=torch.float32, device=v.device)
+    _check(load_library().sparse_prefill_value_norms(ctypes.byref(p), _ptr(v), _ptr(out), _stream(v)))
+    return out
+
+
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
-           return_scores=False, workspace=None, top_k_per_block=None):
-    """sparse_prefill_select (sparse_prefill_select_tpd when top_k_per_block, an int32 [NB]
-    device tensor, is given): returns (block_idx, block_cnt[, pooled_scores])."""
+           return_scores=False, workspace=None, top_k_per_block=None, v=None):
+    """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
+    tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
+    without a schedule).  Returns (block_idx, block_cnt[, scores])."""
     _dev_bf16(q, k)
-    p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale)
+    p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v)
     B, Hq, S, _ = q.shape
     NB, T = S // block_size, row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
     sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if top_k_per_block is None:
+    if v is not None:
+        _dev_bf16(v)
+        kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
+        _check(load_library().sparse_prefill_select_stem(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
+                                                         _ptr(idx), _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(),
+                                                         _stream(q)))
+    elif top_k_per_block is None:
         _check(load_library().sparse_prefill_select(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(idx), _ptr(cnt),
                                                     _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
     else:
@@ -205,8 +227,10 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
-          return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None):
-    """sparse_prefill_fused (…_tpd with a schedule): select + attn on the current stream."""
+          return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
+          output_aware=False):
+    """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
+    current stream."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
@@ -216,7 +240,12 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if top_k_per_block is None:
+    if output_aware:
+        kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
+        _check(load_library().sparse_prefill_fused_stem(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
+                                                        _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),
+                                                        ws.numel(), _stream(q)))
+    elif top_k_per_block is None:
         _check(load_library().sparse_prefill_fused(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                                    _ptr(idx), _ptr(cnt), _ptr(ws), ws.numel(), _stream(q)))
     else:

@@ -41,7 +41,7 @@ Dims resolved(const spa_params* p) {
 }
 
 struct Workspace {
-    size_t qp_off, kp_off, idx_off, cnt_off, vt_off, total;
+    size_t qp_off, kp_off, idx_off, cnt_off, lvn_off, vt_off, total;
 };
 
 Workspace carve(const Dims& d) {
@@ -51,6 +51,7 @@ Workspace carve(const Dims& d) {
     w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
     w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
+    w.lvn_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * sizeof(float));
     w.vt_off = off;
     if (d.D == 128) off = align_up(off + (size_t)d.B * d.Hkv * d.S * d.D * sizeof(uint16_t));
     w.total = off;
@@ -62,13 +63,16 @@ int launch_code(hipError_t e) { return e == hipSuccess ? SPA_OK : SPA_ERR_LAUNCH
 }  // namespace
 
 namespace {
-int select_impl(const spa_params* p, const void* q, const void* k, const int32_t* k_rows, int32_t* block_idx,
-                int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
+// v_or_null: values for the output-aware ranking score, or nullptr for the plain pooled score
+int select_impl(const spa_params* p, const void* q, const void* k, const void* v_or_null, const int32_t* k_rows,
+                int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
+                void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
     if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
     if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
     if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if (v_or_null && (rc = check_tensor(v_or_null, p->v_stride, p->head_dim))) return rc;
     if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
     Dims d = resolved(p);
     Workspace w = carve(d);
@@ -78,7 +82,12 @@ int select_impl(const spa_params* p, const void* q, const void* k, const int32_t
     hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, st);
     if (e != hipSuccess) return SPA_ERR_LAUNCH;
-    return launch_code(launch_score_topk(d, qp, kp, k_rows, block_idx, block_cnt, pooled_scores_or_null, st));
+    float* lvn = nullptr;
+    if (v_or_null) {
+        lvn = (float*)((char*)ws + w.lvn_off);
+        if (launch_vnorm(d, v_or_null, strides_of(p->v_stride), lvn, st) != hipSuccess) return SPA_ERR_LAUNCH;
+    }
+    return launch_code(launch_score_topk(d, qp, kp, k_rows, lvn, block_idx, block_cnt, pooled_scores_or_null, st));
 }
 
 int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_rows, int32_t* block_idx,
@@ -91,9 +100,9 @@ int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_
                                                (hipStream_t)hip_stream));
 }
 
-int fused_impl(const spa_params* p, const void* q, const void* k, const void* v, const int32_t* k_rows, void* out,
-               float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws,
-               size_t ws_bytes, void* hip_stream) {
+int fused_impl(const spa_params* p, const void* q, const void* k, const void* v, const int32_t* k_rows,
+               bool output_aware, void* out, float* lse_or_null, int32_t* block_idx_or_null,
+               int32_t* block_cnt_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
     if ((block_idx_or_null == nullptr) != (block_cnt_or_null == nullptr)) return SPA_ERR_NULLPTR;
@@ -106,7 +115,7 @@ int fused_impl(const spa_params* p, const void* q, const void* k, const void* v,
     if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
     int32_t* idx = block_idx_or_null ? block_idx_or_null : (int32_t*)((char*)ws + w.idx_off);
     int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
-    rc = select_impl(p, q, k, k_rows, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
+    rc = select_impl(p, q, k, output_aware ? v : nullptr, k_rows, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
     if (rc) return rc;
     return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, ws, ws_bytes, hip_stream);
 }
@@ -161,15 +170,16 @@ int sparse_prefill_pool(const spa_params* p, const void* q, const void* k, float
 int sparse_prefill_select(const spa_params* p, const void* q, const void* k, int32_t* block_idx,
                           int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
                           void* hip_stream) {
-    return select_impl(p, q, k, nullptr, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes, hip_stream);
+    return select_impl(p, q, k, nullptr, nullptr, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
+                       hip_stream);
 }
 
 int sparse_prefill_select_tpd(const spa_params* p, const void* q, const void* k, const int32_t* top_k_per_block,
                               int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws,
                               size_t ws_bytes, void* hip_stream) {
     if (!top_k_per_block) return SPA_ERR_NULLPTR;
-    return select_impl(p, q, k, top_k_per_block, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
-                       hip_stream);
+    return select_impl(p, q, k, nullptr, top_k_per_block, block_idx, block_cnt, pooled_scores_or_null, ws,
+                       ws_bytes, hip_stream);
 }
 
 int sparse_prefill_topk_from_scores(const spa_params* p, const float* pooled_scores, int32_t* block_idx,
@@ -211,8 +221,8 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
                          float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null,
                          void* ws, size_t ws_bytes, void* hip_stream) {
-    return fused_impl(p, q, k, v, nullptr, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws, ws_bytes,
-                      hip_stream);
+    return fused_impl(p, q, k, v, nullptr, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws,
+                      ws_bytes, hip_stream);
 }
 
 int sparse_prefill_fused_tpd(const spa_params* p, const void* q, const void* k, const void* v,
@@ -220,8 +230,33 @@ int sparse_prefill_fused_tpd(const spa_params* p, const void* q, const void* k, 
                              int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws, size_t ws_bytes,
                              void* hip_stream) {
     if (!top_k_per_block) return SPA_ERR_NULLPTR;
-    return fused_impl(p, q, k, v, top_k_per_block, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws,
-                      ws_bytes, hip_stream);
+    return fused_impl(p, q, k, v, top_k_per_block, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null,
+                      ws, ws_bytes, hip_stream);
+}
+
+int sparse_prefill_value_norms(const spa_params* p, const void* v, float* log_value_norms, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!log_value_norms) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
+    Dims d = resolved(p);
+    return launch_code(launch_vnorm(d, v, strides_of(p->v_stride), log_value_norms, (hipStream_t)hip_stream));
+}
+
+int sparse_prefill_select_stem(const spa_params* p, const void* q, const void* k, const void* v,
+                               const int32_t* top_k_per_block_or_null, int32_t* block_idx, int32_t* block_cnt,
+                               float* ranking_scores_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!v) return SPA_ERR_NULLPTR;
+    return select_impl(p, q, k, v, top_k_per_block_or_null, block_idx, block_cnt, ranking_scores_or_null, ws,
+                       ws_bytes, hip_stream);
+}
+
+int sparse_prefill_fused_stem(const spa_params* p, const void* q, const void* k, const void* v,
+                              const int32_t* top_k_per_block_or_null, void* out, float* lse_or_null,
+                              int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws, size_t ws_bytes,
+                              void* hip_stream) {
+    return fused_impl(p, q, k, v, top_k_per_block_or_null, true, out, lse_or_null, block_idx_or_null,
+                      block_cnt_or_null, ws, ws_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -33,9 +33,13 @@ inline Strides strides_of(const int64_t s[3]) { return Strides{s[0], s[1], s[2]}
 // Launchers (one per kernel file).  Each returns a hipError_t from the launch.
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        float* qp, float* kp, hipStream_t st);
+// lvn [B*Hkv, NB] fp32: ln of the mean value-vector norm of every key block.
+hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st);
 // k_rows: optional device array of NB per-query-block budgets (clamped to [0, d.k] in the kernel).
+// lvn: optional; added to the score of key block j (output-aware ranking).
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
-                             int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st);
+                             const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
+                             hipStream_t st);
 hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows, int32_t* idx,
                                    int32_t* cnt, hipStream_t st);
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,

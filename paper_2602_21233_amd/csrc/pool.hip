@@ -78,7 +78,68 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     return hipGetLastError();
 }
 
+// ln of the mean L2 norm of a key block's value vectors (the value-magnitude term of the
+// output-aware ranking score, Sec. 4.1.2 Fig. "Stem" (c)).  Same access pattern as pool_kernel:
+// D/8 adjacent lanes cover one token, combine their partial sums of squares with lane-xor
+// exchanges, and the token norms of the 16 (or 32) row groups are added through LDS in a fixed
+// order.  A block of all-zero values gives -inf.
+template <int D, int BS>
+__global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv, int NB,
+                                                    float* __restrict__ lvn) {
+    constexpr int TPR = D / 8;
+    constexpr int RPP = 256 / TPR;
+    constexpr int PASSES = BS / RPP;
+    __shared__ float part[RPP];
+    const int blk = blockIdx.x, hy = blockIdx.y;
+    const int b = hy / Hkv, h = hy % Hkv;
+    const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
+    const int tid = threadIdx.x;
+    const int row0 = tid / TPR, chunk = tid % TPR;
+    uint4 raw[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+        raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * vs.t + chunk * 8);
+    float acc = 0.f;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const uint32_t w[4] = {raw[p].x, raw[p].y, raw[p].z, raw[p].w};
+        float sq = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
+            sq = fmaf(lo, lo, sq);
+            sq = fmaf(hi, hi, sq);
+        }
+#pragma unroll
+        for (int off = 1; off < TPR; off <<= 1) sq += __shfl_xor(sq, off);
+        acc += sqrtf(sq);
+    }
+    if (chunk == 0) part[row0] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r) s += part[r];
+        lvn[(int64_t)hy * NB + blk] = logf(s * (1.0f / (float)BS));
+    }
+}
+
+template <int D, int BS>
+hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
+    dim3 grid(d.NB, d.B * d.Hkv);
+    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NB, lvn);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
+    if (d.D == 128 && d.Bs == 128) return launch_vn<128, 128>(d, v, vs, lvn, st);
+    if (d.D == 128 && d.Bs == 64) return launch_vn<128, 64>(d, v, vs, lvn, st);
+    if (d.D == 64 && d.Bs == 128) return launch_vn<64, 128>(d, v, vs, lvn, st);
+    if (d.D == 64 && d.Bs == 64) return launch_vn<64, 64>(d, v, vs, lvn, st);
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        float* qp, float* kp, hipStream_t st) {

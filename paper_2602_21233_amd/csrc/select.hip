@@ -200,8 +200,8 @@ constexpr int kMfmaWaves = 8;
 template <int D, int R, int MAXC>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, int ns, int nl,
-    int k, const int32_t* __restrict__ k_rows, int T, float scale, int32_t* __restrict__ idx,
-    int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
+    int k, const int32_t* __restrict__ k_rows, const float* __restrict__ lvn, int T, float scale,
+    int32_t* __restrict__ idx, int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
     extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
@@ -218,6 +218,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const int Hkv = Hq / G;
     const float* qbase = qp + (int64_t)bh * NB * D;
     const float* kbase = kp + (int64_t)(b * Hkv + h / G) * NB * D;
+    const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NB : nullptr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
@@ -250,6 +251,8 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     if (wave < n_jt) fetch_tile(wave, kraw);
     for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
         const int j = 32 * jt + l32;
+        // output-aware ranking: the key block's ln(value magnitude) joins its score
+        const float lv = lvbase != nullptr ? lvbase[j < NB ? j : NB - 1] : 0.f;
         float4 knext[2 * DS];
         const bool more = jt + kMfmaWaves < n_jt;             // wave-uniform
         if (more) fetch_tile(jt + kMfmaWaves, knext);
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         for (int r = 0; r < 16; ++r) {
             const int mrow = 8 * (r >> 2) + 4 * half + (r & 3);     // row of the 32x32 result held in acc[r]
             if (mrow < R) {
-                const float sc = scale * acc[r];
+                const float sc = lvbase != nullptr ? scale * acc[r] + lv : scale * acc[r];
                 S[mrow * LD + j] = sc;
                 const int i = i0 + mrow;
                 if (scores_out != nullptr && i < NB && j < NB)
@@ -365,33 +368,34 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
 }
 
 template <int D, int R, int MAXC>
-hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, int32_t* idx,
-                       int32_t* cnt, float* scores_or_null, hipStream_t st) {
+hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+                       int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
     hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC>, lds);
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, k_rows, d.T, d.scale, idx, cnt, scores_or_null);
+                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, k_rows, lvn, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, int32_t* idx,
-                         int32_t* cnt, float* scores_or_null, hipStream_t st) {
+hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+                         int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
-    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
-    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
-    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
-    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
-    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
 }
 
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
-                             int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
-    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, idx, cnt, scores_or_null, st);
+                             const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
+                             hipStream_t st) {
+    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
     return hipErrorInvalidValue;
 }
 

@@ -92,6 +92,15 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
                                         1 << 30, None) == -1
     assert lib.sparse_prefill_fused_tpd(ctypes.byref(p), fake, fake, fake, fake, fake, None, fake, None, fake,
                                         1 << 30, None) == -1
+    # output-aware calls: V is required
+    assert lib.sparse_prefill_select_stem(ctypes.byref(p), fake, fake, None, None, fake, fake, None, fake, 1 << 30,
+                                          None) == -1
+    assert lib.sparse_prefill_select_stem(ctypes.byref(p), fake, fake, ctypes.c_void_p(0x10008), None, fake, fake,
+                                          None, fake, 1 << 30, None) == -4
+    assert lib.sparse_prefill_fused_stem(ctypes.byref(p), fake, fake, None, None, fake, None, None, None, fake,
+                                         1 << 30, None) == -1
+    assert lib.sparse_prefill_value_norms(ctypes.byref(p), fake, None, None) == -1
+    assert lib.sparse_prefill_value_norms(ctypes.byref(p), None, fake, None) == -1
     bad = _params()
     bad.q_stride = (ctypes.c_int64 * 3)(0, 1024 * 128, 100)
     assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -4

@@ -193,6 +193,55 @@ def test_fused_tpd_sampled_128k_headline_shape(spa, oracle):
             assert max(vals) - min(vals) < 1e-5, (b, h, i, sorted(flipped))
 
 
+# ------------------------------ output-aware ranking (Stem's Output-Aware Metric)
+@pytest.mark.parametrize("B,Hkv,NB,D,Bs", [(1, 1, 8, 64, 64), (2, 2, 5, 128, 128), (1, 3, 37, 128, 64), (1, 2, 3, 64, 128)])
+def test_value_norms_parity(spa, oracle, B, Hkv, NB, D, Bs):
+    _, _, v = _qkv(B, Hkv, Hkv, NB * Bs, D, 31)
+    v[0, 0, Bs:2 * Bs] = 0 if NB > 1 else v[0, 0, Bs:2 * Bs]       # a block of zero values -> -inf
+    got = spa.value_norms(v.cuda(), Bs).cpu()
+    want = oracle.vnorm(v, Bs).double().log().float()
+    # fp32 sums of 64..128 squares and of 64..128 norms in another order than fp64, then ln: ~1e-6
+    fin = torch.isfinite(want)
+    assert torch.equal(torch.isneginf(got), ~fin)
+    torch.testing.assert_close(got[fin], want[fin], rtol=0, atol=5e-6)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k", [(2, 4, 2, 21, 128, 64, 1, 4, 6), (1, 6, 2, 70, 128, 128, 2, 3, 9),
+                                                      (1, 2, 1, 300, 64, 64, 1, 2, 24)])
+@pytest.mark.parametrize("with_schedule", [False, True])
+def test_select_and_fused_stem(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k, with_schedule):
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 29)
+    # give the value blocks very different magnitudes so that the metric reorders the ranking
+    g = torch.Generator().manual_seed(NB)
+    gain = torch.exp2(torch.randint(-3, 4, (B, Hkv, NB), generator=g).float())
+    v = (v.float().view(B, Hkv, NB, Bs, D) * gain[..., None, None]).view(B, Hkv, NB * Bs, D).to(torch.bfloat16)
+    kr = _schedules(NB, k)["decay"] if with_schedule else None
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    dkr = None if kr is None else kr.cuda()
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, top_k_per_block=dkr, v=dv)
+    o_idx, o_cnt, o_sp, _, _ = oracle.select(q, kk, Bs, ns, nl, k, k_per_row=kr, v=v)
+    sp = sp.cpu()
+    tri = torch.tril(torch.ones(NB, NB, dtype=torch.bool))
+    # score (rtol 1e-4 / atol 1e-5 as in the plain call) plus ln of the value magnitude (5e-6)
+    torch.testing.assert_close(sp[..., tri], o_sp[..., tri], rtol=1e-4, atol=2e-5)
+    assert torch.isneginf(sp[..., ~tri]).all()
+    g_idx, g_cnt = oracle.topk(sp, ns, nl, k, kr)          # the rule on the GPU's own ranking scores: exact
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    assert torch.equal(cnt.cpu(), o_cnt)
+    assert (idx.cpu() == o_idx).float().mean().item() > 0.98
+    p_idx, _ = spa.select(dq, dk, Bs, ns, nl, k, top_k_per_block=dkr)
+    if k > 0 and NB > ns + nl + k:
+        assert not torch.equal(p_idx, idx)                 # the metric does change what is kept
+    out, lse, idx2, cnt2 = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True,
+                                     top_k_per_block=dkr, output_aware=True)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    want, want_lse = oracle.attn(q, kk, v, idx.cpu(), cnt.cpu(), Bs)
+    diff = (out.float().cpu() - want).abs()
+    # values reach 8x the unit scale here, so the absolute bar scales with them
+    assert diff.max().item() <= 8 * MAX_ABS and diff.mean().item() <= 8 * MEAN_ABS
+    assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
+
+
 # ------------------------------------------------------ select end to end
 @pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k", [
     (1, 1, 1, 8, 64, 64, 1, 2, 2), (2, 4, 2, 21, 128, 64, 1, 4, 6), (1, 6, 2, 70, 128, 128, 2, 3, 9),
