@@ -432,3 +432,40 @@ def test_select_max_block_count(spa, oracle):
 def test_fused_sampled_128k_headline_workload(spa, oracle):
     """The benchmark's own configuration (131072 tokens, 32/8 heads, block 128)."""
     _sampled_workload_check(spa, oracle, 3, n_random=4)
+
+
+# ------------------------------------------------------------- HIP graph replay
+def test_fused_call_replays_from_a_hip_graph(spa, oracle):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no synchronisation,
+    no memset), so a fused call can be captured once and replayed; every replay, with eager work
+    and synchronisations between them, must reproduce the eager result bit for bit."""
+    from paper_2602_21233_amd import binding
+    B, Hq, Hkv, NB, D, Bs, ns, nl, k = 1, 4, 2, 40, 128, 128, 1, 2, 6
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 41)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    eager, e_lse, e_idx, e_cnt = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True)
+    p = binding.make_params(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=NB * Bs, head_dim=D, block_size=Bs,
+                            n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=k, q=dq, k=dk, v=dv, out=dq)
+    ws = torch.empty(spa.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(dq)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        spa.fused(dq, dk, dv, Bs, ns, nl, k, workspace=ws, out=out)          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        spa.fused(dq, dk, dv, Bs, ns, nl, k, workspace=ws, out=out)
+    for rep in range(3):
+        out.zero_()
+        ws.random_(0, 255)                                                      # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        other = spa.fused(dq.flip(2).contiguous(), dk, dv, Bs, ns, nl, k)       # eager work between replays
+        torch.cuda.synchronize()
+        assert other.shape == eager.shape
+    want, _ = oracle.attn(q, kk, v, e_idx.cpu(), e_cnt.cpu(), Bs)
+    _assert_attn_close(out, want)
