@@ -147,7 +147,7 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
 }
 
 /* Steps 3+4 (top-k and merge with the static pattern) for every query block:
- *   Static_i = {j < ns, j <= i} U {max(0,i-nl+1) .. i}
+ *   Static_i = {j < ns, j <= i} U {max(0,i-nl+1) .. i}   (A-shape; more below)
  *   C_i      = {0..i} \ Static_i
  *   TopK_i   = the min(k_i,|C_i|) best-ranked members of C_i
  *   Sel_i    = Static_i U TopK_i, written ascending, padded with -1.
@@ -156,14 +156,27 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
  * dependent budget of Token Position-Decay (Sec. 4.1.2, Fig. "Stem" (b)):
  * k_i = k_row[i] clamped to [0, k], one value per query block, shared by all
  * heads.  The paper prints no decay schedule, so the schedule is an input.
+ * Further static patterns of the library (Sec. 4.1.1 names A-shape, Tri-shape,
+ * Dilated and Strided; none is given a formula, readings at block level):
+ *   stride > 0  (Strided): also static are the blocks j with (i - j) % stride == 0,
+ *                          every stride-th block back from the diagonal;
+ *   n_dense > 0 (Tri-shape): the last n_dense query blocks attend to every
+ *                          causal block (A-shape plus a dense bottom strip).
  * sp: [n_rows_total = B*Hq, NB, NB] fp32; idx: [B*Hq, NB, T]; cnt: [B*Hq, NB];
- * T = min(NB, ns+nl+k) also with a schedule (k is its stated maximum). */
+ * T = oracle_row_capacity(...): min(NB, ns+nl+k+floor((NB-1)/stride)), or NB with
+ * a dense strip; with a schedule k is its stated maximum. */
+int64_t oracle_row_capacity(int64_t NB, int64_t ns, int64_t nl, int64_t k, int64_t stride,
+                            int64_t n_dense) {
+    if (n_dense > 0) return NB;
+    int64_t T = ns + nl + k + (stride > 0 ? (NB - 1) / stride : 0);
+    return T < NB ? T : NB;
+}
+
 int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
-                int64_t nl, int64_t k, const int32_t *k_row, int32_t *idx,
-                int32_t *cnt) {
-    if (ns < 0 || nl < 1 || k < 0) return -1;
-    int64_t T = ns + nl + k;
-    if (T > NB) T = NB;
+                int64_t nl, int64_t k, const int32_t *k_row, int64_t stride,
+                int64_t n_dense, int32_t *idx, int32_t *cnt) {
+    if (ns < 0 || nl < 1 || k < 0 || stride < 0 || n_dense < 0) return -1;
+    int64_t T = oracle_row_capacity(NB, ns, nl, k, stride, n_dense);
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int64_t n = 0; n < n_heads_total; ++n)
@@ -180,7 +193,9 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
             for (int64_t j = 0; j <= i; ++j) {
                 int is_sink = j < ns;
                 int is_local = j >= i - nl + 1;
-                sel[j] = (unsigned char)(is_sink || is_local);
+                int is_strided = stride > 0 && (i - j) % stride == 0;
+                int is_dense_row = i >= NB - n_dense;
+                sel[j] = (unsigned char)(is_sink || is_local || is_strided || is_dense_row);
             }
             int64_t k_i = k;
             if (k_row) {

@@ -190,3 +190,54 @@ def test_tpd_lists_are_nested_in_the_budget(oracle):
             z = set(idx_0[0, h, i, :cnt_0[0, h, i]].tolist())
             static = {j for j in range(i + 1) if j < ns or j >= i - nl + 1}
             assert z == static and z <= s <= b
+
+
+# ---- further static patterns of the library (Sec. 4.1.1: Strided, Tri-shape) ----
+
+def _static_set(i, NB, ns, nl, stride, n_dense):
+    """The definition written out independently of the oracle."""
+    if i >= NB - n_dense:
+        return set(range(i + 1))
+    s = {j for j in range(i + 1) if j < ns or j >= i - nl + 1}
+    if stride > 0:
+        s |= {j for j in range(i, -1, -stride)}
+    return s
+
+
+@pytest.mark.parametrize("ns,nl,k,stride,n_dense", [(1, 2, 3, 4, 0), (0, 1, 2, 3, 0), (1, 2, 3, 0, 3), (2, 2, 4, 5, 2),
+                                                   (1, 1, 0, 2, 0), (1, 3, 2, 1, 0)])
+def test_strided_and_trishape_vs_definition(oracle, ns, nl, k, stride, n_dense):
+    g = torch.Generator().manual_seed(7 * stride + n_dense + k)
+    NB = 26
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    idx, cnt = oracle.topk(sp, ns, nl, k, stride=stride, n_dense=n_dense)
+    T = idx.shape[-1]
+    assert T == (NB if n_dense > 0 else min(NB, ns + nl + k + ((NB - 1) // stride if stride else 0)))
+    for h in range(2):
+        for i in range(NB):
+            static = _static_set(i, NB, ns, nl, stride, n_dense)
+            cand = [j for j in range(i + 1) if j not in static]
+            chosen = sorted(cand, key=lambda j: (-float(sp[0, h, i, j]), j))[:k]
+            want = sorted(static | set(chosen))
+            c = int(cnt[0, h, i])
+            assert c == len(want) <= T
+            assert idx[0, h, i, :c].tolist() == want, (h, i)
+            assert all(x == -1 for x in idx[0, h, i, c:].tolist())
+    # stride 1 makes every causal block static: dense causal lists; so does a strip covering all rows
+    if stride == 1:
+        assert all(int(cnt[0, 0, i]) == i + 1 for i in range(NB))
+
+
+def test_trishape_strip_rows_are_dense_and_the_rest_is_the_a_shape(oracle):
+    g = torch.Generator().manual_seed(2)
+    NB, ns, nl, k, n_dense = 20, 1, 2, 3, 4
+    sp = torch.randn((1, 1, NB, NB), generator=g)
+    idx_t, cnt_t = oracle.topk(sp, ns, nl, k, n_dense=n_dense)
+    idx_a, cnt_a = oracle.topk(sp, ns, nl, k)
+    Ta = idx_a.shape[-1]
+    for i in range(NB):
+        if i >= NB - n_dense:
+            assert idx_t[0, 0, i, : i + 1].tolist() == list(range(i + 1)) and int(cnt_t[0, 0, i]) == i + 1
+        else:
+            assert int(cnt_t[0, 0, i]) == int(cnt_a[0, 0, i])
+            assert idx_t[0, 0, i, :Ta].tolist() == idx_a[0, 0, i].tolist()
