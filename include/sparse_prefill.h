@@ -27,12 +27,16 @@
  *     16-byte aligned and every stride a multiple of 8 elements.
  *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - NB = seq_len / block_size query blocks and key blocks.  Row capacity
- *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks).
+ *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks
+ *                 + (stride_blocks > 0 ? (NB - 1) / stride_blocks : 0)),
+ *     or NB when n_dense_q_blocks > 0 (spa_row_capacity returns it).
  *   - block_idx is [batch, n_q_heads, NB, T] int32, contiguous: for query
  *     block i the selected key blocks in ascending order, then -1 padding.
- *     block_cnt is [batch, n_q_heads, NB] int32: the number of valid entries,
- *     always min(i + 1, n_sink + n_local + top_k) (with a budget schedule:
- *     top_k of that row); the last valid entry is always i (the diagonal block).
+ *     block_cnt is [batch, n_q_heads, NB] int32: the number of valid entries:
+ *     the row's static blocks plus min(top_k, causal blocks that are not static)
+ *     (for the plain A-shape that is min(i + 1, n_sink + n_local + top_k); with a
+ *     budget schedule: top_k of that row); the last valid entry is always i (the
+ *     diagonal block).
  *   - Return value: SPA_OK (0) or a negative SPA_ERR_* code.  Arguments are
  *     validated on the host before anything is enqueued, so a failed call has
  *     no effect on the device.  Results are deterministic run to run.
@@ -51,7 +55,7 @@ enum {
     SPA_OK = 0,
     SPA_ERR_NULLPTR = -1,             /* a required pointer is NULL                         */
     SPA_ERR_BAD_SHAPE = -2,           /* unsupported sizes, see spa_params                  */
-    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1 or top_k < 0               */
+    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1, top_k < 0, stride < 0 or n_dense < 0 */
     SPA_ERR_BAD_STRIDE = -4,          /* stride not a multiple of 8 / pointer not 16-B aligned */
     SPA_ERR_WORKSPACE_TOO_SMALL = -5, /* ws_bytes < spa_workspace_bytes()                   */
     SPA_ERR_LAUNCH = -6               /* the HIP runtime rejected a launch                  */
@@ -73,6 +77,12 @@ typedef struct spa_params {
     int64_t k_stride[3];
     int64_t v_stride[3];
     int64_t o_stride[3];
+    /* Further static patterns of the library (Sec. 4.1.1 names A-shape, Tri-shape, Dilated and
+     * Strided; readings at block level).  Both 0 for the plain A-shape.                      */
+    int32_t stride_blocks;    /* >= 0.  s > 0 (Strided): key blocks j with (i - j) % s == 0 are
+                                 static too, every s-th block back from the diagonal          */
+    int32_t n_dense_q_blocks; /* >= 0.  n > 0 (Tri-shape): the last n query blocks attend to
+                                 every causal block                                           */
 } spa_params;
 
 /* Human-readable text for a return code.  Never NULL. */

@@ -21,6 +21,7 @@ int check_shape(const spa_params* p) {
     if (p->seq_len / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
     if ((int64_t)p->batch * p->n_q_heads * (p->seq_len / p->block_size) > 0x7fffffffLL) return SPA_ERR_BAD_SHAPE;
     if (p->n_sink_blocks < 0 || p->n_local_blocks < 1 || p->top_k_blocks < 0) return SPA_ERR_BAD_PATTERN;
+    if (p->stride_blocks < 0 || p->n_dense_q_blocks < 0) return SPA_ERR_BAD_PATTERN;
     if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return SPA_ERR_BAD_SHAPE;
     return SPA_OK;
 }
@@ -129,7 +130,7 @@ const char* spa_strerror(int code) {
         case SPA_OK: return "ok";
         case SPA_ERR_NULLPTR: return "a required pointer is NULL";
         case SPA_ERR_BAD_SHAPE: return "unsupported shape (head_dim and block_size must be 64 or 128, seq_len a multiple of block_size with at most 4096 blocks, n_q_heads a multiple of n_kv_heads)";
-        case SPA_ERR_BAD_PATTERN: return "bad static pattern or budget (need n_sink >= 0, n_local >= 1, top_k >= 0)";
+        case SPA_ERR_BAD_PATTERN: return "bad static pattern or budget (need n_sink >= 0, n_local >= 1, top_k >= 0, stride >= 0, n_dense >= 0)";
         case SPA_ERR_BAD_STRIDE: return "strides must be non-negative multiples of 8 elements, token stride >= head_dim, pointers 16-byte aligned";
         case SPA_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than spa_workspace_bytes()";
         case SPA_ERR_LAUNCH: return "the HIP runtime rejected a kernel launch";

@@ -120,16 +120,17 @@ struct XcdSplit {
     int seq_len;
 };
 
-// Ranges with equal work; row i visits min(i + 1, T) key blocks.
-XcdSplit balanced_split(int NB, int T, int G) {
+// Ranges with equal work; row i visits about row_work(d, i) key blocks.
+XcdSplit balanced_split(const Dims& d) {
+    const int NB = d.NB, G = d.G;
     XcdSplit sp;
     int64_t total = 0;
-    for (int i = 0; i < NB; ++i) total += (i + 1 < T ? i + 1 : T);
+    for (int i = 0; i < NB; ++i) total += row_work(d, i);
     int64_t acc = 0;
     int x = 1;
     sp.first[0] = 0;
     for (int i = 0; i < NB && x < 8; ++i) {
-        acc += (i + 1 < T ? i + 1 : T);
+        acc += row_work(d, i);
         while (x < 8 && acc * 8 >= total * x) sp.first[x++] = i + 1;
     }
     while (x <= 8) sp.first[x++] = NB;
@@ -178,8 +179,10 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const int slot = blockIdx.x >> 3;
     const int head_slot = slot / split.seq_len;           // b * Hkv + kv head
     const int within = slot % split.seq_len;
-    const int i = split.first[xcd] + within / G;
-    if (i >= split.first[xcd + 1]) return;                // the whole workgroup leaves, before any barrier
+    // a range is walked from its last row to its first: where rows differ in length (dense strip,
+    // strided columns, the short first rows) the long ones start first
+    const int i = split.first[xcd + 1] - 1 - within / G;
+    if (i < split.first[xcd]) return;                     // the whole workgroup leaves, before any barrier
     const int g = within % G;
     const int Hkv = Hq / G;
     const int kvh = head_slot % Hkv;
@@ -481,7 +484,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                        (const uint16_t*)v, vs, d.Hkv, d.NB, (uint16_t*)vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const XcdSplit split = balanced_split(d.NB, d.T, d.G);
+    const XcdSplit split = balanced_split(d);
     const int64_t nwg = 8ll * split.seq_len * d.B * d.Hkv;
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,

@@ -41,20 +41,43 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int /*lane*/) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// The static pattern.  Plain A-shape: sink blocks + local window.  EXT adds the strided columns
+// ((i - j) % stride == 0) and the dense bottom strip of the Tri-shape (rows i >= NB - n_dense).
+struct Pattern {
+    int ns, nl, stride, n_dense, NB;
+    float inv_stride;
+};
+inline Pattern pattern_of(const Dims& d) {
+    return Pattern{d.ns, d.nl, d.stride, d.n_dense, d.NB, d.stride > 0 ? 1.0f / (float)d.stride : 0.f};
+}
+inline bool extended(const Dims& d) { return d.stride > 0 || d.n_dense > 0; }
+
+// is key block j (0 <= j <= i) static for query block i?
+template <bool EXT>
+__device__ __forceinline__ bool static_block(const Pattern& pt, int i, int j) {
+    bool s = j < pt.ns || j >= i - pt.nl + 1;
+    if constexpr (EXT) {
+        if (pt.stride > 0) {
+            // i - j < 4096: the nearest integer to (i - j) / stride is exact for multiples
+            const int dist = i - j;
+            const int quot = (int)__builtin_rintf((float)dist * pt.inv_stride);
+            s = s || (quot * pt.stride == dist);
+        }
+        s = s || (i >= pt.NB - pt.n_dense);
+    }
+    return s;
+}
+
 // keys[0 .. 64*ceil((i+1)/64)): rank_key of candidates, 0 for static blocks and padding.
 // Runs on one full wave; all control flow is wave-uniform.
-__device__ void select_row(const uint32_t* keys, int i, int ns, int nl, int k, int T,
+template <bool EXT>
+__device__ void select_row(const uint32_t* keys, int i, const Pattern& pt, int k, int T,
                            int32_t* __restrict__ idx_row, int32_t* __restrict__ cnt_out) {
     const int lane = threadIdx.x & 63;
     const int n = i + 1;
     const int chunks = (n + 63) >> 6;
-    const int lo = i - nl + 1;                                // first local-window block (may be < 0)
-    int n_sink = ns < n ? ns : n;
-    int n_local = nl < n ? nl : n;
-    int first_local = lo > 0 ? lo : 0;
-    int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
-    const int n_static = n_sink + n_local - overlap;
-    const int n_cand = n - n_static;
+    int n_cand = 0;                                           // candidates are the nonzero keys
+    for (int m = 0; m < chunks; ++m) n_cand += __popcll(__ballot(keys[(m << 6) + lane] != 0u));
     const int kk = k < n_cand ? k : n_cand;
 
     uint32_t thr = 0xffffffffu;   // select key > thr ... nothing, by default
@@ -88,8 +111,7 @@ __device__ void select_row(const uint32_t* keys, int i, int ns, int nl, int k, i
     for (int m = 0; m < chunks; ++m) {
         int j = (m << 6) + lane;
         uint32_t key = keys[j];
-        bool in_row = j < n;
-        bool is_static = in_row && (j < ns || j >= lo);
+        bool is_static = j < n && static_block<EXT>(pt, i, j);
         bool is_eq = need_eq > 0 && key == thr && key != 0u;
         uint64_t eq_mask = __ballot(is_eq);
         bool take = is_static || (key != 0u && key > thr) ||
@@ -113,8 +135,9 @@ __device__ __forceinline__ int row_budget(const int32_t* __restrict__ k_rows, in
     return v < 0 ? 0 : (v > k ? k : v);
 }
 
+template <bool EXT>
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
-    const float* __restrict__ scores, int64_t n_rows, int NB, int ns, int nl, int k,
+    const float* __restrict__ scores, int64_t n_rows, int NB, Pattern pt, int k,
     const int32_t* __restrict__ k_rows, int T, int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
     extern __shared__ uint32_t lds_keys[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -124,16 +147,15 @@ __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
     const int padded = ((NB + 63) >> 6) << 6;
     uint32_t* keys = lds_keys + wave * padded;
     const float* srow = scores + row * NB;
-    const int lo = i - nl + 1;
     const int chunks = (i + 64) >> 6;
     for (int m = 0; m < chunks; ++m) {
         int j = (m << 6) + lane;
         uint32_t key = 0u;
-        if (j <= i && !(j < ns || j >= lo)) key = rank_key(srow[j]);
+        if (j <= i && !static_block<EXT>(pt, i, j)) key = rank_key(srow[j]);
         keys[j] = key;
     }
     // each wave reads back only its own slice; LDS ops of one wave are ordered
-    select_row(keys, i, ns, nl, row_budget(k_rows, i, k), T, idx + row * T, cnt + row);
+    select_row<EXT>(keys, i, pt, row_budget(k_rows, i, k), T, idx + row * T, cnt + row);
 }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -197,9 +219,9 @@ __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC],
 
 constexpr int kMfmaWaves = 8;
 
-template <int D, int R, int MAXC>
+template <int D, int R, int MAXC, bool EXT>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
-    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, int ns, int nl,
+    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, Pattern pt,
     int k, const int32_t* __restrict__ k_rows, const float* __restrict__ lvn, int T, float scale,
     int32_t* __restrict__ idx, int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
@@ -297,20 +319,28 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         const int i = i0 + r;
         if (i >= NB) break;                               // wave-uniform
         const int n = i + 1;
-        const int lo = i - nl + 1;
         const float* srow = S + r * LD;
         uint32_t key[MAXC];
 #pragma unroll
         for (int m = 0; m < MAXC; ++m) {
             const int j = (m << 6) + lane;                // < MAXC*64 <= LD: always inside the row
             const uint32_t kv = rank_key(srow[j]);        // columns past the computed tiles hold junk: masked next
-            key[m] = (j <= i && !(j < ns || j >= lo)) ? kv : 0u;
+            key[m] = (j <= i && !static_block<EXT>(pt, i, j)) ? kv : 0u;
         }
-        int n_sink = ns < n ? ns : n;
-        int n_local = nl < n ? nl : n;
-        int first_local = lo > 0 ? lo : 0;
-        int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
-        const int n_cand = n - (n_sink + n_local - overlap);
+        int n_cand;
+        if constexpr (EXT) {                              // count the candidates: no closed form worth having
+            int ncl = 0;
+#pragma unroll
+            for (int m = 0; m < MAXC; ++m) ncl += key[m] != 0u ? 1 : 0;
+            n_cand = wave_sum(ncl);
+        } else {
+            const int lo = i - pt.nl + 1;
+            int n_sink = pt.ns < n ? pt.ns : n;
+            int n_local = pt.nl < n ? pt.nl : n;
+            int first_local = lo > 0 ? lo : 0;
+            int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
+            n_cand = n - (n_sink + n_local - overlap);
+        }
         const int k_i = row_budget(k_rows, i, k);
         const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
@@ -330,7 +360,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
 #pragma nounroll
         for (int m = 0; m < chunks; ++m) {
             const int j = (m << 6) + lane;
-            const bool is_static = j < n && (j < ns || j >= lo);
+            const bool is_static = j < n && static_block<EXT>(pt, i, j);
             const uint32_t kv = (j <= i && !is_static) ? rank_key(srow[j]) : 0u;
             const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
             const uint64_t eq_mask = __ballot(is_eq);
@@ -360,24 +390,36 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
                                    int32_t* cnt, hipStream_t st) {
     int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
     unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
-    hipError_t e = allow_lds((const void*)topk_from_scores_kernel, keys_lds_bytes(d.NB));
+    const void* fn = extended(d) ? (const void*)topk_from_scores_kernel<true> : (const void*)topk_from_scores_kernel<false>;
+    hipError_t e = allow_lds(fn, keys_lds_bytes(d.NB));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(topk_from_scores_kernel, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                       scores, n_rows, d.NB, d.ns, d.nl, d.k, k_rows, d.T, idx, cnt);
+    if (extended(d))
+        hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
+                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, d.T, idx, cnt);
+    else
+        hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
+                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, d.T, idx, cnt);
+    return hipGetLastError();
+}
+
+template <int D, int R, int MAXC, bool EXT>
+hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+                       int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
+    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
+    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT>, lds);
+    if (e != hipSuccess) return e;
+    const int n_tiles = (d.NB + R - 1) / R;
+    dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
+                       d.G, d.NB, n_tiles, pattern_of(d), d.k, k_rows, lvn, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
 template <int D, int R, int MAXC>
 hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
-    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC>, lds);
-    if (e != hipSuccess) return e;
-    const int n_tiles = (d.NB + R - 1) / R;
-    dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
-    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, n_tiles, d.ns, d.nl, d.k, k_rows, lvn, d.T, d.scale, idx, cnt, scores_or_null);
-    return hipGetLastError();
+    if (extended(d)) return launch_mfma_e<D, R, MAXC, true>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma_e<D, R, MAXC, false>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
 }
 
 template <int D>

@@ -242,6 +242,45 @@ def test_select_and_fused_stem(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k, wi
     assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
 
 
+# ------------------------------------ further static patterns (Strided, Tri-shape)
+@pytest.mark.parametrize("NB", [1, 19, 65, 300, 1100])
+@pytest.mark.parametrize("ns,nl,k,stride,n_dense", [(1, 2, 7, 4, 0), (0, 1, 5, 7, 0), (1, 2, 3, 0, 3), (2, 3, 9, 16, 2),
+                                                   (1, 1, 0, 2, 0), (1, 2, 4, 1, 0), (1, 2, 4, 70, 0)])
+def test_topk_static_patterns_bit_exact(spa, oracle, NB, ns, nl, k, stride, n_dense):
+    g = torch.Generator().manual_seed(NB * 3 + stride)
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    sp[0, 1] = torch.randint(0, 3, (NB, NB), generator=g).float()
+    for kr in (None, _schedules(NB, k)["decay"]):
+        want_idx, want_cnt = oracle.topk(sp, ns, nl, k, kr, stride=stride, n_dense=n_dense)
+        idx, cnt = spa.topk_from_scores(sp.cuda(), ns, nl, k, top_k_per_block=None if kr is None else kr.cuda(),
+                                        stride_blocks=stride, n_dense_q_blocks=n_dense)
+        assert idx.shape == want_idx.shape
+        assert torch.equal(cnt.cpu(), want_cnt)
+        assert torch.equal(idx.cpu(), want_idx)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k,stride,n_dense", [
+    (1, 4, 2, 21, 128, 64, 1, 2, 4, 5, 0), (1, 2, 1, 70, 128, 128, 1, 3, 6, 0, 4), (1, 2, 2, 300, 64, 64, 1, 2, 12, 32, 3)])
+def test_select_and_fused_static_patterns(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k, stride, n_dense):
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 37)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, stride_blocks=stride,
+                              n_dense_q_blocks=n_dense)
+    g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k, stride=stride, n_dense=n_dense)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    o_idx, o_cnt, *_ = oracle.select(q, kk, Bs, ns, nl, k, stride=stride, n_dense=n_dense)
+    assert torch.equal(cnt.cpu(), o_cnt)
+    if n_dense:
+        i = NB - 1
+        assert idx[0, 0, i, : i + 1].tolist() == list(range(i + 1))
+    out, lse, idx2, cnt2 = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True,
+                                     stride_blocks=stride, n_dense_q_blocks=n_dense)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    want, want_lse = oracle.attn(q, kk, v, idx.cpu(), cnt.cpu(), Bs)
+    _assert_attn_close(out, want)
+    assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
+
+
 # ------------------------------------------------------ select end to end
 @pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k", [
     (1, 1, 1, 8, 64, 64, 1, 2, 2), (2, 4, 2, 21, 128, 64, 1, 4, 6), (1, 6, 2, 70, 128, 128, 2, 3, 9),
