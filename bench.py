@@ -7,6 +7,12 @@ heads, head_dim 128, block 128, sink 1 + local 4 + top-k 64).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N] [--no-cpu-baseline]
+                    [--variant uniform|tpd|stem|strided|trishape]
+
+--variant (default uniform = the headline) times the same workload under the other selection
+rules the library has: a position-decaying budget (tpd), that plus the output-aware ranking
+score (stem), strided static columns, or a Tri-shape dense strip; FLOPs are then counted on the
+block pairs the lists actually hold.
 """
 import argparse
 import json
@@ -68,6 +74,7 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1200)
+    ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape"), default="uniform")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs with no exchange; "
@@ -92,15 +99,32 @@ def main():
     ws = torch.empty(spa.workspace_bytes(p), dtype=torch.uint8, device="cuda")
     out = torch.empty_like(dq)
 
+    sel_kw, pat_kw = {}, {}
+    if args.variant in ("tpd", "stem"):
+        sel_kw["top_k_per_block"] = inputs.decay_schedule(w).cuda()
+    if args.variant == "stem":
+        sel_kw["v"] = dv
+    if args.variant == "strided":
+        pat_kw = dict(stride_blocks=16)
+    if args.variant == "trishape":
+        pat_kw = dict(n_dense_q_blocks=8)
+    if pat_kw:
+        p = binding.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, seq_len=w.seq_len,
+                                head_dim=w.head_dim, block_size=Bs, n_sink_blocks=ns, n_local_blocks=nl,
+                                top_k_blocks=tk, q=dq, k=dk, v=dv, out=dq, **pat_kw)
+        ws = torch.empty(spa.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+
+    pattern = (ns, nl, tk, pat_kw.get("stride_blocks", 0), pat_kw.get("n_dense_q_blocks", 0))
+
     def step(events=None):
         # the same three launches sparse_prefill_fused makes, split so that the
         # attention kernel can be bracketed by events on its own stream
         if events:
             events[0].record()
-        idx, cnt = spa.select(dq, dk, Bs, ns, nl, tk, workspace=ws)
+        idx, cnt = spa.select(dq, dk, Bs, ns, nl, tk, workspace=ws, **sel_kw, **pat_kw)
         if events:
             events[1].record()
-        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out, workspace=ws)
+        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out, workspace=ws, pattern=pattern)
         if events:
             events[2].record()
         return idx, cnt
@@ -119,7 +143,10 @@ def main():
     att_ms = sorted(e[1].elapsed_time(e[2]) for e in evs)
     sel_avg, att_avg = sum(sel_ms) / len(sel_ms), sum(att_ms) / len(att_ms)
 
-    flops = float(w.attn_flops)
+    # the output-aware score reads V once more (2 bytes per element)
+    select_bytes = w.select_bytes + (2 * w.batch * w.n_kv_heads * w.seq_len * w.head_dim if args.variant == "stem" else 0)
+    visited_pairs = w.visited_pairs if args.variant == "uniform" else int(cnt.sum().item())
+    flops = 4.0 * Bs * Bs * w.head_dim * visited_pairs
     achieved = flops / (att_avg * 1e-3) / 1e12
     result = {
         "metric": "sparse prefill attention effective TFLOP/s on visited blocks (select + attention), 128K tokens",
@@ -130,22 +157,22 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "seq_len": w.seq_len, "head_dim": w.head_dim, "block_size": Bs, "sink_blocks": ns,
-                   "local_blocks": nl, "top_k_blocks": tk, "visited_pairs": w.visited_pairs,
-                   "flops_per_step": flops},
+                   "local_blocks": nl, "top_k_blocks": tk, "visited_pairs": visited_pairs,
+                   "flops_per_step": flops, "variant": args.variant},
         "select_ms": {"avg": sel_avg, "p10": sel_ms[len(sel_ms) // 10], "p50": sel_ms[len(sel_ms) // 2],
                       "p90": sel_ms[(len(sel_ms) * 9) // 10]},
         "attn_ms": {"avg": att_avg, "p10": att_ms[len(att_ms) // 10], "p50": att_ms[len(att_ms) // 2],
                     "p90": att_ms[(len(att_ms) * 9) // 10]},
-        "select_hbm": {"achieved": w.select_bytes / (sel_avg * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                       "frac": w.select_bytes / (sel_avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                       "bytes": w.select_bytes},
+        "select_hbm": {"achieved": select_bytes / (sel_avg * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": select_bytes / (sel_avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                       "bytes": select_bytes},
         "roofline": {"bound": "mfma", "kernel": "attn_d128_kernel<128>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": read_traffic_note("attn_kernel"), "traffic_unit": "bytes/launch",
                      "timed": "events around sparse_prefill_attn on its stream: the attention kernel plus the "
                               "V transpose that precedes it (~0.08 ms)"},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.variant == "uniform":
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, idx.cpu(), cnt.cpu(), args.cpu_rows)
     print(json.dumps(result))
 

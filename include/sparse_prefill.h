@@ -138,6 +138,9 @@ int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_sco
  * block_idx / block_cnt must satisfy the layout rules at the top of this file
  * (ascending, unique, 0 <= entry <= i, last valid entry == i, 1 <= cnt <= T);
  * lists produced by the select calls always do.  They are NOT validated.
+ * Of p this call uses the shape, strides and scale; the pattern fields fix T and
+ * serve as a hint of how uneven the rows are (a dense strip or strided columns
+ * make the library deal the query blocks to the chip's partitions one by one).
  * ws: spa_workspace_bytes() bytes of scratch, 256-byte aligned; its contents
  * need not survive between calls. */
 int sparse_prefill_attn(const spa_params *p, const void *q, const void *k, const void *v,

@@ -216,14 +216,21 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
 
 
 def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
-         workspace=None):
-    """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S])."""
+         workspace=None, pattern=None):
+    """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S]).
+    pattern: optional (n_sink, n_local, top_k, stride_blocks, n_dense_q_blocks) the lists were made
+    with; it only tells the library how uneven the rows are (scheduling hint)."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
     T = block_idx.shape[-1]
     # the pattern fields only fix T here; the lists themselves carry the selection
-    p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out)
+    if pattern is None:
+        p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out)
+    else:
+        ns, nl, tk, stride, n_dense = pattern
+        p = _params_from(q, k, block_size, ns, nl, tk, softmax_scale, v=v, out=out, stride_blocks=stride,
+                         n_dense_q_blocks=n_dense)
     if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
             or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
         raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")

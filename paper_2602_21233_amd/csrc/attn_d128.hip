@@ -113,33 +113,26 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
 // and clusters the VALU work, so the wave stalls on the LDS latency once per MFMA.
 #define SPA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Query-block ranges of the 8 XCDs: XCD x owns blocks first[x] .. first[x+1]-1 of every head;
-// seq_len = workgroups per (head, XCD) in the grid = the longest range times G.
-struct XcdSplit {
-    int first[9];
-    int seq_len;
+// How the query blocks of a head are dealt to the 8 XCDs (workgroup ids go round robin over the
+// XCDs and are dispatched in id order, so the XCDs advance through their sequences in step: what
+// has to be equal is the work of the rows that sit at the same position of the 8 sequences).
+//   - the n_dense rows of a Tri-shape strip (each visits up to NB blocks) are dealt one by one;
+//   - the other rows are dealt in runs of `run` consecutive rows, last row first.  Neighbouring
+//     rows share their local-window blocks in the XCD's L2, which favours runs; rows whose length
+//     varies with the position (budget schedule, strided columns, the short first rows) favour a
+//     fine deal.  run = 8 for the plain A-shape, 1 for the extended patterns.
+// seq_len = workgroups per (head, XCD) in the grid; surplus workgroups exit at once.
+struct RowDeal {
+    int n_dense, run, seq_len;
 };
 
-// Ranges with equal work; row i visits about row_work(d, i) key blocks.
-XcdSplit balanced_split(const Dims& d) {
-    const int NB = d.NB, G = d.G;
-    XcdSplit sp;
-    int64_t total = 0;
-    for (int i = 0; i < NB; ++i) total += row_work(d, i);
-    int64_t acc = 0;
-    int x = 1;
-    sp.first[0] = 0;
-    for (int i = 0; i < NB && x < 8; ++i) {
-        acc += row_work(d, i);
-        while (x < 8 && acc * 8 >= total * x) sp.first[x++] = i + 1;
-    }
-    while (x <= 8) sp.first[x++] = NB;
-    sp.first[8] = NB;
-    int longest = 0;
-    for (int y = 0; y < 8; ++y)
-        if (sp.first[y + 1] - sp.first[y] > longest) longest = sp.first[y + 1] - sp.first[y];
-    sp.seq_len = longest * G;
-    return sp;
+RowDeal deal_rows(const Dims& d) {
+    RowDeal r;
+    r.n_dense = d.n_dense < d.NB ? d.n_dense : d.NB;
+    r.run = (d.stride > 0 || d.n_dense > 0) ? 1 : 8;
+    const int runs = (d.NB - r.n_dense + r.run - 1) / r.run;
+    r.seq_len = (((r.n_dense + 7) >> 3) + ((runs + 7) >> 3) * r.run) * d.G;
+    return r;
 }
 
 template <int N>
@@ -158,7 +151,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale, XcdSplit split) {
+    float scale, RowDeal deal) {
     constexpr int NW = BS / 32;         // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
@@ -168,21 +161,27 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][TILE];   // K sub-tile t in buffer t % 2
     __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][TILE];   // V^T likewise
 
-    // Workgroup -> (b, kv head, query block, head in group).  Workgroup ids go round robin over
-    // the 8 XCDs.  In time, the whole chip works through one KV head after the other, so that the
-    // K and V^T of the current head (tens of MB) stay in the memory-side cache; in space, each XCD
-    // takes a contiguous range of that head's query blocks with all G heads of the group, which
-    // share most of their key blocks in that XCD's L2.  The ranges hold equal numbers of visited
-    // block pairs, not of rows (the first rows of a sequence are short), so the XCDs stay in step;
-    // an XCD whose range has fewer rows than the longest one lets the surplus workgroups exit.
+    // Workgroup -> (b, kv head, query block, head in group).  In time, the whole chip works
+    // through one KV head after the other, so that the K and V^T of the current head (tens of MB)
+    // stay in the memory-side cache; in space, see RowDeal.  All G heads of a group follow each
+    // other, they share most of their key blocks.
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
-    const int head_slot = slot / split.seq_len;           // b * Hkv + kv head
-    const int within = slot % split.seq_len;
-    // a range is walked from its last row to its first: where rows differ in length (dense strip,
-    // strided columns, the short first rows) the long ones start first
-    const int i = split.first[xcd + 1] - 1 - within / G;
-    if (i < split.first[xcd]) return;                     // the whole workgroup leaves, before any barrier
+    const int head_slot = slot / deal.seq_len;            // b * Hkv + kv head
+    const int within = slot % deal.seq_len;
+    const int pos = within / G;                           // position in this XCD's row sequence
+    const int n_single = (deal.n_dense + 7) >> 3;
+    int i;
+    if (pos < n_single) {
+        const int hidx = pos * 8 + xcd;
+        if (hidx >= deal.n_dense) return;                 // the whole workgroup leaves, before any barrier
+        i = NB - 1 - hidx;
+    } else {
+        const int rr = pos - n_single;
+        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
+        if (ridx >= NB - deal.n_dense) return;
+        i = NB - deal.n_dense - 1 - ridx;
+    }
     const int g = within % G;
     const int Hkv = Hq / G;
     const int kvh = head_slot % Hkv;
@@ -484,12 +483,12 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                        (const uint16_t*)v, vs, d.Hkv, d.NB, (uint16_t*)vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const XcdSplit split = balanced_split(d);
-    const int64_t nwg = 8ll * split.seq_len * d.B * d.Hkv;
+    const RowDeal deal = deal_rows(d);
+    const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, split);
+                       d.G, d.NB, d.T, d.S, d.scale, deal);
     return hipGetLastError();
 }
 

@@ -17,13 +17,6 @@ struct Dims {
     float scale;
 };
 
-// Upper bound of the work of query block i in visited key blocks (static blocks + full budget).
-inline int row_work(const Dims& d, int i) {
-    if (i >= d.NB - d.n_dense) return i + 1;
-    int64_t w = (int64_t)d.ns + d.nl + d.k + (d.stride > 0 ? i / d.stride : 0);
-    return (int)(w < i + 1 ? w : i + 1);
-}
-
 inline Dims dims_of(const spa_params& p) {
     Dims d;
     d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
