@@ -162,6 +162,12 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
  *                          every stride-th block back from the diagonal;
  *   n_dense > 0 (Tri-shape): the last n_dense query blocks attend to every
  *                          causal block (A-shape plus a dense bottom strip).
+ * Per-head configuration (Sec. 4.1.1, "Decoupling Sparse Kernels from Model
+ * Architectures": the settings are metadata applied to specific heads): with
+ * head_pattern != NULL query head h = n % Hq uses its own triple
+ *   (ns_h, nl_h, k_h) = head_pattern[3h .. 3h+2] clamped to [0,ns], [1,nl], [0,k];
+ * ns, nl, k are then the stated maxima (they fix T); a budget schedule is
+ * capped per head: k_{i,h} = min(k_row[i] clamped to [0,k], k_h).
  * sp: [n_rows_total = B*Hq, NB, NB] fp32; idx: [B*Hq, NB, T]; cnt: [B*Hq, NB];
  * T = oracle_row_capacity(...): min(NB, ns+nl+k+floor((NB-1)/stride)), or NB with
  * a dense strip; with a schedule k is its stated maximum. */
@@ -172,17 +178,29 @@ int64_t oracle_row_capacity(int64_t NB, int64_t ns, int64_t nl, int64_t k, int64
     return T < NB ? T : NB;
 }
 
-int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
-                int64_t nl, int64_t k, const int32_t *k_row, int64_t stride,
-                int64_t n_dense, int32_t *idx, int32_t *cnt) {
-    if (ns < 0 || nl < 1 || k < 0 || stride < 0 || n_dense < 0) return -1;
-    int64_t T = oracle_row_capacity(NB, ns, nl, k, stride, n_dense);
+static int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_max,
+                int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
+                int64_t n_dense, const int32_t *head_pattern, int64_t Hq, int32_t *idx,
+                int32_t *cnt) {
+    if (ns_max < 0 || nl_max < 1 || k_max < 0 || stride < 0 || n_dense < 0) return -1;
+    if (head_pattern && Hq < 1) return -1;
+    const int64_t ns0 = ns_max, nl0 = nl_max, k0 = k_max;
+    int64_t T = oracle_row_capacity(NB, ns0, nl0, k0, stride, n_dense);
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int64_t n = 0; n < n_heads_total; ++n)
         for (int64_t i = 0; i < NB; ++i) {
             const float *srow = sp + (n * NB + i) * NB;
             int32_t *orow = idx + (n * NB + i) * T;
+            int64_t ns = ns0, nl = nl0, k = k0;
+            if (head_pattern) {
+                const int32_t *hp = head_pattern + 3 * (n % Hq);
+                ns = clamp64(hp[0], 0, ns0);
+                nl = clamp64(hp[1], 1, nl0);
+                k = clamp64(hp[2], 0, k0);
+            }
             /* state[j]: 0 = candidate, 1 = selected */
             unsigned char *sel = (unsigned char *)calloc((size_t)NB, 1);
             if (!sel) {
@@ -199,8 +217,7 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns,
             }
             int64_t k_i = k;
             if (k_row) {
-                k_i = k_row[i];
-                if (k_i < 0) k_i = 0;
+                k_i = clamp64(k_row[i], 0, k0);
                 if (k_i > k) k_i = k;
             }
             for (int64_t pick = 0; pick < k_i; ++pick) {

@@ -241,3 +241,36 @@ def test_trishape_strip_rows_are_dense_and_the_rest_is_the_a_shape(oracle):
         else:
             assert int(cnt_t[0, 0, i]) == int(cnt_a[0, 0, i])
             assert idx_t[0, 0, i, :Ta].tolist() == idx_a[0, 0, i].tolist()
+
+
+# ---- per-head configuration (Sec. 4.1.1: settings applied to specific heads) ----
+
+def test_head_pattern_equals_per_head_uniform_calls(oracle):
+    g = torch.Generator().manual_seed(12)
+    NB, Hq = 22, 4
+    sp = torch.randn((2, Hq, NB, NB), generator=g)
+    hp = torch.tensor([[1, 2, 5], [0, 1, 0], [2, 3, 2], [9, 9, 9]], dtype=torch.int32)   # last row: clamped to the maxima
+    ns, nl, k = 2, 3, 5
+    idx, cnt = oracle.topk(sp, ns, nl, k, head_pattern=hp)
+    T = idx.shape[-1]
+    assert T == min(NB, ns + nl + k)
+    eff = [(1, 2, 5), (0, 1, 0), (2, 3, 2), (2, 3, 5)]
+    for h, (a, b, c) in enumerate(eff):
+        i1, c1 = oracle.topk(sp[:, h:h + 1].contiguous(), a, b, c)
+        T1 = i1.shape[-1]
+        assert torch.equal(cnt[:, h], c1[:, 0])
+        assert torch.equal(idx[:, h, :, :T1], i1[:, 0])
+        assert (idx[:, h, :, T1:] == -1).all()
+
+
+def test_head_pattern_caps_the_budget_schedule(oracle):
+    g = torch.Generator().manual_seed(13)
+    NB, Hq, ns, nl, k = 18, 2, 1, 2, 6
+    sp = torch.randn((1, Hq, NB, NB), generator=g)
+    kr = _decaying(NB, 6, 1)
+    hp = torch.tensor([[1, 2, 6], [1, 2, 3]], dtype=torch.int32)
+    idx, cnt = oracle.topk(sp, ns, nl, k, kr, head_pattern=hp)
+    for h, kh in enumerate((6, 3)):
+        for i in range(NB):
+            want = brute_force_row(sp[0, h, i].numpy(), i, ns, nl, min(int(kr[i]), kh))
+            assert idx[0, h, i, : cnt[0, h, i]].tolist() == want
