@@ -210,6 +210,40 @@ int sparse_prefill_fused_stem(const spa_params *p, const void *q, const void *k,
                               int32_t *block_cnt_or_null, void *ws, size_t ws_bytes,
                               void *hip_stream);
 
+/* ---- General form: every selection option in one place ---------------------------------------
+ * The paper's framework applies its sparsity settings as metadata to specific layers or heads
+ * (Sec. 4.1.1, "Decoupling Sparse Kernels from Model Architectures").  spa_select_opts carries
+ * the per-call metadata; the struct is read on the HOST, its pointers are DEVICE pointers, any of
+ * them may be NULL, and a NULL opts means the plain call.
+ *   top_k_per_block  [NB] int32: Token Position-Decay schedule, as in the _tpd calls.
+ *   v                V in the layout of p->v_stride: switches the ranking to the output-aware
+ *                    score of the _stem calls (for the fused call only "non-NULL" matters, the
+ *                    values read are those of its own v argument).
+ *   head_pattern     [n_q_heads][3] int32 = (n_sink, n_local, top_k) of each query head, clamped
+ *                    in the kernels to [0, p->n_sink_blocks], [1, p->n_local_blocks],
+ *                    [0, p->top_k_blocks]: the spa_params values are then the maxima and fix the row
+ *                    capacity.  With a schedule, head h draws min(schedule[i], top_k of h) blocks.
+ * The _tpd and _stem calls above are these calls with the corresponding fields set. */
+typedef struct spa_select_opts {
+    const int32_t *top_k_per_block;
+    const void *v;
+    const int32_t *head_pattern;
+} spa_select_opts;
+
+int sparse_prefill_select_ex(const spa_params *p, const void *q, const void *k,
+                             const spa_select_opts *opts, int32_t *block_idx, int32_t *block_cnt,
+                             float *ranking_scores_or_null, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
+int sparse_prefill_topk_from_scores_ex(const spa_params *p, const float *scores,
+                                       const spa_select_opts *opts, int32_t *block_idx,
+                                       int32_t *block_cnt, void *hip_stream);
+
+int sparse_prefill_fused_ex(const spa_params *p, const void *q, const void *k, const void *v,
+                            const spa_select_opts *opts, void *out, float *lse_or_null,
+                            int32_t *block_idx_or_null, int32_t *block_cnt_or_null, void *ws,
+                            size_t ws_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

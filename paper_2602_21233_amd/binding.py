@@ -15,7 +15,8 @@ EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_pr
            "sparse_prefill_select", "sparse_prefill_topk_from_scores", "sparse_prefill_attn",
            "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
            "sparse_prefill_fused_tpd", "sparse_prefill_value_norms", "sparse_prefill_select_stem",
-           "sparse_prefill_fused_stem")
+           "sparse_prefill_fused_stem", "sparse_prefill_select_ex", "sparse_prefill_topk_from_scores_ex",
+           "sparse_prefill_fused_ex")
 
 
 class SpaError(RuntimeError):
@@ -32,6 +33,10 @@ class SpaParams(ctypes.Structure):
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
                 ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32)]
+
+
+class SpaSelectOpts(ctypes.Structure):
+    _fields_ = [("top_k_per_block", ctypes.c_void_p), ("v", ctypes.c_void_p), ("head_pattern", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -62,6 +67,10 @@ def load_library():
     lib.sparse_prefill_value_norms.argtypes = [pp, vp, vp, vp]
     lib.sparse_prefill_select_stem.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_fused_stem.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    po = ctypes.POINTER(SpaSelectOpts)
+    lib.sparse_prefill_select_ex.argtypes = [pp, vp, vp, po, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_topk_from_scores_ex.argtypes = [pp, vp, po, vp, vp, vp]
+    lib.sparse_prefill_fused_ex.argtypes = [pp, vp, vp, vp, po, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -123,6 +132,20 @@ def _schedule(top_k_per_block, n_blocks, device):
     return t
 
 
+def _head_pattern(hp, n_q_heads):
+    if hp.dtype != torch.int32 or not hp.is_cuda or not hp.is_contiguous() or tuple(hp.shape) != (n_q_heads, 3):
+        raise TypeError("head_pattern must be a contiguous int32 tensor [n_q_heads, 3] on the GPU")
+    return hp
+
+
+def _opts(top_k_per_block=None, v=None, head_pattern=None) -> SpaSelectOpts:
+    o = SpaSelectOpts()
+    o.top_k_per_block = None if top_k_per_block is None else top_k_per_block.data_ptr()
+    o.v = None if v is None else v.data_ptr()
+    o.head_pattern = None if head_pattern is None else head_pattern.data_ptr()
+    return o
+
+
 def row_capacity(p: SpaParams) -> int:
     t = ctypes.c_int32()
     _check(load_library().spa_row_capacity(ctypes.byref(p), ctypes.byref(t)))
@@ -164,7 +187,7 @@ def value_norms(v, block_size):
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
            return_scores=False, workspace=None, top_k_per_block=None, v=None, stride_blocks=0,
-           n_dense_q_blocks=0):
+           n_dense_q_blocks=0, head_pattern=None):
     """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
     tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
     without a schedule).  Returns (block_idx, block_cnt[, scores])."""
@@ -177,7 +200,12 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
     sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if v is not None:
+    if head_pattern is not None:
+        kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
+        o = _opts(kr, v, _head_pattern(head_pattern, Hq))
+        _check(load_library().sparse_prefill_select_ex(ctypes.byref(p), _ptr(q), _ptr(k), ctypes.byref(o), _ptr(idx),
+                                                       _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
+    elif v is not None:
         _dev_bf16(v)
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
         _check(load_library().sparse_prefill_select_stem(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
@@ -194,7 +222,7 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
 
 
 def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_per_block=None,
-                     stride_blocks=0, n_dense_q_blocks=0):
+                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None):
     """sparse_prefill_topk_from_scores (…_tpd with a schedule) on [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
         raise TypeError("expected contiguous fp32 scores on the GPU")
@@ -205,7 +233,12 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
     T = row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
-    if top_k_per_block is None:
+    if head_pattern is not None:
+        kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, scores.device)
+        o = _opts(kr, None, _head_pattern(head_pattern, Hq))
+        _check(load_library().sparse_prefill_topk_from_scores_ex(ctypes.byref(p), _ptr(scores), ctypes.byref(o),
+                                                                 _ptr(idx), _ptr(cnt), _stream(scores)))
+    elif top_k_per_block is None:
         _check(load_library().sparse_prefill_topk_from_scores(ctypes.byref(p), _ptr(scores), _ptr(idx), _ptr(cnt),
                                                               _stream(scores)))
     else:
@@ -244,7 +277,7 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
           return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
-          output_aware=False, stride_blocks=0, n_dense_q_blocks=0):
+          output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None):
     """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
     current stream."""
     _dev_bf16(q, k, v)
@@ -257,7 +290,13 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if output_aware:
+    if head_pattern is not None:
+        kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
+        o = _opts(kr, v if output_aware else None, _head_pattern(head_pattern, Hq))
+        _check(load_library().sparse_prefill_fused_ex(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ctypes.byref(o),
+                                                      _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),
+                                                      ws.numel(), _stream(q)))
+    elif output_aware:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
         _check(load_library().sparse_prefill_fused_stem(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
                                                         _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),

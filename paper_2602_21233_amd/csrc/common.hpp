@@ -39,11 +39,12 @@ hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, 
 hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st);
 // k_rows: optional device array of NB per-query-block budgets (clamped to [0, d.k] in the kernel).
 // lvn: optional; added to the score of key block j (output-aware ranking).
+// head_pattern: optional device array [Hq][3] = (n_sink, n_local, top_k) per query head.
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
-                             const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
-                             hipStream_t st);
-hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows, int32_t* idx,
-                                   int32_t* cnt, hipStream_t st);
+                             const int32_t* head_pattern, const float* lvn, int32_t* idx, int32_t* cnt,
+                             float* scores_or_null, hipStream_t st);
+hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows,
+                                   const int32_t* head_pattern, int32_t* idx, int32_t* cnt, hipStream_t st);
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
                        void* out, Strides os, float* lse, hipStream_t st);

@@ -135,15 +135,28 @@ __device__ __forceinline__ int row_budget(const int32_t* __restrict__ k_rows, in
     return v < 0 ? 0 : (v > k ? k : v);
 }
 
+// Per-head configuration: head h replaces (n_sink, n_local, top_k) by its own triple, clamped to
+// [0, ns], [1, nl], [0, k] of the call (which are then the maxima that fix the row capacity).
+__device__ __forceinline__ void head_config(const int32_t* __restrict__ head_pattern, int h, Pattern& pt, int& k) {
+    if (head_pattern == nullptr) return;
+    const int32_t* hp = head_pattern + 3 * h;
+    const int a = hp[0], b = hp[1], c = hp[2];
+    pt.ns = a < 0 ? 0 : (a > pt.ns ? pt.ns : a);
+    pt.nl = b < 1 ? 1 : (b > pt.nl ? pt.nl : b);
+    k = c < 0 ? 0 : (c > k ? k : c);
+}
+
 template <bool EXT>
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
     const float* __restrict__ scores, int64_t n_rows, int NB, Pattern pt, int k,
-    const int32_t* __restrict__ k_rows, int T, int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+    const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern, int Hq, int T,
+    int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
     extern __shared__ uint32_t lds_keys[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
     if (row >= n_rows) return;                               // whole wave leaves together
     const int i = (int)(row % NB);
+    head_config(head_pattern, (int)((row / NB) % Hq), pt, k);
     const int padded = ((NB + 63) >> 6) << 6;
     uint32_t* keys = lds_keys + wave * padded;
     const float* srow = scores + row * NB;
@@ -222,8 +235,9 @@ constexpr int kMfmaWaves = 8;
 template <int D, int R, int MAXC, bool EXT>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, Pattern pt,
-    int k, const int32_t* __restrict__ k_rows, const float* __restrict__ lvn, int T, float scale,
-    int32_t* __restrict__ idx, int32_t* __restrict__ cnt, float* __restrict__ scores_out) {
+    int k, const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern,
+    const float* __restrict__ lvn, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
+    float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
     extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
@@ -314,6 +328,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     __syncthreads();
 
     // ---- phase 2 ---------------------------------------------------------------------
+    head_config(head_pattern, h, pt, k);
 #pragma nounroll
     for (int r = wave; r < R; r += kMfmaWaves) {
         const int i = i0 + r;
@@ -386,8 +401,8 @@ size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) 
 
 }  // namespace
 
-hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows, int32_t* idx,
-                                   int32_t* cnt, hipStream_t st) {
+hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows,
+                                   const int32_t* head_pattern, int32_t* idx, int32_t* cnt, hipStream_t st) {
     int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
     unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
     const void* fn = extended(d) ? (const void*)topk_from_scores_kernel<true> : (const void*)topk_from_scores_kernel<false>;
@@ -395,15 +410,15 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     if (e != hipSuccess) return e;
     if (extended(d))
         hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, d.T, idx, cnt);
+                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
     else
         hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, d.T, idx, cnt);
+                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
     return hipGetLastError();
 }
 
 template <int D, int R, int MAXC, bool EXT>
-hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
     hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT>, lds);
@@ -411,33 +426,33 @@ hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const 
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, n_tiles, pattern_of(d), d.k, k_rows, lvn, d.T, d.scale, idx, cnt, scores_or_null);
+                       d.G, d.NB, n_tiles, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
 template <int D, int R, int MAXC>
-hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    if (extended(d)) return launch_mfma_e<D, R, MAXC, true>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma_e<D, R, MAXC, false>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (extended(d)) return launch_mfma_e<D, R, MAXC, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma_e<D, R, MAXC, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 
 template <int D>
-hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const float* lvn,
+hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                          int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
-    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
-                             const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
+                             const int32_t* head_pattern, const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
                              hipStream_t st) {
-    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
-    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, lvn, idx, cnt, scores_or_null, st);
+    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
     return hipErrorInvalidValue;
 }
 

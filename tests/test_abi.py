@@ -105,6 +105,18 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
                                          1 << 30, None) == -1
     assert lib.sparse_prefill_value_norms(ctypes.byref(p), fake, None, None) == -1
     assert lib.sparse_prefill_value_norms(ctypes.byref(p), None, fake, None) == -1
+    # general form: a NULL opts is the plain call, argument checks are unchanged
+    from paper_2602_21233_amd import binding
+    o = binding.SpaSelectOpts()
+    assert lib.sparse_prefill_select_ex(ctypes.byref(p), fake, fake, None, fake, fake, None, None, 1 << 30, None) == -1
+    assert lib.sparse_prefill_select_ex(ctypes.byref(p), fake, fake, ctypes.byref(o), fake, fake, None, fake, 16,
+                                        None) == -5
+    o.v = 0x10008
+    assert lib.sparse_prefill_select_ex(ctypes.byref(p), fake, fake, ctypes.byref(o), fake, fake, None, fake,
+                                        1 << 30, None) == -4
+    assert lib.sparse_prefill_topk_from_scores_ex(ctypes.byref(p), None, None, fake, fake, None) == -1
+    assert lib.sparse_prefill_fused_ex(ctypes.byref(p), fake, fake, fake, None, fake, None, fake, None, fake,
+                                       1 << 30, None) == -1
     bad = _params()
     bad.q_stride = (ctypes.c_int64 * 3)(0, 1024 * 128, 100)
     assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -4

@@ -281,6 +281,45 @@ def test_select_and_fused_static_patterns(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns
     assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
 
 
+# --------------------------------------- per-head configuration (metadata per head)
+@pytest.mark.parametrize("NB", [19, 130, 600])
+def test_topk_head_pattern_bit_exact(spa, oracle, NB):
+    g = torch.Generator().manual_seed(NB)
+    Hq, ns, nl, k = 4, 2, 3, 12
+    sp = torch.randn((2, Hq, NB, NB), generator=g)
+    hp = torch.tensor([[1, 2, 12], [0, 1, 0], [2, 3, 5], [7, 0, 99]], dtype=torch.int32)     # last: clamped
+    for kr in (None, _schedules(NB, k)["decay"]):
+        for stride in (0, 5):
+            want_idx, want_cnt = oracle.topk(sp, ns, nl, k, kr, stride=stride, head_pattern=hp)
+            idx, cnt = spa.topk_from_scores(sp.cuda(), ns, nl, k, top_k_per_block=None if kr is None else kr.cuda(),
+                                            stride_blocks=stride, head_pattern=hp.cuda())
+            assert torch.equal(cnt.cpu(), want_cnt)
+            assert torch.equal(idx.cpu(), want_idx)
+
+
+def test_select_and_fused_head_pattern(spa, oracle):
+    B, Hq, Hkv, NB, D, Bs, ns, nl, k = 1, 4, 2, 70, 128, 128, 2, 3, 9
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 43)
+    hp = torch.tensor([[1, 1, 9], [2, 3, 0], [0, 2, 4], [2, 3, 9]], dtype=torch.int32)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    kr = _schedules(NB, k)["decay"]
+    for sched, aware in ((None, False), (kr, True)):
+        dkr = None if sched is None else sched.cuda()
+        idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, top_k_per_block=dkr,
+                                  v=dv if aware else None, head_pattern=hp.cuda())
+        g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k, sched, head_pattern=hp)
+        assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+        o_idx, o_cnt, *_ = oracle.select(q, kk, Bs, ns, nl, k, k_per_row=sched, v=v if aware else None,
+                                         head_pattern=hp)
+        assert torch.equal(cnt.cpu(), o_cnt)
+        out, lse, idx2, cnt2 = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True,
+                                         top_k_per_block=dkr, output_aware=aware, head_pattern=hp.cuda())
+        assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+        want, want_lse = oracle.attn(q, kk, v, idx.cpu(), cnt.cpu(), Bs)
+        _assert_attn_close(out, want)
+        assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
+
+
 # ------------------------------------------------------ select end to end
 @pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k", [
     (1, 1, 1, 8, 64, 64, 1, 2, 2), (2, 4, 2, 21, 128, 64, 1, 4, 6), (1, 6, 2, 70, 128, 128, 2, 3, 9),
