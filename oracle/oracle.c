@@ -160,6 +160,8 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
  * Dilated and Strided; none is given a formula, readings at block level):
  *   stride > 0  (Strided): also static are the blocks j with (i - j) % stride == 0,
  *                          every stride-th block back from the diagonal;
+ *   reach > 0   (Dilated): ... but only those closer than reach blocks, i - j < reach:
+ *                          a local window of reach/stride blocks with gaps (dilation = stride);
  *   n_dense > 0 (Tri-shape): the last n_dense query blocks attend to every
  *                          causal block (A-shape plus a dense bottom strip).
  * Per-head configuration (Sec. 4.1.1, "Decoupling Sparse Kernels from Model
@@ -172,9 +174,11 @@ static int ranks_before(float sa, int64_t ja, float sb, int64_t jb) {
  * T = oracle_row_capacity(...): min(NB, ns+nl+k+floor((NB-1)/stride)), or NB with
  * a dense strip; with a schedule k is its stated maximum. */
 int64_t oracle_row_capacity(int64_t NB, int64_t ns, int64_t nl, int64_t k, int64_t stride,
-                            int64_t n_dense) {
+                            int64_t n_dense, int64_t reach) {
     if (n_dense > 0) return NB;
-    int64_t T = ns + nl + k + (stride > 0 ? (NB - 1) / stride : 0);
+    int64_t far = NB - 1;                       /* largest distance i - j of a strided block */
+    if (reach > 0 && reach - 1 < far) far = reach - 1;
+    int64_t T = ns + nl + k + (stride > 0 ? far / stride : 0);
     return T < NB ? T : NB;
 }
 
@@ -182,12 +186,12 @@ static int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo :
 
 int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_max,
                 int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
-                int64_t n_dense, const int32_t *head_pattern, int64_t Hq, int32_t *idx,
-                int32_t *cnt) {
-    if (ns_max < 0 || nl_max < 1 || k_max < 0 || stride < 0 || n_dense < 0) return -1;
+                int64_t n_dense, int64_t reach, const int32_t *head_pattern, int64_t Hq,
+                int32_t *idx, int32_t *cnt) {
+    if (ns_max < 0 || nl_max < 1 || k_max < 0 || stride < 0 || n_dense < 0 || reach < 0) return -1;
     if (head_pattern && Hq < 1) return -1;
     const int64_t ns0 = ns_max, nl0 = nl_max, k0 = k_max;
-    int64_t T = oracle_row_capacity(NB, ns0, nl0, k0, stride, n_dense);
+    int64_t T = oracle_row_capacity(NB, ns0, nl0, k0, stride, n_dense, reach);
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int64_t n = 0; n < n_heads_total; ++n)
@@ -211,7 +215,7 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
             for (int64_t j = 0; j <= i; ++j) {
                 int is_sink = j < ns;
                 int is_local = j >= i - nl + 1;
-                int is_strided = stride > 0 && (i - j) % stride == 0;
+                int is_strided = stride > 0 && (i - j) % stride == 0 && (reach == 0 || i - j < reach);
                 int is_dense_row = i >= NB - n_dense;
                 sel[j] = (unsigned char)(is_sink || is_local || is_strided || is_dense_row);
             }

@@ -36,8 +36,8 @@ def _load():
         i64, f32, vp = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
         lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, f32, vp]
-        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, i64, i64, vp, i64, vp, vp]
-        lib.oracle_row_capacity.argtypes = [i64] * 6
+        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, i64, i64, i64, vp, i64, vp, vp]
+        lib.oracle_row_capacity.argtypes = [i64] * 7
         lib.oracle_row_capacity.restype = ctypes.c_int64
         lib.oracle_vnorm.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_scores_oam.argtypes = [vp, vp, i64, i64, i64, i64]
@@ -59,8 +59,8 @@ def default_scale(head_dim: int) -> float:
     return float(np.float32(1.0) / np.sqrt(np.float32(head_dim)))
 
 
-def row_capacity(n_blocks: int, ns: int, nl: int, k: int, stride: int = 0, n_dense: int = 0) -> int:
-    return int(_load().oracle_row_capacity(n_blocks, ns, nl, k, stride, n_dense))
+def row_capacity(n_blocks: int, ns: int, nl: int, k: int, stride: int = 0, n_dense: int = 0, reach: int = 0) -> int:
+    return int(_load().oracle_row_capacity(n_blocks, ns, nl, k, stride, n_dense, reach))
 
 
 def _bits(x: torch.Tensor) -> torch.Tensor:
@@ -115,7 +115,7 @@ def scores_oam(sp: torch.Tensor, vn: torch.Tensor) -> torch.Tensor:
 
 
 def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | None = None,
-         stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None):
+         stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0):
     """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32.
     k_per_row: optional [NB] int32 position-dependent budget (clamped to [0, k]).
     stride / n_dense: strided static columns and the dense bottom strip of the Tri-shape.
@@ -124,7 +124,7 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
     B, Hq, NB, _ = sp.shape
     sp = sp.contiguous()
     assert sp.dtype == torch.float32
-    T = row_capacity(NB, ns, nl, k, stride, n_dense)
+    T = row_capacity(NB, ns, nl, k, stride, n_dense, reach)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32)
     kr_ptr = None
@@ -137,14 +137,14 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
         head_pattern = head_pattern.to(torch.int32).contiguous()
         assert head_pattern.shape == (Hq, 3) and head_pattern.device.type == "cpu"
         hp_ptr = head_pattern.data_ptr()
-    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, kr_ptr, stride, n_dense, hp_ptr, Hq,
+    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr, Hq,
                                idx.data_ptr(), cnt.data_ptr()), "topk")
     return idx, cnt
 
 
 def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
            scale: float | None = None, k_per_row: torch.Tensor | None = None, v: torch.Tensor | None = None,
-           stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None):
+           stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0):
     """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp).  With v the ranking score is
     the output-aware one (scores_oam) and sp is that score."""
     scale = default_scale(q.shape[-1]) if scale is None else scale
@@ -152,7 +152,7 @@ def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, 
     sp = scores(qp, kp, scale)
     if v is not None:
         sp = scores_oam(sp, vnorm(v, block_size))
-    idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row, stride, n_dense, head_pattern)
+    idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row, stride, n_dense, head_pattern, reach)
     return idx, cnt, sp, qp, kp
 
 

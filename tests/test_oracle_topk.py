@@ -194,14 +194,30 @@ def test_tpd_lists_are_nested_in_the_budget(oracle):
 
 # ---- further static patterns of the library (Sec. 4.1.1: Strided, Tri-shape) ----
 
-def _static_set(i, NB, ns, nl, stride, n_dense):
+def _static_set(i, NB, ns, nl, stride, n_dense, reach=0):
     """The definition written out independently of the oracle."""
     if i >= NB - n_dense:
         return set(range(i + 1))
     s = {j for j in range(i + 1) if j < ns or j >= i - nl + 1}
     if stride > 0:
-        s |= {j for j in range(i, -1, -stride)}
+        s |= {j for j in range(i, -1, -stride) if reach == 0 or i - j < reach}
     return s
+
+
+@pytest.mark.parametrize("stride,reach", [(3, 10), (2, 2), (4, 100), (5, 11), (1, 6)])
+def test_dilated_window_vs_definition(oracle, stride, reach):
+    g = torch.Generator().manual_seed(stride * 10 + reach)
+    NB, ns, nl, k = 31, 1, 2, 3
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    idx, cnt = oracle.topk(sp, ns, nl, k, stride=stride, reach=reach)
+    assert idx.shape[-1] == min(NB, ns + nl + k + min(NB - 1, reach - 1) // stride)
+    for h in range(2):
+        for i in range(NB):
+            static = _static_set(i, NB, ns, nl, stride, 0, reach)
+            cand = [j for j in range(i + 1) if j not in static]
+            chosen = sorted(cand, key=lambda j: (-float(sp[0, h, i, j]), j))[:k]
+            c = int(cnt[0, h, i])
+            assert idx[0, h, i, :c].tolist() == sorted(static | set(chosen)), (h, i)
 
 
 @pytest.mark.parametrize("ns,nl,k,stride,n_dense", [(1, 2, 3, 4, 0), (0, 1, 2, 3, 0), (1, 2, 3, 0, 3), (2, 2, 4, 5, 2),
