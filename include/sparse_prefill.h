@@ -28,7 +28,8 @@
  *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - NB = seq_len / block_size query blocks and key blocks.  Row capacity
  *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks
- *                 + (stride_blocks > 0 ? (NB - 1) / stride_blocks : 0)),
+ *                 + (stride_blocks > 0 ? min(NB - 1, reach - 1) / stride_blocks : 0)),
+ *     reach = stride_reach_blocks or NB when that is 0,
  *     or NB when n_dense_q_blocks > 0 (spa_row_capacity returns it).
  *   - block_idx is [batch, n_q_heads, NB, T] int32, contiguous: for query
  *     block i the selected key blocks in ascending order, then -1 padding.
@@ -55,7 +56,7 @@ enum {
     SPA_OK = 0,
     SPA_ERR_NULLPTR = -1,             /* a required pointer is NULL                         */
     SPA_ERR_BAD_SHAPE = -2,           /* unsupported sizes, see spa_params                  */
-    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1, top_k < 0, stride < 0 or n_dense < 0 */
+    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1, or a negative top_k, stride, reach or n_dense */
     SPA_ERR_BAD_STRIDE = -4,          /* stride not a multiple of 8 / pointer not 16-B aligned */
     SPA_ERR_WORKSPACE_TOO_SMALL = -5, /* ws_bytes < spa_workspace_bytes()                   */
     SPA_ERR_LAUNCH = -6               /* the HIP runtime rejected a launch                  */
@@ -83,6 +84,9 @@ typedef struct spa_params {
                                  static too, every s-th block back from the diagonal          */
     int32_t n_dense_q_blocks; /* >= 0.  n > 0 (Tri-shape): the last n query blocks attend to
                                  every causal block                                           */
+    int32_t stride_reach_blocks; /* >= 0.  r > 0 (Dilated): the strided blocks count only while
+                                 i - j < r, i.e. a local window of r / s blocks with dilation s;
+                                 0 = the whole sequence.  Ignored when stride_blocks == 0     */
 } spa_params;
 
 /* Human-readable text for a return code.  Never NULL. */

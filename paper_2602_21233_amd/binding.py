@@ -32,7 +32,8 @@ class SpaParams(ctypes.Structure):
                 ("top_k_blocks", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
-                ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32)]
+                ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32),
+                ("stride_reach_blocks", ctypes.c_int32)]
 
 
 class SpaSelectOpts(ctypes.Structure):
@@ -91,24 +92,25 @@ def _strides(t):
 
 def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, n_sink_blocks,
                 n_local_blocks, top_k_blocks, softmax_scale=None, q=None, k=None, v=None, out=None,
-                stride_blocks=0, n_dense_q_blocks=0) -> SpaParams:
+                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0) -> SpaParams:
     p = SpaParams()
     p.batch, p.n_q_heads, p.n_kv_heads = batch, n_q_heads, n_kv_heads
     p.seq_len, p.head_dim, p.block_size = seq_len, head_dim, block_size
     p.n_sink_blocks, p.n_local_blocks, p.top_k_blocks = n_sink_blocks, n_local_blocks, top_k_blocks
     p.stride_blocks, p.n_dense_q_blocks = stride_blocks, n_dense_q_blocks
+    p.stride_reach_blocks = stride_reach_blocks
     p.softmax_scale = 0.0 if softmax_scale is None else float(softmax_scale)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = _strides(q), _strides(k), _strides(v), _strides(out)
     return p
 
 
 def _params_from(q, k, block_size, ns, nl, topk, scale, v=None, out=None, stride_blocks=0,
-                 n_dense_q_blocks=0) -> SpaParams:
+                 n_dense_q_blocks=0, stride_reach_blocks=0) -> SpaParams:
     B, Hq, S, D = q.shape
     return make_params(batch=B, n_q_heads=Hq, n_kv_heads=k.shape[1], seq_len=S, head_dim=D,
                        block_size=block_size, n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=topk,
                        softmax_scale=scale, q=q, k=k, v=v, out=out, stride_blocks=stride_blocks,
-                       n_dense_q_blocks=n_dense_q_blocks)
+                       n_dense_q_blocks=n_dense_q_blocks, stride_reach_blocks=stride_reach_blocks)
 
 
 def _ptr(t):
@@ -187,13 +189,14 @@ def value_norms(v, block_size):
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
            return_scores=False, workspace=None, top_k_per_block=None, v=None, stride_blocks=0,
-           n_dense_q_blocks=0, head_pattern=None):
+           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
     """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
     tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
     without a schedule).  Returns (block_idx, block_cnt[, scores])."""
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v,
-                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks)
+                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
+                     stride_reach_blocks=stride_reach_blocks)
     B, Hq, S, _ = q.shape
     NB, T = S // block_size, row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
@@ -222,14 +225,15 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
 
 
 def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_per_block=None,
-                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None):
+                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
     """sparse_prefill_topk_from_scores (…_tpd with a schedule) on [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
         raise TypeError("expected contiguous fp32 scores on the GPU")
     B, Hq, NB, _ = scores.shape
     p = make_params(batch=B, n_q_heads=Hq, n_kv_heads=Hq, seq_len=NB * 64, head_dim=64, block_size=64,
                     n_sink_blocks=n_sink_blocks, n_local_blocks=n_local_blocks, top_k_blocks=top_k_blocks,
-                    stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks)
+                    stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
+                    stride_reach_blocks=stride_reach_blocks)
     T = row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
@@ -251,7 +255,7 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
 def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
          workspace=None, pattern=None):
     """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S]).
-    pattern: optional (n_sink, n_local, top_k, stride_blocks, n_dense_q_blocks) the lists were made
+    pattern: optional (n_sink, n_local, top_k, stride_blocks, n_dense_q_blocks[, stride_reach_blocks]) the lists were made
     with; it only tells the library how uneven the rows are (scheduling hint)."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
@@ -261,9 +265,9 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
     if pattern is None:
         p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out)
     else:
-        ns, nl, tk, stride, n_dense = pattern
+        ns, nl, tk, stride, n_dense, *rest = pattern
         p = _params_from(q, k, block_size, ns, nl, tk, softmax_scale, v=v, out=out, stride_blocks=stride,
-                         n_dense_q_blocks=n_dense)
+                         n_dense_q_blocks=n_dense, stride_reach_blocks=rest[0] if rest else 0)
     if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
             or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
         raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")
@@ -277,14 +281,15 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
           return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
-          output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None):
+          output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
     """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
     current stream."""
     _dev_bf16(q, k, v)
     B, Hq, S, D = q.shape
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v, out=out,
-                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks)
+                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
+                     stride_reach_blocks=stride_reach_blocks)
     NB, T = S // block_size, row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device) if return_lists else None
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None

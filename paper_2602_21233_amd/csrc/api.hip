@@ -21,7 +21,7 @@ int check_shape(const spa_params* p) {
     if (p->seq_len / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
     if ((int64_t)p->batch * p->n_q_heads * (p->seq_len / p->block_size) > 0x7fffffffLL) return SPA_ERR_BAD_SHAPE;
     if (p->n_sink_blocks < 0 || p->n_local_blocks < 1 || p->top_k_blocks < 0) return SPA_ERR_BAD_PATTERN;
-    if (p->stride_blocks < 0 || p->n_dense_q_blocks < 0) return SPA_ERR_BAD_PATTERN;
+    if (p->stride_blocks < 0 || p->n_dense_q_blocks < 0 || p->stride_reach_blocks < 0) return SPA_ERR_BAD_PATTERN;
     if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return SPA_ERR_BAD_SHAPE;
     return SPA_OK;
 }

@@ -13,7 +13,7 @@ constexpr int kMaxBlocks = 4096;  // NB limit: one score row must fit a wave's L
 struct Dims {
     int B, Hq, Hkv, G, S, D, Bs, NB, T;
     int ns, nl, k;
-    int stride, n_dense;          // strided static columns, dense bottom strip (0 = off)
+    int stride, n_dense, reach;   // strided static columns, dense bottom strip, reach of the strided columns (0 = off)
     float scale;
 };
 
@@ -22,8 +22,10 @@ inline Dims dims_of(const spa_params& p) {
     d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
     d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = p.seq_len / p.block_size;
     d.ns = p.n_sink_blocks; d.nl = p.n_local_blocks; d.k = p.top_k_blocks;
-    d.stride = p.stride_blocks; d.n_dense = p.n_dense_q_blocks;
-    int64_t t = (int64_t)d.ns + d.nl + d.k + (d.stride > 0 ? (d.NB - 1) / d.stride : 0);
+    d.stride = p.stride_blocks; d.n_dense = p.n_dense_q_blocks; d.reach = p.stride_reach_blocks;
+    int64_t far = d.NB - 1;
+    if (d.reach > 0 && d.reach - 1 < far) far = d.reach - 1;
+    int64_t t = (int64_t)d.ns + d.nl + d.k + (d.stride > 0 ? far / d.stride : 0);
     d.T = (int)((t < d.NB && d.n_dense <= 0) ? t : d.NB);
     d.scale = p.softmax_scale;
     return d;

@@ -42,13 +42,14 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int /*lane*/) {
 }
 
 // The static pattern.  Plain A-shape: sink blocks + local window.  EXT adds the strided columns
-// ((i - j) % stride == 0) and the dense bottom strip of the Tri-shape (rows i >= NB - n_dense).
+// ((i - j) % stride == 0, within a reach for the Dilated pattern) and the dense bottom strip of the Tri-shape (rows i >= NB - n_dense).
 struct Pattern {
-    int ns, nl, stride, n_dense, NB;
+    int ns, nl, stride, n_dense, NB, reach;   // reach: strided blocks count while i - j < reach
     float inv_stride;
 };
 inline Pattern pattern_of(const Dims& d) {
-    return Pattern{d.ns, d.nl, d.stride, d.n_dense, d.NB, d.stride > 0 ? 1.0f / (float)d.stride : 0.f};
+    return Pattern{d.ns, d.nl, d.stride, d.n_dense, d.NB, d.reach > 0 ? d.reach : d.NB,
+                   d.stride > 0 ? 1.0f / (float)d.stride : 0.f};
 }
 inline bool extended(const Dims& d) { return d.stride > 0 || d.n_dense > 0; }
 
@@ -61,7 +62,7 @@ __device__ __forceinline__ bool static_block(const Pattern& pt, int i, int j) {
             // i - j < 4096: the nearest integer to (i - j) / stride is exact for multiples
             const int dist = i - j;
             const int quot = (int)__builtin_rintf((float)dist * pt.inv_stride);
-            s = s || (quot * pt.stride == dist);
+            s = s || (quot * pt.stride == dist && dist < pt.reach);
         }
         s = s || (i >= pt.NB - pt.n_dense);
     }

@@ -51,6 +51,7 @@ def test_row_capacity_and_workspace(lib):
     assert m.row_capacity(_params(stride_blocks=3)) == 8           # 6 + (8 - 1) // 3
     assert m.row_capacity(_params(top_k_blocks=0, stride_blocks=4)) == 4
     assert m.row_capacity(_params(n_dense_q_blocks=2)) == 8        # a dense strip needs full rows
+    assert m.row_capacity(_params(top_k_blocks=0, stride_blocks=2, stride_reach_blocks=5)) == 5   # 3 + (5 - 1) // 2
     ws = m.workspace_bytes(_params())
     # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists + transposed V (2*1024*128 bf16),
     # each 256-byte aligned
@@ -61,7 +62,7 @@ def test_row_capacity_and_workspace(lib):
     (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(seq_len=1000), -2),
     (dict(n_q_heads=5), -2), (dict(batch=0), -2), (dict(seq_len=128 * 4097), -2),
     (dict(n_local_blocks=0), -3), (dict(n_sink_blocks=-1), -3), (dict(top_k_blocks=-2), -3),
-    (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3),
+    (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3), (dict(stride_reach_blocks=-1), -3),
     (dict(softmax_scale=-1.0), -2),
 ])
 def test_bad_params_rejected_on_host(lib, kw, code):

@@ -259,6 +259,31 @@ def test_topk_static_patterns_bit_exact(spa, oracle, NB, ns, nl, k, stride, n_de
         assert torch.equal(idx.cpu(), want_idx)
 
 
+@pytest.mark.parametrize("NB", [19, 65, 300, 1100])
+@pytest.mark.parametrize("ns,nl,k,stride,reach", [(1, 2, 7, 3, 10), (0, 1, 5, 2, 2), (1, 2, 4, 8, 64), (1, 1, 0, 1, 6)])
+def test_topk_dilated_window_bit_exact(spa, oracle, NB, ns, nl, k, stride, reach):
+    g = torch.Generator().manual_seed(NB + stride * reach)
+    sp = torch.randn((1, 2, NB, NB), generator=g)
+    want_idx, want_cnt = oracle.topk(sp, ns, nl, k, stride=stride, reach=reach)
+    idx, cnt = spa.topk_from_scores(sp.cuda(), ns, nl, k, stride_blocks=stride, stride_reach_blocks=reach)
+    assert idx.shape == want_idx.shape
+    assert torch.equal(cnt.cpu(), want_cnt) and torch.equal(idx.cpu(), want_idx)
+
+
+def test_select_and_fused_dilated_window(spa, oracle):
+    B, Hq, Hkv, NB, D, Bs, ns, nl, k, stride, reach = 1, 2, 1, 70, 128, 128, 1, 2, 5, 4, 24
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 47)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    out, lse, idx, cnt = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True,
+                                   stride_blocks=stride, stride_reach_blocks=reach)
+    _, _, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, stride_blocks=stride, stride_reach_blocks=reach)
+    g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k, stride=stride, reach=reach)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    want, want_lse = oracle.attn(q, kk, v, idx.cpu(), cnt.cpu(), Bs)
+    _assert_attn_close(out, want)
+    assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k,stride,n_dense", [
     (1, 4, 2, 21, 128, 64, 1, 2, 4, 5, 0), (1, 2, 1, 70, 128, 128, 1, 3, 6, 0, 4), (1, 2, 2, 300, 64, 64, 1, 2, 12, 32, 3)])
 def test_select_and_fused_static_patterns(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k, stride, n_dense):
