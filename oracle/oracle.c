@@ -31,7 +31,9 @@
  * the whole pipeline is "parity unpinned": the paper prints no value for it.
  *
  * Layouts: all tensors contiguous.  Q [B,Hq,S,D], K/V [B,Hkv,S,D] as bf16 bit
- * patterns (uint16).  NB = S/Bs.  T = min(NB, ns+nl+k).
+ * patterns (uint16).  NB = ceil(S/Bs): the last block may be partial (it then
+ * holds S - (NB-1)*Bs tokens; block means are taken over the tokens that exist,
+ * and tokens past S neither attend nor are attended to).  T = min(NB, ns+nl+k).
  */
 #include <math.h>
 #include <stdint.h>
@@ -50,16 +52,17 @@ static double bf16_to_f64(uint16_t h) {
  * x: [n_heads_total, S, D] bf16; xp: [n_heads_total, NB, D] fp32. */
 int oracle_pool(const uint16_t *x, int64_t n_heads_total, int64_t S, int64_t D,
                 int64_t Bs, float *xp) {
-    if (Bs <= 0 || S % Bs) return -1;
-    int64_t NB = S / Bs;
+    if (Bs <= 0 || S <= 0) return -1;
+    int64_t NB = (S + Bs - 1) / Bs;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int64_t n = 0; n < n_heads_total; ++n)
         for (int64_t i = 0; i < NB; ++i)
             for (int64_t d = 0; d < D; ++d) {
+                int64_t len = S - i * Bs < Bs ? S - i * Bs : Bs;   /* tokens of block i */
                 double acc = 0.0;
-                for (int64_t t = 0; t < Bs; ++t)
+                for (int64_t t = 0; t < len; ++t)
                     acc += bf16_to_f64(x[(n * S + i * Bs + t) * D + d]);
-                xp[(n * NB + i) * D + d] = (float)(acc / (double)Bs);
+                xp[(n * NB + i) * D + d] = (float)(acc / (double)len);
             }
     return 0;
 }
@@ -102,13 +105,14 @@ int oracle_scores(const float *qp, const float *kp, int64_t B, int64_t Hq,
  * oracle_scores_oam applies the second line in place. */
 int oracle_vnorm(const uint16_t *v, int64_t n_heads_total, int64_t S, int64_t D,
                  int64_t Bs, float *vn) {
-    if (Bs <= 0 || S % Bs) return -1;
-    int64_t NB = S / Bs;
+    if (Bs <= 0 || S <= 0) return -1;
+    int64_t NB = (S + Bs - 1) / Bs;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int64_t n = 0; n < n_heads_total; ++n)
         for (int64_t j = 0; j < NB; ++j) {
+            int64_t len = S - j * Bs < Bs ? S - j * Bs : Bs;
             double acc = 0.0;
-            for (int64_t t = 0; t < Bs; ++t) {
+            for (int64_t t = 0; t < len; ++t) {
                 double sq = 0.0;
                 for (int64_t d = 0; d < D; ++d) {
                     double x = bf16_to_f64(v[(n * S + j * Bs + t) * D + d]);
@@ -116,7 +120,7 @@ int oracle_vnorm(const uint16_t *v, int64_t n_heads_total, int64_t S, int64_t D,
                 }
                 acc += sqrt(sq);
             }
-            vn[n * NB + j] = (float)(acc / (double)Bs);
+            vn[n * NB + j] = (float)(acc / (double)len);
         }
     return 0;
 }
@@ -256,8 +260,8 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                 int64_t Bs, int64_t T, float scale, const int32_t *idx,
                 const int32_t *cnt, const int32_t *rows, int64_t n_rows,
                 float *out, float *lse) {
-    if (Hkv <= 0 || Hq % Hkv || Bs <= 0 || S % Bs) return -1;
-    int64_t G = Hq / Hkv, NB = S / Bs;
+    if (Hkv <= 0 || Hq % Hkv || Bs <= 0 || S <= 0) return -1;
+    int64_t G = Hq / Hkv, NB = (S + Bs - 1) / Bs;
     if (!rows) n_rows = B * Hq * NB;
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 4)
@@ -267,6 +271,15 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             if (rows) { b = rows[3 * r]; h = rows[3 * r + 1]; i = rows[3 * r + 2]; }
             else { b = r / (Hq * NB); h = (r / NB) % Hq; i = r % NB; }
             int64_t t = i * Bs + tq;
+            /* with rows == NULL the output is [B,Hq,S,D]; with a list it is [n_rows,Bs,D] */
+            int64_t orow_idx = rows ? r * Bs + tq : (b * Hq + h) * S + t;
+            if (t >= S) {                      /* token past the end of a partial last block */
+                if (rows) {
+                    for (int64_t d = 0; d < D; ++d) out[orow_idx * D + d] = 0.0f;
+                    if (lse) lse[orow_idx] = 0.0f;
+                }
+                continue;
+            }
             const uint16_t *qt = q + ((b * Hq + h) * S + t) * D;
             const uint16_t *kh = k + ((b * Hkv + h / G) * S) * D;
             const uint16_t *vh = v + ((b * Hkv + h / G) * S) * D;
@@ -285,7 +298,7 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             for (int64_t e = 0; e < c; ++e)
                 for (int64_t u = 0; u < Bs; ++u) {
                     int64_t s = (int64_t)sel[e] * Bs + u;
-                    if (s > t) continue; /* causal */
+                    if (s > t) continue; /* causal; t < S, so keys past the end never pass */
                     double dot = 0.0;
                     for (int64_t d = 0; d < D; ++d)
                         dot += bf16_to_f64(qt[d]) * bf16_to_f64(kh[s * D + d]);
@@ -302,9 +315,9 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                 for (int64_t d = 0; d < D; ++d)
                     acc[d] += p * bf16_to_f64(vh[key[e] * D + d]);
             }
-            float *orow = out + (r * Bs + tq) * D;
+            float *orow = out + orow_idx * D;
             for (int64_t d = 0; d < D; ++d) orow[d] = (float)(acc[d] / l);
-            if (lse) lse[r * Bs + tq] = (float)(m + log(l));
+            if (lse) lse[orow_idx] = (float)(m + log(l));
             free(x); free(key); free(acc);
         }
     return fail ? -2 : 0;

@@ -77,7 +77,7 @@ def pool(x: torch.Tensor, block_size: int) -> torch.Tensor:
     """x [B,H,S,D] bf16 -> [B,H,S/Bs,D] fp32 block means."""
     B, H, S, D = x.shape
     xb = _bits(x)
-    out = torch.empty((B, H, S // block_size, D), dtype=torch.float32)
+    out = torch.empty((B, H, -(-S // block_size), D), dtype=torch.float32)
     _check(_load().oracle_pool(xb.data_ptr(), B * H, S, D, block_size, out.data_ptr()), "pool")
     return out
 
@@ -98,7 +98,7 @@ def vnorm(v: torch.Tensor, block_size: int) -> torch.Tensor:
     """v [B,Hkv,S,D] bf16 -> [B,Hkv,S/Bs] fp32: mean L2 norm of each block's value vectors."""
     B, H, S, D = v.shape
     vb = _bits(v)
-    out = torch.empty((B, H, S // block_size), dtype=torch.float32)
+    out = torch.empty((B, H, -(-S // block_size)), dtype=torch.float32)
     _check(_load().oracle_vnorm(vb.data_ptr(), B * H, S, D, block_size, out.data_ptr()), "vnorm")
     return out
 
@@ -168,7 +168,7 @@ def attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, c
     idx = idx.contiguous().to(torch.int32)
     cnt = cnt.contiguous().to(torch.int32)
     if rows is None:
-        n = B * Hq * (S // block_size)
+        n = B * Hq * (-(-S // block_size))
         out = torch.empty((B, Hq, S, D), dtype=torch.float32)
         lse = torch.empty((B, Hq, S), dtype=torch.float32)
         rows_ptr = None

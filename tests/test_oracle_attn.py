@@ -173,3 +173,52 @@ def test_select_pipeline_invariants_on_workload(oracle):
     out, lse = oracle.attn(q, k, v, idx, cnt, w.block_size)
     bf, _ = brute_force(q, k, v, idx, cnt, w.block_size, oracle.default_scale(w.head_dim))
     np.testing.assert_allclose(out.numpy(), bf, rtol=0, atol=1e-6)
+
+
+# ---- sequence length that is not a multiple of the block size (partial last block) ----
+
+@pytest.mark.parametrize("S,Bs", [(37, 8), (16 * 3 + 1, 16), (5, 8), (63, 16)])
+def test_ragged_all_blocks_equals_dense_causal_sdpa(oracle, S, Bs):
+    B, Hq, Hkv, D = 1, 4, 2, 16
+    q, k, v = _qkv(B, Hq, Hkv, S, D, 60 + S)
+    NB = -(-S // Bs)
+    idx, cnt = _all_causal(B, Hq, NB)
+    out, lse = oracle.attn(q, k, v, idx, cnt, Bs)
+    assert out.shape == (B, Hq, S, D) and lse.shape == (B, Hq, S)
+    ref = F.scaled_dot_product_attention(q.float(), k.float().repeat_interleave(2, 1), v.float().repeat_interleave(2, 1),
+                                         is_causal=True)
+    torch.testing.assert_close(out, ref, rtol=1e-4, atol=1e-5)
+
+
+def test_ragged_equals_the_padded_sequence_on_the_tokens_that_exist(oracle):
+    """Causality: tokens appended after the end cannot change the rows before them, so a ragged
+    run equals the run on the sequence padded to whole blocks, given the same lists."""
+    B, Hq, Hkv, D, Bs, S = 1, 2, 1, 16, 8, 43
+    NB = -(-S // Bs)
+    qp, kp, vp = _qkv(B, Hq, Hkv, NB * Bs, D, 71)
+    q, k, v = qp[:, :, :S].contiguous(), kp[:, :, :S].contiguous(), vp[:, :, :S].contiguous()
+    g = torch.Generator().manual_seed(3)
+    sp = torch.randn((B, Hq, NB, NB), generator=g)
+    idx, cnt = oracle.topk(sp, 1, 2, 2)
+    out_r, lse_r = oracle.attn(q, k, v, idx, cnt, Bs)
+    out_p, lse_p = oracle.attn(qp, kp, vp, idx, cnt, Bs)
+    assert torch.equal(out_r, out_p[:, :, :S]) and torch.equal(lse_r, lse_p[:, :, :S])
+    rows = [(0, 1, NB - 1), (0, 0, 2)]
+    out_s, lse_s = oracle.attn(q, k, v, idx, cnt, Bs, rows=rows)
+    tail = S - (NB - 1) * Bs
+    assert torch.equal(out_s[0, :tail], out_r[0, 1, (NB - 1) * Bs:]) and (out_s[0, tail:] == 0).all()
+    assert torch.equal(out_s[1], out_r[0, 0, 2 * Bs:3 * Bs])
+
+
+def test_ragged_pooling_averages_the_tokens_that_exist(oracle):
+    Bs, D, S = 8, 16, 29
+    x = torch.randn((2, 3, S, D), generator=torch.Generator().manual_seed(4)).to(torch.bfloat16)
+    got = oracle.pool(x, Bs)
+    assert got.shape == (2, 3, 4, D)
+    xd = x.double().numpy()
+    for i in range(4):
+        want = xd[:, :, i * Bs:min((i + 1) * Bs, S)].mean(axis=2)
+        np.testing.assert_allclose(got[:, :, i].numpy(), want, rtol=1e-6, atol=1e-7)
+    vn = oracle.vnorm(x, Bs)
+    want = np.linalg.norm(xd[:, :, 24:29], axis=-1).mean(-1)
+    np.testing.assert_allclose(vn[:, :, 3].numpy(), want, rtol=2e-7)
