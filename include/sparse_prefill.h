@@ -26,7 +26,9 @@
  *     `*_stride`; the head_dim axis is contiguous.  Base pointers must be
  *     16-byte aligned and every stride a multiple of 8 elements.
  *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
- *   - NB = seq_len / block_size query blocks and key blocks.  Row capacity
+ *   - NB = ceil(seq_len / block_size) query blocks and key blocks; seq_len need not be a
+ *     multiple of block_size: the last block is then partial, block means are taken over
+ *     the tokens that exist and nothing is read or written past seq_len.  Row capacity
  *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks
  *                 + (stride_blocks > 0 ? min(NB - 1, reach - 1) / stride_blocks : 0)),
  *     reach = stride_reach_blocks or NB when that is 0,
@@ -66,7 +68,7 @@ typedef struct spa_params {
     int32_t batch;          /* >= 1                                                   */
     int32_t n_q_heads;      /* >= 1, multiple of n_kv_heads                           */
     int32_t n_kv_heads;     /* >= 1                                                   */
-    int32_t seq_len;        /* multiple of block_size; seq_len / block_size <= 4096   */
+    int32_t seq_len;        /* >= 1; ceil(seq_len / block_size) <= 4096               */
     int32_t head_dim;       /* 64 or 128                                              */
     int32_t block_size;     /* 64 or 128 tokens                                       */
     int32_t n_sink_blocks;  /* >= 0: key blocks 0 .. n_sink-1 are always selected     */

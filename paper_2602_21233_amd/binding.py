@@ -169,7 +169,7 @@ def pool(q, k, block_size):
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, 0, 1, 0, None)
     B, Hq, S, D = q.shape
-    NB = S // block_size
+    NB = -(-S // block_size)
     qp = torch.empty((B, Hq, NB, D), dtype=torch.float32, device=q.device)
     kp = torch.empty((B, k.shape[1], NB, D), dtype=torch.float32, device=q.device)
     _check(load_library().sparse_prefill_pool(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(qp), _ptr(kp), _stream(q)))
@@ -182,7 +182,7 @@ def value_norms(v, block_size):
     B, Hkv, S, D = v.shape
     p = make_params(batch=B, n_q_heads=Hkv, n_kv_heads=Hkv, seq_len=S, head_dim=D, block_size=block_size,
                     n_sink_blocks=0, n_local_blocks=1, top_k_blocks=0, v=v)
-    out = torch.empty((B, Hkv, S // block_size), dtype=torch.float32, device=v.device)
+    out = torch.empty((B, Hkv, -(-S // block_size)), dtype=torch.float32, device=v.device)
     _check(load_library().sparse_prefill_value_norms(ctypes.byref(p), _ptr(v), _ptr(out), _stream(v)))
     return out
 
@@ -198,7 +198,7 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
                      stride_reach_blocks=stride_reach_blocks)
     B, Hq, S, _ = q.shape
-    NB, T = S // block_size, row_capacity(p)
+    NB, T = -(-S // block_size), row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
     sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
@@ -290,7 +290,7 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v, out=out,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
                      stride_reach_blocks=stride_reach_blocks)
-    NB, T = S // block_size, row_capacity(p)
+    NB, T = -(-S // block_size), row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device) if return_lists else None
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None

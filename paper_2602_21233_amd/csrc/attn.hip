@@ -79,7 +79,10 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     // Q^T fragments (B operand): lane holds query row 32*wave + l32, dims 16s + 8*half .. +7.
     bf16x8 qf[DS];
     {
-        const uint16_t* qrow = qb + (int64_t)(32 * wave + l32) * qs.t + 8 * half;
+        // rows past the end of a partial last block read the last token (never stored)
+        int qr = 32 * wave + l32;
+        if (i * BS + qr > S - 1) qr = S - 1 - i * BS;
+        const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
         for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
     }
@@ -98,10 +101,12 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     auto fetch = [&](int blk) {
         const uint16_t* kt = kb + (int64_t)blk * BS * ks.t;
         const uint16_t* vt = vb + (int64_t)blk * BS * vs.t;
+        const int last_row = S - 1 - blk * BS;          // >= BS - 1 except in a partial last block
 #pragma unroll
         for (int p = 0; p < CPT; ++p) {
             int cidx = p * NT + tid;
             int row = cidx / (D / 8), col = (cidx % (D / 8)) * 8;
+            if (row > last_row) row = last_row;         // keys past the end: re-read the last token, always masked
             kreg[p] = *reinterpret_cast<const uint4*>(kt + (int64_t)row * ks.t + col);
             vreg[p] = *reinterpret_cast<const uint4*>(vt + (int64_t)row * vs.t + col);
         }
@@ -198,6 +203,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / l_tot;
     const int qpos = 32 * wave + l32;
+    if (i * BS + qpos >= S) return;                     // token past the end of a partial last block
     uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + qpos) * os.t;
 #pragma unroll
     for (int dc = 0; dc < DC; ++dc)

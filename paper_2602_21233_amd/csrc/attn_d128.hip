@@ -75,7 +75,7 @@ __device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) 
 // V [B,Hkv,S,D] (strided) -> Vt [B,Hkv,NB,D,BS] contiguous.
 template <int BS>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv,
-                                                          int NB, uint16_t* __restrict__ vt) {
+                                                          int NB, int S, uint16_t* __restrict__ vt) {
     constexpr int PITCH = D + 2;
     __shared__ uint16_t tile[BS * PITCH];
     const int blk = blockIdx.x, bh = blockIdx.y;
@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
     for (int p = 0; p < BS * D / 8 / 256; ++p) {
         int c = p * 256 + tid;
         int row = c / (D / 8), col = (c % (D / 8)) * 8;
-        uint4 x = *reinterpret_cast<const uint4*>(src + (int64_t)row * vs.t + col);
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);           // tokens past the end of a partial last block: zeros
+        if (blk * BS + row < S) x = *reinterpret_cast<const uint4*>(src + (int64_t)row * vs.t + col);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row * PITCH + col]);   // PITCH even: 4-byte aligned
         dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
     }
@@ -220,11 +221,27 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint32_t v_dst = lds_address(&smemV[0][0]) + wave * LPW * 1024;
     auto issue_k = [&](auto buf_tag, int st, int blk) {
         constexpr int BUF = decltype(buf_tag)::value;
-        const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + (st % NSUB) * KT) * ks.t);
-        static_for<LPW>([&](auto x_tag) {
-            constexpr int X = decltype(x_tag)::value;
-            lds_dma16<BUF * TILE_B + X * 1024>(k_dst, k_offb[X], kt);
-        });
+        const int sub = st % NSUB;
+        if ((blk + 1) * BS <= S) {
+            const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + sub * KT) * ks.t);
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                lds_dma16<BUF * TILE_B + X * 1024>(k_dst, k_offb[X], kt);
+            });
+        } else {
+            // partial last block (only ever the diagonal block of the last query block): key rows past
+            // the end re-read the last token; they are masked for every query that exists
+            const char* kt = reinterpret_cast<const char*>(kb + (int64_t)blk * BS * ks.t);
+            const int last_row = S - 1 - blk * BS;
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                const int krow = 4 * (wave * LPW + X) + (lane >> 4);
+                int row = sub * KT + krow;
+                if (row > last_row) row = last_row;
+                const uint32_t off = 2u * ((uint32_t)row * (uint32_t)ks.t + (uint32_t)(((lane & 15) ^ swz_k(krow)) << 3));
+                lds_dma16<BUF * TILE_B + X * 1024>(k_dst, off, kt);
+            });
+        }
     };
     auto issue_v = [&](auto buf_tag, int st, int blk) {
         constexpr int BUF = decltype(buf_tag)::value;
@@ -246,7 +263,10 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
     bf16x8 qf[8];
     {
-        const uint16_t* qrow = qb + (int64_t)(32 * wave + l32) * qs.t + 8 * half;
+        // rows past the end of a partial last block read the last token (their results are never stored)
+        int qr = 32 * wave + l32;
+        if (i * BS + qr > S - 1) qr = S - 1 - i * BS;
+        const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
     }
@@ -461,6 +481,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     // ---- epilogue ----------------------------------------------------------------
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
+    if (i * BS + q_in_blk >= S) return;                  // token past the end of a partial last block
     uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
 #pragma unroll
     for (int dc = 0; dc < 4; ++dc)
@@ -480,7 +501,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
                   void* vt, hipStream_t st) {
     hipLaunchKernelGGL((transpose_v_kernel<BS>), dim3(d.NB, d.B * d.Hkv), dim3(256), 0, st,
-                       (const uint16_t*)v, vs, d.Hkv, d.NB, (uint16_t*)vt);
+                       (const uint16_t*)v, vs, d.Hkv, d.NB, d.S, (uint16_t*)vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const RowDeal deal = deal_rows(d);

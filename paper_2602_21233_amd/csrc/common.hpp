@@ -20,7 +20,7 @@ struct Dims {
 inline Dims dims_of(const spa_params& p) {
     Dims d;
     d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
-    d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = p.seq_len / p.block_size;
+    d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = (p.seq_len + p.block_size - 1) / p.block_size;   // the last block may be partial
     d.ns = p.n_sink_blocks; d.nl = p.n_local_blocks; d.k = p.top_k_blocks;
     d.stride = p.stride_blocks; d.n_dense = p.n_dense_q_blocks; d.reach = p.stride_reach_blocks;
     int64_t far = d.NB - 1;

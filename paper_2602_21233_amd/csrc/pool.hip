@@ -19,7 +19,7 @@ template <int D, int BS>
 __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ q, Strides qs,
                                                    int n_q_rows /* B*Hq or 0 */, int Hq,
                                                    const uint16_t* __restrict__ k, Strides ks, int Hkv,
-                                                   float* __restrict__ qp, float* __restrict__ kp, int NB) {
+                                                   float* __restrict__ qp, float* __restrict__ kp, int NB, int S) {
     constexpr int TPR = D / 8;          // lanes per token row
     constexpr int RPP = 256 / TPR;      // token rows per pass
     constexpr int PASSES = BS / RPP;
@@ -44,10 +44,15 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
     const int tid = threadIdx.x;
     const int row0 = tid / TPR, chunk = tid % TPR;
 
+    // the last block of a sequence may be partial: tokens past the end are not read
+    const int n_valid = S - blk * BS < BS ? S - blk * BS : BS;
     uint4 raw[PASSES];
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p)
-        raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * qs.t + chunk * 8);
+    for (int p = 0; p < PASSES; ++p) {
+        raw[p] = make_uint4(0u, 0u, 0u, 0u);
+        if (p * RPP + row0 < n_valid)
+            raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * qs.t + chunk * 8);
+    }
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
@@ -63,7 +68,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
         float s = 0.f;
 #pragma unroll
         for (int r = 0; r < RPP; ++r) s += part[r][tid];
-        dst[tid] = s * (1.0f / (float)BS);
+        dst[tid] = n_valid == BS ? s * (1.0f / (float)BS) : s / (float)n_valid;
     }
 }
 
@@ -74,7 +79,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     if (nq + nk == 0) return hipSuccess;
     dim3 grid(d.NB, nq + nk);
     hipLaunchKernelGGL((pool_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)q, qs, nq, d.Hq,
-                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB);
+                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S);
     return hipGetLastError();
 }
 
@@ -85,7 +90,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
 // order.  A block of all-zero values gives -inf.
 template <int D, int BS>
 __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv, int NB,
-                                                    float* __restrict__ lvn) {
+                                                    int S, float* __restrict__ lvn) {
     constexpr int TPR = D / 8;
     constexpr int RPP = 256 / TPR;
     constexpr int PASSES = BS / RPP;
@@ -95,10 +100,14 @@ __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__
     const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
     const int tid = threadIdx.x;
     const int row0 = tid / TPR, chunk = tid % TPR;
+    const int n_valid = S - blk * BS < BS ? S - blk * BS : BS;      // partial last block
     uint4 raw[PASSES];
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p)
-        raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * vs.t + chunk * 8);
+    for (int p = 0; p < PASSES; ++p) {
+        raw[p] = make_uint4(0u, 0u, 0u, 0u);                          // a missing token adds a norm of 0
+        if (p * RPP + row0 < n_valid)
+            raw[p] = *reinterpret_cast<const uint4*>(src + (int64_t)(p * RPP + row0) * vs.t + chunk * 8);
+    }
     float acc = 0.f;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
@@ -120,14 +129,14 @@ __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__
         float s = 0.f;
 #pragma unroll
         for (int r = 0; r < RPP; ++r) s += part[r];
-        lvn[(int64_t)hy * NB + blk] = logf(s * (1.0f / (float)BS));
+        lvn[(int64_t)hy * NB + blk] = logf(n_valid == BS ? s * (1.0f / (float)BS) : s / (float)n_valid);
     }
 }
 
 template <int D, int BS>
 hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
     dim3 grid(d.NB, d.B * d.Hkv);
-    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NB, lvn);
+    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NB, d.S, lvn);
     return hipGetLastError();
 }
 

@@ -51,6 +51,8 @@ def test_row_capacity_and_workspace(lib):
     assert m.row_capacity(_params(stride_blocks=3)) == 8           # 6 + (8 - 1) // 3
     assert m.row_capacity(_params(top_k_blocks=0, stride_blocks=4)) == 4
     assert m.row_capacity(_params(n_dense_q_blocks=2)) == 8        # a dense strip needs full rows
+    assert m.row_capacity(_params(seq_len=1000, top_k_blocks=100)) == 8   # 7 whole blocks + a partial one
+    assert m.row_capacity(_params(seq_len=1025, top_k_blocks=100)) == 9
     assert m.row_capacity(_params(top_k_blocks=0, stride_blocks=2, stride_reach_blocks=5)) == 5   # 3 + (5 - 1) // 2
     ws = m.workspace_bytes(_params())
     # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists + transposed V (2*1024*128 bf16),
@@ -59,7 +61,7 @@ def test_row_capacity_and_workspace(lib):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(seq_len=1000), -2),
+    (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(seq_len=0), -2),
     (dict(n_q_heads=5), -2), (dict(batch=0), -2), (dict(seq_len=128 * 4097), -2),
     (dict(n_local_blocks=0), -3), (dict(n_sink_blocks=-1), -3), (dict(top_k_blocks=-2), -3),
     (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3), (dict(stride_reach_blocks=-1), -3),

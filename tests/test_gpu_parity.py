@@ -537,6 +537,47 @@ def test_fused_sampled_128k_headline_workload(spa, oracle):
     _sampled_workload_check(spa, oracle, 3, n_random=4)
 
 
+# ------------------------------ sequence length not a multiple of the block size
+@pytest.mark.parametrize("S,D,Bs", [(8 * 64 + 1, 64, 64), (5 * 128 + 77, 128, 128), (37 * 64 + 63, 128, 64), (100, 64, 128),
+                                    (3 * 128 + 127, 64, 128), (9 * 128 + 32, 128, 128), (9 * 128 + 33, 128, 128)])
+def test_ragged_sequence_length(spa, oracle, S, D, Bs):
+    B, Hq, Hkv, ns, nl, k = 1, 4, 2, 1, 2, 3
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 53 + S)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    NB = -(-S // Bs)
+    qp, kp = spa.pool(dq, dk, Bs)
+    assert qp.shape == (B, Hq, NB, D)
+    torch.testing.assert_close(qp.cpu(), oracle.pool(q, Bs), rtol=0, atol=2e-6)
+    torch.testing.assert_close(kp.cpu(), oracle.pool(kk, Bs), rtol=0, atol=2e-6)
+    torch.testing.assert_close(spa.value_norms(dv, Bs).cpu(), oracle.vnorm(v, Bs).double().log().float(), rtol=0,
+                               atol=5e-6)
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True)
+    g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    o_idx, o_cnt, o_sp, *_ = oracle.select(q, kk, Bs, ns, nl, k)
+    tri = torch.tril(torch.ones(NB, NB, dtype=torch.bool))
+    torch.testing.assert_close(sp.cpu()[..., tri], o_sp[..., tri], rtol=1e-4, atol=1e-5)
+    # poison what lies behind the outputs: nothing may be written past the last token
+    big_out = torch.full((B, Hq, NB * Bs, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    out_view = big_out[:, :, :S]
+    out, lse = spa.attn(dq, dk, dv, idx, cnt, Bs, return_lse=True, out=out_view)
+    want, want_lse = oracle.attn(q, kk, v, idx.cpu(), cnt.cpu(), Bs)
+    _assert_attn_close(out, want)
+    assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
+    assert (big_out[:, :, S:] == 7.0).all()
+    fused = spa.fused(dq, dk, dv, Bs, ns, nl, k)
+    assert torch.equal(fused, out.contiguous())
+
+
+def test_ragged_all_blocks_is_dense_causal_attention(spa, oracle):
+    S, D, Bs = 6 * 128 + 50, 128, 128
+    q, kk, v = _qkv(1, 2, 1, S, D, 59)
+    out = spa.fused(q.cuda(), kk.cuda(), v.cuda(), Bs, 0, 1, 4096)
+    ref = torch.nn.functional.scaled_dot_product_attention(q.float(), kk.float().repeat_interleave(2, 1),
+                                                           v.float().repeat_interleave(2, 1), is_causal=True)
+    _assert_attn_close(out, ref)
+
+
 # ------------------------------------------------------------- HIP graph replay
 def test_fused_call_replays_from_a_hip_graph(spa, oracle):
     """The calls only enqueue kernels on the caller's stream (no allocation, no synchronisation,
