@@ -144,11 +144,21 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
 
 def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
            scale: float | None = None, k_per_row: torch.Tensor | None = None, v: torch.Tensor | None = None,
-           stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0):
+           stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0,
+           group_shared: bool = False):
     """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp).  With v the ranking score is
-    the output-aware one (scores_oam) and sp is that score."""
+    the output-aware one (scores_oam) and sp is that score.
+
+    group_shared: one list per KV head, shared by the G query heads of its group (a variant the
+    paper's per-head metadata allows; reading: the group is ranked by the mean of its heads'
+    pooled scores, i.e. by the score of the group-mean pooled query).  idx/cnt/sp then have
+    n_kv_heads in the head axis and qp is the group mean [B,Hkv,NB,D]."""
     scale = default_scale(q.shape[-1]) if scale is None else scale
     qp, kp = pool(q, block_size), pool(k, block_size)
+    if group_shared:
+        B, Hq, NB, D = qp.shape
+        Hkv = kp.shape[1]
+        qp = qp.view(B, Hkv, Hq // Hkv, NB, D).double().mean(2).float()
     sp = scores(qp, kp, scale)
     if v is not None:
         sp = scores_oam(sp, vnorm(v, block_size))

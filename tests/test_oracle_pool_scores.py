@@ -70,3 +70,23 @@ def test_scores_single_dim_hand_values(oracle):
     ninf = float("-inf")
     want = torch.tensor([[0.25, ninf, ninf], [0.5, -1.0, ninf], [-1.0, 2.0, -16.0]])
     assert torch.equal(sp[0, 0], want)
+
+
+def test_group_shared_scores_are_the_mean_of_the_heads_scores(oracle):
+    """Linearity: the score of the group-mean pooled query is the mean of the heads' scores, so
+    ranking a KV group by it is ranking by the summed pooled attention of its heads."""
+    B, Hq, Hkv, NB, Bs, D = 2, 6, 2, 9, 8, 16
+    g = torch.Generator().manual_seed(21)
+    q = torch.randn((B, Hq, NB * Bs, D), generator=g).to(torch.bfloat16)
+    k = torch.randn((B, Hkv, NB * Bs, D), generator=g).to(torch.bfloat16)
+    idx_g, cnt_g, sp_g, qp_g, _ = oracle.select(q, k, Bs, 1, 2, 2, group_shared=True)
+    _, _, sp, qp, _ = oracle.select(q, k, Bs, 1, 2, 2)
+    assert sp_g.shape == (B, Hkv, NB, NB) and idx_g.shape[1] == Hkv
+    want = sp.view(B, Hkv, Hq // Hkv, NB, NB).double().mean(2)
+    tri = torch.tril(torch.ones(NB, NB, dtype=torch.bool))
+    np.testing.assert_allclose(sp_g[..., tri].numpy(), want[..., tri].numpy(), rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(qp_g.numpy(), qp.view(B, Hkv, 3, NB, D).double().mean(2).numpy(), rtol=1e-6, atol=1e-7)
+    # one head per group: nothing changes
+    i1, c1, s1, *_ = oracle.select(q[:, :2], k, Bs, 1, 2, 2, group_shared=True)
+    i0, c0, s0, *_ = oracle.select(q[:, :2], k, Bs, 1, 2, 2)
+    assert torch.equal(i1, i0) and torch.equal(c1, c0) and torch.equal(s1, s0)
