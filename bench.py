@@ -7,7 +7,7 @@ heads, head_dim 128, block 128, sink 1 + local 4 + top-k 64).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N] [--no-cpu-baseline]
-                    [--variant uniform|tpd|stem|strided|trishape]
+                    [--variant uniform|tpd|stem|strided|trishape|shared]
 
 --variant (default uniform = the headline) times the same workload under the other selection
 rules the library has: a position-decaying budget (tpd), that plus the output-aware ranking
@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1200)
-    ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape"), default="uniform")
+    ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared"), default="uniform")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs with no exchange; "
@@ -108,10 +108,13 @@ def main():
         pat_kw = dict(stride_blocks=16)
     if args.variant == "trishape":
         pat_kw = dict(n_dense_q_blocks=8)
-    if pat_kw:
+    shared = args.variant == "shared"
+    if shared:
+        sel_kw["group_shared"] = True
+    if pat_kw or shared:
         p = binding.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, seq_len=w.seq_len,
                                 head_dim=w.head_dim, block_size=Bs, n_sink_blocks=ns, n_local_blocks=nl,
-                                top_k_blocks=tk, q=dq, k=dk, v=dv, out=dq, **pat_kw)
+                                top_k_blocks=tk, q=dq, k=dk, v=dv, out=dq, lists_per_kv_head=shared, **pat_kw)
         ws = torch.empty(spa.workspace_bytes(p), dtype=torch.uint8, device="cuda")
 
     pattern = (ns, nl, tk, pat_kw.get("stride_blocks", 0), pat_kw.get("n_dense_q_blocks", 0))
@@ -124,7 +127,7 @@ def main():
         idx, cnt = spa.select(dq, dk, Bs, ns, nl, tk, workspace=ws, **sel_kw, **pat_kw)
         if events:
             events[1].record()
-        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out, workspace=ws, pattern=pattern)
+        spa.attn(dq, dk, dv, idx, cnt, Bs, out=out, workspace=ws, pattern=pattern, group_shared=shared)
         if events:
             events[2].record()
         return idx, cnt
@@ -145,7 +148,7 @@ def main():
 
     # the output-aware score reads V once more (2 bytes per element)
     select_bytes = w.select_bytes + (2 * w.batch * w.n_kv_heads * w.seq_len * w.head_dim if args.variant == "stem" else 0)
-    visited_pairs = w.visited_pairs if args.variant == "uniform" else int(cnt.sum().item())
+    visited_pairs = w.visited_pairs if args.variant == "uniform" else int(cnt.sum().item()) * (w.group if shared else 1)
     flops = 4.0 * Bs * Bs * w.head_dim * visited_pairs
     achieved = flops / (att_avg * 1e-3) / 1e12
     result = {

@@ -89,6 +89,13 @@ typedef struct spa_params {
     int32_t stride_reach_blocks; /* >= 0.  r > 0 (Dilated): the strided blocks count only while
                                  i - j < r, i.e. a local window of r / s blocks with dilation s;
                                  0 = the whole sequence.  Ignored when stride_blocks == 0     */
+    int32_t lists_per_kv_head; /* 0 or 1.  1 (group-shared selection): one list per KV head, shared
+                                 by the n_q_heads / n_kv_heads query heads of its group; the group
+                                 is ranked by the mean of its heads' pooled scores.  block_idx,
+                                 block_cnt and the optional scores then have n_kv_heads in their
+                                 head axis (also for sparse_prefill_attn and, per KV head, for
+                                 spa_select_opts.head_pattern).  The heads of a group then walk the
+                                 same key blocks at the same time, which the L2 turns into reuse */
 } spa_params;
 
 /* Human-readable text for a return code.  Never NULL. */

@@ -33,7 +33,7 @@ class SpaParams(ctypes.Structure):
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
                 ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32),
-                ("stride_reach_blocks", ctypes.c_int32)]
+                ("stride_reach_blocks", ctypes.c_int32), ("lists_per_kv_head", ctypes.c_int32)]
 
 
 class SpaSelectOpts(ctypes.Structure):
@@ -92,25 +92,27 @@ def _strides(t):
 
 def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, n_sink_blocks,
                 n_local_blocks, top_k_blocks, softmax_scale=None, q=None, k=None, v=None, out=None,
-                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0) -> SpaParams:
+                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0, lists_per_kv_head=0) -> SpaParams:
     p = SpaParams()
     p.batch, p.n_q_heads, p.n_kv_heads = batch, n_q_heads, n_kv_heads
     p.seq_len, p.head_dim, p.block_size = seq_len, head_dim, block_size
     p.n_sink_blocks, p.n_local_blocks, p.top_k_blocks = n_sink_blocks, n_local_blocks, top_k_blocks
     p.stride_blocks, p.n_dense_q_blocks = stride_blocks, n_dense_q_blocks
     p.stride_reach_blocks = stride_reach_blocks
+    p.lists_per_kv_head = int(lists_per_kv_head)
     p.softmax_scale = 0.0 if softmax_scale is None else float(softmax_scale)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = _strides(q), _strides(k), _strides(v), _strides(out)
     return p
 
 
 def _params_from(q, k, block_size, ns, nl, topk, scale, v=None, out=None, stride_blocks=0,
-                 n_dense_q_blocks=0, stride_reach_blocks=0) -> SpaParams:
+                 n_dense_q_blocks=0, stride_reach_blocks=0, group_shared=False) -> SpaParams:
     B, Hq, S, D = q.shape
     return make_params(batch=B, n_q_heads=Hq, n_kv_heads=k.shape[1], seq_len=S, head_dim=D,
                        block_size=block_size, n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=topk,
                        softmax_scale=scale, q=q, k=k, v=v, out=out, stride_blocks=stride_blocks,
-                       n_dense_q_blocks=n_dense_q_blocks, stride_reach_blocks=stride_reach_blocks)
+                       n_dense_q_blocks=n_dense_q_blocks, stride_reach_blocks=stride_reach_blocks,
+                       lists_per_kv_head=group_shared)
 
 
 def _ptr(t):
@@ -189,15 +191,17 @@ def value_norms(v, block_size):
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
            return_scores=False, workspace=None, top_k_per_block=None, v=None, stride_blocks=0,
-           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
+           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, group_shared=False):
     """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
     tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
     without a schedule).  Returns (block_idx, block_cnt[, scores])."""
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
-                     stride_reach_blocks=stride_reach_blocks)
+                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared)
     B, Hq, S, _ = q.shape
+    if group_shared:
+        Hq = k.shape[1]                              # one list per KV head
     NB, T = -(-S // block_size), row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
@@ -253,7 +257,7 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
 
 
 def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
-         workspace=None, pattern=None):
+         workspace=None, pattern=None, group_shared=False):
     """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S]).
     pattern: optional (n_sink, n_local, top_k, stride_blocks, n_dense_q_blocks[, stride_reach_blocks]) the lists were made
     with; it only tells the library how uneven the rows are (scheduling hint)."""
@@ -263,11 +267,15 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
     T = block_idx.shape[-1]
     # the pattern fields only fix T here; the lists themselves carry the selection
     if pattern is None:
-        p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out)
+        p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out,
+                         group_shared=group_shared)
     else:
         ns, nl, tk, stride, n_dense, *rest = pattern
         p = _params_from(q, k, block_size, ns, nl, tk, softmax_scale, v=v, out=out, stride_blocks=stride,
-                         n_dense_q_blocks=n_dense, stride_reach_blocks=rest[0] if rest else 0)
+                         n_dense_q_blocks=n_dense, stride_reach_blocks=rest[0] if rest else 0,
+                         group_shared=group_shared)
+    if block_idx.shape[1] != (k.shape[1] if group_shared else Hq):
+        raise TypeError("block_idx has the wrong number of heads for this call")
     if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
             or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
         raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")
@@ -281,7 +289,8 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
           return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
-          output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
+          output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0,
+          group_shared=False):
     """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
     current stream."""
     _dev_bf16(q, k, v)
@@ -289,15 +298,16 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v, out=out,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
-                     stride_reach_blocks=stride_reach_blocks)
+                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared)
     NB, T = -(-S // block_size), row_capacity(p)
-    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device) if return_lists else None
-    cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if return_lists else None
+    Hl = k.shape[1] if group_shared else Hq          # heads in the lists
+    idx = torch.empty((B, Hl, NB, T), dtype=torch.int32, device=q.device) if return_lists else None
+    cnt = torch.empty((B, Hl, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
     ws = _workspace(p, q.device) if workspace is None else workspace
     if head_pattern is not None:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
-        o = _opts(kr, v if output_aware else None, _head_pattern(head_pattern, Hq))
+        o = _opts(kr, v if output_aware else None, _head_pattern(head_pattern, Hl))
         _check(load_library().sparse_prefill_fused_ex(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ctypes.byref(o),
                                                       _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),
                                                       ws.numel(), _stream(q)))

@@ -20,6 +20,7 @@ int check_shape(const spa_params* p) {
     if ((p->seq_len + p->block_size - 1) / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
     if ((int64_t)p->batch * p->n_q_heads * ((p->seq_len + p->block_size - 1) / p->block_size) > 0x7fffffffLL) return SPA_ERR_BAD_SHAPE;
     if (p->n_sink_blocks < 0 || p->n_local_blocks < 1 || p->top_k_blocks < 0) return SPA_ERR_BAD_PATTERN;
+    if (p->lists_per_kv_head != 0 && p->lists_per_kv_head != 1) return SPA_ERR_BAD_PATTERN;
     if (p->stride_blocks < 0 || p->n_dense_q_blocks < 0 || p->stride_reach_blocks < 0) return SPA_ERR_BAD_PATTERN;
     if (!(p->softmax_scale >= 0.0f) || isinf(p->softmax_scale)) return SPA_ERR_BAD_SHAPE;
     return SPA_OK;
@@ -41,7 +42,7 @@ Dims resolved(const spa_params* p) {
 }
 
 struct Workspace {
-    size_t qp_off, kp_off, idx_off, cnt_off, lvn_off, vt_off, total;
+    size_t qp_off, kp_off, qg_off, idx_off, cnt_off, lvn_off, vt_off, total;
 };
 
 Workspace carve(const Dims& d) {
@@ -49,6 +50,7 @@ Workspace carve(const Dims& d) {
     size_t off = 0;
     w.qp_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.D * sizeof(float));
     w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
+    w.qg_off = off; if (d.shared) off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
     w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
     w.lvn_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * sizeof(float));
@@ -87,6 +89,15 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
         lvn = (float*)((char*)ws + w.lvn_off);
         if (launch_vnorm(d, v_or_null, strides_of(p->v_stride), lvn, st) != hipSuccess) return SPA_ERR_LAUNCH;
     }
+    if (d.shared) {
+        // one list per KV head: rank the group by its mean pooled query, then select as if the
+        // KV heads were the query heads
+        float* qg = (float*)((char*)ws + w.qg_off);
+        if (launch_group_mean(d, qp, qg, st) != hipSuccess) return SPA_ERR_LAUNCH;
+        d.Hq = d.Hkv;
+        d.G = 1;
+        qp = qg;
+    }
     return launch_code(launch_score_topk(d, qp, kp, k_rows, head_pattern, lvn, block_idx, block_cnt, pooled_scores_or_null, st));
 }
 
@@ -97,6 +108,7 @@ int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_
     if (rc) return rc;
     if (!pooled_scores || !block_idx || !block_cnt) return SPA_ERR_NULLPTR;
     Dims d = resolved(p);
+    if (d.shared) { d.Hq = d.Hkv; d.G = 1; }
     return launch_code(launch_topk_from_scores(d, pooled_scores, k_rows, head_pattern, block_idx, block_cnt,
                                                (hipStream_t)hip_stream));
 }

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ v, Strides vs, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, uint16_t* __restrict__ out, Strides os, float* __restrict__ lse,
-    int Hq, int G, int NB, int T, int S, float scale) {
+    int Hq, int G, int NB, int T, int S, float scale, int shared) {
     constexpr int NT = BS * 2;        // threads
     constexpr int KC = BS / 32;       // 32-key chunks of a key tile
     constexpr int DS = D / 16;        // 16-wide slices of head_dim (QK^T reduction)
@@ -72,7 +72,8 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
     const uint16_t* vb = v + b * vs.b + kvh * vs.h;
-    const int64_t row_id = ((int64_t)b * Hq + h) * NB + i;
+    // block lists are per query head, or per KV head when the group shares its selection
+    const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
     const int n_sel = cnt[row_id];
 
@@ -227,7 +228,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     int64_t nwg = (int64_t)d.B * d.Hq * d.NB;
     hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st,
                        (const uint16_t*)q, qs, (const uint16_t*)k, ks, (const uint16_t*)v, vs, idx, cnt,
-                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale);
+                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared);
     return hipGetLastError();
 }
 

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale, RowDeal deal) {
+    float scale, RowDeal deal, int shared) {
     constexpr int NW = BS / 32;         // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
@@ -197,7 +197,8 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
     const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * NB) * D * BS;
-    const int64_t row_id = ((int64_t)b * Hq + h) * NB + i;
+    // block lists are per query head, or per KV head when the group shares its selection
+    const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
     const int n_sel = cnt[row_id];
     const int n_st = n_sel * NSUB;
@@ -509,7 +510,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal);
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared);
     return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@ constexpr int kMaxBlocks = 4096;  // NB limit: one score row must fit a wave's L
 struct Dims {
     int B, Hq, Hkv, G, S, D, Bs, NB, T;
     int ns, nl, k;
+    int shared;                   // 1: block lists are per KV head (group-shared selection)
     int stride, n_dense, reach;   // strided static columns, dense bottom strip, reach of the strided columns (0 = off)
     float scale;
 };
@@ -22,6 +23,7 @@ inline Dims dims_of(const spa_params& p) {
     d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
     d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = (p.seq_len + p.block_size - 1) / p.block_size;   // the last block may be partial
     d.ns = p.n_sink_blocks; d.nl = p.n_local_blocks; d.k = p.top_k_blocks;
+    d.shared = p.lists_per_kv_head != 0;
     d.stride = p.stride_blocks; d.n_dense = p.n_dense_q_blocks; d.reach = p.stride_reach_blocks;
     int64_t far = d.NB - 1;
     if (d.reach > 0 && d.reach - 1 < far) far = d.reach - 1;
@@ -37,6 +39,8 @@ inline Strides strides_of(const int64_t s[3]) { return Strides{s[0], s[1], s[2]}
 // Launchers (one per kernel file).  Each returns a hipError_t from the launch.
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        float* qp, float* kp, hipStream_t st);
+// qg[b, kv head, :] = mean over the G query heads of the group of qp[b, head, :]  (n = NB * D values per head)
+hipError_t launch_group_mean(const Dims& d, const float* qp, float* qg, hipStream_t st);
 // lvn [B*Hkv, NB] fp32: ln of the mean value-vector norm of every key block.
 hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st);
 // k_rows: optional device array of NB per-query-block budgets (clamped to [0, d.k] in the kernel).

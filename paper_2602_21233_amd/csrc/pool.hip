@@ -133,6 +133,22 @@ __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__
     }
 }
 
+// group-shared selection: the pooled queries of the G heads of a KV group are averaged
+__global__ __launch_bounds__(256) void group_mean_kernel(const float4* __restrict__ qp, float4* __restrict__ qg, int G,
+                                                         int64_t n4 /* float4 per head */, int64_t total4) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (x >= total4) return;
+    const int64_t head = x / n4, within = x % n4;      // head = b * Hkv + kv head
+    const float4* src = qp + head * G * n4 + within;
+    float4 acc = src[0];
+    for (int g = 1; g < G; ++g) {
+        const float4 t = src[g * n4];
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+    const float inv = 1.0f / (float)G;
+    qg[x] = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+}
+
 template <int D, int BS>
 hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
     dim3 grid(d.NB, d.B * d.Hkv);
@@ -141,6 +157,13 @@ hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipSt
 }
 
 }  // namespace
+
+hipError_t launch_group_mean(const Dims& d, const float* qp, float* qg, hipStream_t st) {
+    const int64_t n4 = (int64_t)d.NB * d.D / 4, total4 = n4 * d.B * d.Hkv;
+    hipLaunchKernelGGL(group_mean_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, st,
+                       (const float4*)qp, (float4*)qg, d.G, n4, total4);
+    return hipGetLastError();
+}
 
 hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
     if (d.D == 128 && d.Bs == 128) return launch_vn<128, 128>(d, v, vs, lvn, st);

@@ -64,7 +64,7 @@ def test_row_capacity_and_workspace(lib):
     (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(seq_len=0), -2),
     (dict(n_q_heads=5), -2), (dict(batch=0), -2), (dict(seq_len=128 * 4097), -2),
     (dict(n_local_blocks=0), -3), (dict(n_sink_blocks=-1), -3), (dict(top_k_blocks=-2), -3),
-    (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3), (dict(stride_reach_blocks=-1), -3),
+    (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3), (dict(stride_reach_blocks=-1), -3), (dict(lists_per_kv_head=2), -3),
     (dict(softmax_scale=-1.0), -2),
 ])
 def test_bad_params_rejected_on_host(lib, kw, code):

@@ -537,6 +537,32 @@ def test_fused_sampled_128k_headline_workload(spa, oracle):
     _sampled_workload_check(spa, oracle, 3, n_random=4)
 
 
+# ------------------------------------------- group-shared selection (lists per KV head)
+@pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k", [(2, 4, 2, 21, 128, 64, 1, 4, 6), (1, 8, 2, 70, 128, 128, 2, 3, 9),
+                                                      (1, 3, 1, 40, 64, 64, 1, 2, 5)])
+def test_group_shared_selection(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k):
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 61)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    G = Hq // Hkv
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, group_shared=True)
+    assert idx.shape[:3] == (B, Hkv, NB) and sp.shape == (B, Hkv, NB, NB)
+    o_idx, o_cnt, o_sp, *_ = oracle.select(q, kk, Bs, ns, nl, k, group_shared=True)
+    tri = torch.tril(torch.ones(NB, NB, dtype=torch.bool))
+    torch.testing.assert_close(sp.cpu()[..., tri], o_sp[..., tri], rtol=1e-4, atol=1e-5)
+    g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    assert torch.equal(cnt.cpu(), o_cnt)
+    # attention with the shared lists == attention with the same lists repeated for every head of the group
+    out, lse = spa.attn(dq, dk, dv, idx, cnt, Bs, return_lse=True, group_shared=True)
+    idx_h, cnt_h = idx.repeat_interleave(G, dim=1).contiguous(), cnt.repeat_interleave(G, dim=1).contiguous()
+    out_h, lse_h = spa.attn(dq, dk, dv, idx_h, cnt_h, Bs, return_lse=True)
+    assert torch.equal(out, out_h) and torch.equal(lse, lse_h)
+    want, want_lse = oracle.attn(q, kk, v, idx_h.cpu(), cnt_h.cpu(), Bs)
+    _assert_attn_close(out, want)
+    fused, idx2, cnt2 = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lists=True, group_shared=True)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt) and torch.equal(fused, out)
+
+
 # ------------------------------ sequence length not a multiple of the block size
 @pytest.mark.parametrize("S,D,Bs", [(8 * 64 + 1, 64, 64), (5 * 128 + 77, 128, 128), (37 * 64 + 63, 128, 64), (100, 64, 128),
                                     (3 * 128 + 127, 64, 128), (9 * 128 + 32, 128, 128), (9 * 128 + 33, 128, 128)])
