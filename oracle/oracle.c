@@ -34,6 +34,11 @@
  * patterns (uint16).  NB = ceil(S/Bs): the last block may be partial (it then
  * holds S - (NB-1)*Bs tokens; block means are taken over the tokens that exist,
  * and tokens past S neither attend nor are attended to).  T = min(NB, ns+nl+k).
+ * KV prefix (chunked prefill): the queries may be the last Sq tokens of a
+ * sequence of Skv = P + Sq tokens whose keys and values are all present, P a
+ * multiple of Bs.  Query block i then sits at block position i + off, off = P/Bs,
+ * of NBk = off + NBq key blocks; everything below is written for that case and
+ * off = 0 is the plain one.
  */
 #include <math.h>
 #include <stdint.h>
@@ -68,21 +73,22 @@ int oracle_pool(const uint16_t *x, int64_t n_heads_total, int64_t S, int64_t D,
 }
 
 /* Step 2 (pattern computation, scoring): sp[b,h,i,j] = scale * <qp[b,h,i,:],
- * kp[b,h/G,j,:]> for j <= i, from the fp32 pooled values, fp64 accumulate, one
- * rounding to fp32.  Entries with j > i are set to -inf. */
+ * kp[b,h/G,j,:]> for j <= i + off, from the fp32 pooled values, fp64 accumulate,
+ * one rounding to fp32.  Entries with j > i + off are set to -inf.
+ * qp [B,Hq,NBq,D], kp [B,Hkv,NBk,D], sp [B,Hq,NBq,NBk], off = NBk - NBq. */
 int oracle_scores(const float *qp, const float *kp, int64_t B, int64_t Hq,
-                  int64_t Hkv, int64_t NB, int64_t D, float scale, float *sp) {
-    if (Hkv <= 0 || Hq % Hkv) return -1;
-    int64_t G = Hq / Hkv;
+                  int64_t Hkv, int64_t NBq, int64_t NBk, int64_t D, float scale, float *sp) {
+    if (Hkv <= 0 || Hq % Hkv || NBk < NBq) return -1;
+    int64_t G = Hq / Hkv, off = NBk - NBq;
 #pragma omp parallel for collapse(3) schedule(static)
     for (int64_t b = 0; b < B; ++b)
         for (int64_t h = 0; h < Hq; ++h)
-            for (int64_t i = 0; i < NB; ++i) {
-                const float *qrow = qp + ((b * Hq + h) * NB + i) * D;
-                float *srow = sp + ((b * Hq + h) * NB + i) * NB;
-                for (int64_t j = 0; j < NB; ++j) {
-                    if (j > i) { srow[j] = -INFINITY; continue; }
-                    const float *krow = kp + ((b * Hkv + h / G) * NB + j) * D;
+            for (int64_t i = 0; i < NBq; ++i) {
+                const float *qrow = qp + ((b * Hq + h) * NBq + i) * D;
+                float *srow = sp + ((b * Hq + h) * NBq + i) * NBk;
+                for (int64_t j = 0; j < NBk; ++j) {
+                    if (j > i + off) { srow[j] = -INFINITY; continue; }
+                    const float *krow = kp + ((b * Hkv + h / G) * NBk + j) * D;
                     double acc = 0.0;
                     for (int64_t d = 0; d < D; ++d)
                         acc += (double)qrow[d] * (double)krow[d];
@@ -126,16 +132,16 @@ int oracle_vnorm(const uint16_t *v, int64_t n_heads_total, int64_t S, int64_t D,
 }
 
 int oracle_scores_oam(float *sp, const float *vn, int64_t B, int64_t Hq, int64_t Hkv,
-                      int64_t NB) {
-    if (Hkv <= 0 || Hq % Hkv) return -1;
-    int64_t G = Hq / Hkv;
+                      int64_t NBq, int64_t NBk) {
+    if (Hkv <= 0 || Hq % Hkv || NBk < NBq) return -1;
+    int64_t G = Hq / Hkv, off = NBk - NBq;
 #pragma omp parallel for collapse(3) schedule(static)
     for (int64_t b = 0; b < B; ++b)
         for (int64_t h = 0; h < Hq; ++h)
-            for (int64_t i = 0; i < NB; ++i) {
-                float *srow = sp + ((b * Hq + h) * NB + i) * NB;
-                const float *vrow = vn + (b * Hkv + h / G) * NB;
-                for (int64_t j = 0; j <= i; ++j)
+            for (int64_t i = 0; i < NBq; ++i) {
+                float *srow = sp + ((b * Hq + h) * NBq + i) * NBk;
+                const float *vrow = vn + (b * Hkv + h / G) * NBk;
+                for (int64_t j = 0; j <= i + off; ++j)
                     srow[j] = (float)((double)srow[j] + log((double)vrow[j]));
             }
     return 0;
@@ -188,20 +194,22 @@ int64_t oracle_row_capacity(int64_t NB, int64_t ns, int64_t nl, int64_t k, int64
 
 static int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_max,
+int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk, int64_t ns_max,
                 int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
                 int64_t n_dense, int64_t reach, const int32_t *head_pattern, int64_t Hq,
                 int32_t *idx, int32_t *cnt) {
     if (ns_max < 0 || nl_max < 1 || k_max < 0 || stride < 0 || n_dense < 0 || reach < 0) return -1;
     if (head_pattern && Hq < 1) return -1;
-    const int64_t ns0 = ns_max, nl0 = nl_max, k0 = k_max;
-    int64_t T = oracle_row_capacity(NB, ns0, nl0, k0, stride, n_dense, reach);
+    if (NBk < NBq) return -1;
+    const int64_t ns0 = ns_max, nl0 = nl_max, k0 = k_max, off = NBk - NBq;
+    int64_t T = oracle_row_capacity(NBk, ns0, nl0, k0, stride, n_dense, reach);
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int64_t n = 0; n < n_heads_total; ++n)
-        for (int64_t i = 0; i < NB; ++i) {
-            const float *srow = sp + (n * NB + i) * NB;
-            int32_t *orow = idx + (n * NB + i) * T;
+        for (int64_t iq = 0; iq < NBq; ++iq) {
+            const int64_t i = iq + off;           /* block position of query block iq in the sequence */
+            const float *srow = sp + (n * NBq + iq) * NBk;
+            int32_t *orow = idx + (n * NBq + iq) * T;
             int64_t ns = ns0, nl = nl0, k = k0;
             if (head_pattern) {
                 const int32_t *hp = head_pattern + 3 * (n % Hq);
@@ -210,7 +218,7 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
                 k = clamp64(hp[2], 0, k0);
             }
             /* state[j]: 0 = candidate, 1 = selected */
-            unsigned char *sel = (unsigned char *)calloc((size_t)NB, 1);
+            unsigned char *sel = (unsigned char *)calloc((size_t)NBk, 1);
             if (!sel) {
 #pragma omp atomic write
                 fail = 1;
@@ -220,12 +228,12 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
                 int is_sink = j < ns;
                 int is_local = j >= i - nl + 1;
                 int is_strided = stride > 0 && (i - j) % stride == 0 && (reach == 0 || i - j < reach);
-                int is_dense_row = i >= NB - n_dense;
+                int is_dense_row = i >= NBk - n_dense;
                 sel[j] = (unsigned char)(is_sink || is_local || is_strided || is_dense_row);
             }
             int64_t k_i = k;
-            if (k_row) {
-                k_i = clamp64(k_row[i], 0, k0);
+            if (k_row) {                          /* one entry per query block of this call */
+                k_i = clamp64(k_row[iq], 0, k0);
                 if (k_i > k) k_i = k;
             }
             for (int64_t pick = 0; pick < k_i; ++pick) {
@@ -240,7 +248,7 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
             int64_t c = 0;
             for (int64_t j = 0; j <= i; ++j)
                 if (sel[j]) orow[c++] = (int32_t)j;
-            cnt[n * NB + i] = (int32_t)c;
+            cnt[n * NBq + iq] = (int32_t)c;
             for (; c < T; ++c) orow[c] = -1;
             free(sel);
         }
@@ -248,7 +256,8 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
 }
 
 /* Step 5 (sparse attention on the located regions).  For query token t in
- * block i: keys = { s : s/Bs in Sel_i, s <= t }, logits x_s = scale * q_t.k_s,
+ * block i (sequence position P + t with a KV prefix of P tokens):
+ * keys = { s : s/Bs in Sel_i, s <= P + t }, logits x_s = scale * q_t.k_s,
  * m = max x_s, p_s = exp(x_s - m), out_t = sum p_s v_s / sum p_s,
  * lse_t = m + log sum p_s.  Everything in fp64; results rounded once to fp32.
  *
@@ -256,12 +265,13 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NB, int64_t ns_m
  * all of them in (b,h,i) order, so out is then laid out [B,Hq,S,D].
  * out: [n_rows, Bs, D] fp32; lse: [n_rows, Bs] fp32 (may be NULL). */
 int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
-                int64_t B, int64_t Hq, int64_t Hkv, int64_t S, int64_t D,
+                int64_t B, int64_t Hq, int64_t Hkv, int64_t S, int64_t Skv, int64_t D,
                 int64_t Bs, int64_t T, float scale, const int32_t *idx,
                 const int32_t *cnt, const int32_t *rows, int64_t n_rows,
                 float *out, float *lse) {
-    if (Hkv <= 0 || Hq % Hkv || Bs <= 0 || S <= 0) return -1;
-    int64_t G = Hq / Hkv, NB = (S + Bs - 1) / Bs;
+    if (Hkv <= 0 || Hq % Hkv || Bs <= 0 || S <= 0 || Skv < S || (Skv - S) % Bs) return -1;
+    /* S query tokens = the last S of Skv; P = Skv - S tokens of KV prefix */
+    int64_t G = Hq / Hkv, NB = (S + Bs - 1) / Bs, P = Skv - S;
     if (!rows) n_rows = B * Hq * NB;
     int fail = 0;
 #pragma omp parallel for collapse(2) schedule(dynamic, 4)
@@ -281,8 +291,8 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                 continue;
             }
             const uint16_t *qt = q + ((b * Hq + h) * S + t) * D;
-            const uint16_t *kh = k + ((b * Hkv + h / G) * S) * D;
-            const uint16_t *vh = v + ((b * Hkv + h / G) * S) * D;
+            const uint16_t *kh = k + ((b * Hkv + h / G) * Skv) * D;
+            const uint16_t *vh = v + ((b * Hkv + h / G) * Skv) * D;
             const int32_t *sel = idx + ((b * Hq + h) * NB + i) * T;
             int64_t c = cnt[(b * Hq + h) * NB + i];
             double *x = (double *)malloc(sizeof(double) * (size_t)(c * Bs + 1));
@@ -298,7 +308,7 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             for (int64_t e = 0; e < c; ++e)
                 for (int64_t u = 0; u < Bs; ++u) {
                     int64_t s = (int64_t)sel[e] * Bs + u;
-                    if (s > t) continue; /* causal; t < S, so keys past the end never pass */
+                    if (s > P + t) continue; /* causal; P + t < Skv, so keys past the end never pass */
                     double dot = 0.0;
                     for (int64_t d = 0; d < D; ++d)
                         dot += bf16_to_f64(qt[d]) * bf16_to_f64(kh[s * D + d]);

@@ -35,13 +35,13 @@ def _load():
         lib = ctypes.CDLL(build())
         i64, f32, vp = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
         lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
-        lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, f32, vp]
-        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, vp, i64, i64, i64, vp, i64, vp, vp]
+        lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, f32, vp]
+        lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, i64, vp, i64, i64, i64, vp, i64, vp, vp]
         lib.oracle_row_capacity.argtypes = [i64] * 7
         lib.oracle_row_capacity.restype = ctypes.c_int64
         lib.oracle_vnorm.argtypes = [vp, i64, i64, i64, i64, vp]
-        lib.oracle_scores_oam.argtypes = [vp, vp, i64, i64, i64, i64]
-        lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, f32,
+        lib.oracle_scores_oam.argtypes = [vp, vp, i64, i64, i64, i64, i64]
+        lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, f32,
                                     vp, vp, vp, i64, vp, vp]
         for f in (lib.oracle_pool, lib.oracle_scores, lib.oracle_topk, lib.oracle_attn,
                   lib.oracle_num_threads, lib.oracle_vnorm, lib.oracle_scores_oam):
@@ -83,13 +83,14 @@ def pool(x: torch.Tensor, block_size: int) -> torch.Tensor:
 
 
 def scores(qp: torch.Tensor, kp: torch.Tensor, scale: float) -> torch.Tensor:
-    """qp [B,Hq,NB,D], kp [B,Hkv,NB,D] fp32 -> [B,Hq,NB,NB] fp32 (j>i: -inf)."""
+    """qp [B,Hq,NBq,D], kp [B,Hkv,NBk,D] fp32 -> [B,Hq,NBq,NBk] fp32 (j > i + NBk - NBq: -inf).
+    NBk > NBq is a KV prefix: the query blocks are the last NBq of the NBk blocks."""
     B, Hq, NB, D = qp.shape
-    Hkv = kp.shape[1]
+    Hkv, NBk = kp.shape[1], kp.shape[2]
     qp, kp = qp.contiguous(), kp.contiguous()
     assert qp.dtype == torch.float32 and kp.dtype == torch.float32
-    sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32)
-    _check(_load().oracle_scores(qp.data_ptr(), kp.data_ptr(), B, Hq, Hkv, NB, D, scale,
+    sp = torch.empty((B, Hq, NB, NBk), dtype=torch.float32)
+    _check(_load().oracle_scores(qp.data_ptr(), kp.data_ptr(), B, Hq, Hkv, NB, NBk, D, scale,
                                  sp.data_ptr()), "scores")
     return sp
 
@@ -105,26 +106,27 @@ def vnorm(v: torch.Tensor, block_size: int) -> torch.Tensor:
 
 def scores_oam(sp: torch.Tensor, vn: torch.Tensor) -> torch.Tensor:
     """Output-aware scores: sp[b,h,i,j] + ln vn[b,h/G,j] for j <= i (a copy; j > i untouched)."""
-    B, Hq, NB, _ = sp.shape
+    B, Hq, NB, NBk = sp.shape
     Hkv = vn.shape[1]
     out = sp.contiguous().clone()
     vn = vn.contiguous()
-    assert out.dtype == torch.float32 and vn.dtype == torch.float32 and vn.shape == (B, Hkv, NB)
-    _check(_load().oracle_scores_oam(out.data_ptr(), vn.data_ptr(), B, Hq, Hkv, NB), "scores_oam")
+    assert out.dtype == torch.float32 and vn.dtype == torch.float32 and vn.shape == (B, Hkv, NBk)
+    _check(_load().oracle_scores_oam(out.data_ptr(), vn.data_ptr(), B, Hq, Hkv, NB, NBk), "scores_oam")
     return out
 
 
 def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | None = None,
          stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0):
-    """sp [B,Hq,NB,NB] fp32 -> idx [B,Hq,NB,T] int32 (pad -1), cnt [B,Hq,NB] int32.
+    """sp [B,Hq,NBq,NBk] fp32 -> idx [B,Hq,NBq,T] int32 (pad -1), cnt [B,Hq,NBq] int32; NBk > NBq
+    is a KV prefix of NBk - NBq blocks (pattern and capacity then refer to positions in NBk).
     k_per_row: optional [NB] int32 position-dependent budget (clamped to [0, k]).
     stride / n_dense: strided static columns and the dense bottom strip of the Tri-shape.
     head_pattern: optional [Hq,3] int32 (n_sink, n_local, top_k) per query head; ns, nl, k are
     then the maxima."""
-    B, Hq, NB, _ = sp.shape
+    B, Hq, NB, NBk = sp.shape
     sp = sp.contiguous()
     assert sp.dtype == torch.float32
-    T = row_capacity(NB, ns, nl, k, stride, n_dense, reach)
+    T = row_capacity(NBk, ns, nl, k, stride, n_dense, reach)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32)
     kr_ptr = None
@@ -137,7 +139,7 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
         head_pattern = head_pattern.to(torch.int32).contiguous()
         assert head_pattern.shape == (Hq, 3) and head_pattern.device.type == "cpu"
         hp_ptr = head_pattern.data_ptr()
-    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr, Hq,
+    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, NBk, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr, Hq,
                                idx.data_ptr(), cnt.data_ptr()), "topk")
     return idx, cnt
 
@@ -171,7 +173,7 @@ def attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, c
     """Block-sparse causal attention.  rows=None: out [B,Hq,S,D], lse [B,Hq,S];
     rows=[(b,h,i),...]: out [n,Bs,D], lse [n,Bs].  fp32 results of fp64 math."""
     B, Hq, S, D = q.shape
-    Hkv = k.shape[1]
+    Hkv, Skv = k.shape[1], k.shape[2]            # Skv > S: the queries are the last S tokens (KV prefix)
     T = idx.shape[-1]
     scale = default_scale(D) if scale is None else scale
     qb, kb, vb = _bits(q), _bits(k), _bits(v)
@@ -188,7 +190,7 @@ def attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, c
         out = torch.empty((n, block_size, D), dtype=torch.float32)
         lse = torch.empty((n, block_size), dtype=torch.float32)
         rows_ptr = rows_t.data_ptr()
-    _check(_load().oracle_attn(qb.data_ptr(), kb.data_ptr(), vb.data_ptr(), B, Hq, Hkv, S, D,
+    _check(_load().oracle_attn(qb.data_ptr(), kb.data_ptr(), vb.data_ptr(), B, Hq, Hkv, S, Skv, D,
                                block_size, T, scale, idx.data_ptr(), cnt.data_ptr(), rows_ptr, n,
                                out.data_ptr(), lse.data_ptr()), "attn")
     return out, lse

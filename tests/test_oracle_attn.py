@@ -222,3 +222,38 @@ def test_ragged_pooling_averages_the_tokens_that_exist(oracle):
     vn = oracle.vnorm(x, Bs)
     want = np.linalg.norm(xd[:, :, 24:29], axis=-1).mean(-1)
     np.testing.assert_allclose(vn[:, :, 3].numpy(), want, rtol=2e-7)
+
+
+# ---- KV prefix (chunked prefill): the queries are the last tokens of a longer sequence ----
+
+@pytest.mark.parametrize("Sq,P,Bs", [(24, 16, 8), (19, 32, 8), (8, 8, 8), (33, 48, 16)])
+def test_prefix_call_equals_the_rows_of_the_full_run(oracle, Sq, P, Bs):
+    """Every step is local to a query block, so running only the last Sq tokens against the full
+    K/V must reproduce the full run's rows: pooled scores, lists and attention."""
+    B, Hq, Hkv, D, ns, nl, k = 1, 4, 2, 16, 1, 2, 2
+    S = P + Sq
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 80 + Sq)
+    off = P // Bs
+    idx_f, cnt_f, sp_f, *_ = oracle.select(q, kk, Bs, ns, nl, k, v=v)
+    out_f, lse_f = oracle.attn(q, kk, v, idx_f, cnt_f, Bs)
+    qc = q[:, :, P:].contiguous()
+    idx_c, cnt_c, sp_c, *_ = oracle.select(qc, kk, Bs, ns, nl, k, v=v)
+    assert sp_c.shape == (B, Hq, -(-Sq // Bs), -(-S // Bs))
+    assert torch.equal(sp_c, sp_f[:, :, off:]) and torch.equal(idx_c, idx_f[:, :, off:]) and torch.equal(cnt_c, cnt_f[:, :, off:])
+    out_c, lse_c = oracle.attn(qc, kk, v, idx_c, cnt_c, Bs)
+    assert torch.equal(out_c, out_f[:, :, P:]) and torch.equal(lse_c, lse_f[:, :, P:])
+
+
+def test_prefix_all_blocks_equals_dense_causal_rows(oracle):
+    B, Hq, Hkv, D, Bs, P, Sq = 1, 2, 1, 16, 8, 24, 21
+    S = P + Sq
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 91)
+    qc = q[:, :, P:].contiguous()
+    NBq, NBk = -(-Sq // Bs), -(-S // Bs)
+    sp = torch.zeros((B, Hq, NBq, NBk))
+    idx, cnt = oracle.topk(sp, 0, 1, NBk)
+    assert all(int(cnt[0, 0, i]) == i + P // Bs + 1 for i in range(NBq))
+    out, _ = oracle.attn(qc, kk, v, idx, cnt, Bs)
+    ref = F.scaled_dot_product_attention(q.float(), kk.float().repeat_interleave(2, 1), v.float().repeat_interleave(2, 1),
+                                         is_causal=True)[:, :, P:]
+    torch.testing.assert_close(out, ref, rtol=1e-4, atol=1e-5)
