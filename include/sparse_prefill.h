@@ -21,7 +21,7 @@
  *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t passed
  *     as void*, NULL = the default stream) and completes asynchronously.
  *   - Q is [batch, n_q_heads, seq_len, head_dim], K and V are
- *     [batch, n_kv_heads, seq_len, head_dim], OUT has Q's shape; bf16.  The
+ *     [batch, n_kv_heads, kv_prefix_len + seq_len, head_dim], OUT has Q's shape; bf16.  The
  *     strides (in elements) of the batch, head and token axes come from
  *     `*_stride`; the head_dim axis is contiguous.  Base pointers must be
  *     16-byte aligned and every stride a multiple of 8 elements.
@@ -89,6 +89,14 @@ typedef struct spa_params {
     int32_t stride_reach_blocks; /* >= 0.  r > 0 (Dilated): the strided blocks count only while
                                  i - j < r, i.e. a local window of r / s blocks with dilation s;
                                  0 = the whole sequence.  Ignored when stride_blocks == 0     */
+    int32_t kv_prefix_len;    /* >= 0, multiple of block_size.  P > 0 (chunked prefill): K and V hold
+                                 P + seq_len tokens and the seq_len queries are the last of them.
+                                 Query block i then has block position i + P / block_size among
+                                 NBk = P / block_size + NB key blocks: the causal limit, the static
+                                 pattern, the row capacity (with NBk in place of NB) and the key
+                                 axis of the score output refer to those positions; block_idx and
+                                 block_cnt keep one row per query block of the call, and a budget
+                                 schedule one entry per query block of the call.  NBk <= 4096     */
     int32_t lists_per_kv_head; /* 0 or 1.  1 (group-shared selection): one list per KV head, shared
                                  by the n_q_heads / n_kv_heads query heads of its group; the group
                                  is ranked by the mean of its heads' pooled scores.  block_idx,

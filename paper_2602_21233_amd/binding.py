@@ -33,7 +33,8 @@ class SpaParams(ctypes.Structure):
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
                 ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32),
-                ("stride_reach_blocks", ctypes.c_int32), ("lists_per_kv_head", ctypes.c_int32)]
+                ("stride_reach_blocks", ctypes.c_int32), ("kv_prefix_len", ctypes.c_int32),
+                ("lists_per_kv_head", ctypes.c_int32)]
 
 
 class SpaSelectOpts(ctypes.Structure):
@@ -92,7 +93,7 @@ def _strides(t):
 
 def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, n_sink_blocks,
                 n_local_blocks, top_k_blocks, softmax_scale=None, q=None, k=None, v=None, out=None,
-                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0, lists_per_kv_head=0) -> SpaParams:
+                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0, lists_per_kv_head=0, kv_prefix_len=0) -> SpaParams:
     p = SpaParams()
     p.batch, p.n_q_heads, p.n_kv_heads = batch, n_q_heads, n_kv_heads
     p.seq_len, p.head_dim, p.block_size = seq_len, head_dim, block_size
@@ -100,6 +101,7 @@ def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, 
     p.stride_blocks, p.n_dense_q_blocks = stride_blocks, n_dense_q_blocks
     p.stride_reach_blocks = stride_reach_blocks
     p.lists_per_kv_head = int(lists_per_kv_head)
+    p.kv_prefix_len = kv_prefix_len
     p.softmax_scale = 0.0 if softmax_scale is None else float(softmax_scale)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = _strides(q), _strides(k), _strides(v), _strides(out)
     return p
@@ -112,7 +114,7 @@ def _params_from(q, k, block_size, ns, nl, topk, scale, v=None, out=None, stride
                        block_size=block_size, n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=topk,
                        softmax_scale=scale, q=q, k=k, v=v, out=out, stride_blocks=stride_blocks,
                        n_dense_q_blocks=n_dense_q_blocks, stride_reach_blocks=stride_reach_blocks,
-                       lists_per_kv_head=group_shared)
+                       lists_per_kv_head=group_shared, kv_prefix_len=k.shape[2] - S)
 
 
 def _ptr(t):
@@ -173,7 +175,7 @@ def pool(q, k, block_size):
     B, Hq, S, D = q.shape
     NB = -(-S // block_size)
     qp = torch.empty((B, Hq, NB, D), dtype=torch.float32, device=q.device)
-    kp = torch.empty((B, k.shape[1], NB, D), dtype=torch.float32, device=q.device)
+    kp = torch.empty((B, k.shape[1], -(-k.shape[2] // block_size), D), dtype=torch.float32, device=q.device)
     _check(load_library().sparse_prefill_pool(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(qp), _ptr(kp), _stream(q)))
     return qp, kp
 
@@ -205,7 +207,8 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     NB, T = -(-S // block_size), row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device)
-    sp = torch.empty((B, Hq, NB, NB), dtype=torch.float32, device=q.device) if return_scores else None
+    NBk = -(-k.shape[2] // block_size)               # key blocks (more than NB with a KV prefix)
+    sp = torch.empty((B, Hq, NB, NBk), dtype=torch.float32, device=q.device) if return_scores else None
     ws = _workspace(p, q.device) if workspace is None else workspace
     if head_pattern is not None:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
@@ -233,8 +236,9 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
     """sparse_prefill_topk_from_scores (…_tpd with a schedule) on [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
         raise TypeError("expected contiguous fp32 scores on the GPU")
-    B, Hq, NB, _ = scores.shape
+    B, Hq, NB, NBk = scores.shape                    # NBk > NB: a KV prefix of NBk - NB blocks
     p = make_params(batch=B, n_q_heads=Hq, n_kv_heads=Hq, seq_len=NB * 64, head_dim=64, block_size=64,
+                    kv_prefix_len=(NBk - NB) * 64,
                     n_sink_blocks=n_sink_blocks, n_local_blocks=n_local_blocks, top_k_blocks=top_k_blocks,
                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
                     stride_reach_blocks=stride_reach_blocks)

@@ -17,7 +17,8 @@ int check_shape(const spa_params* p) {
     if (p->n_q_heads % p->n_kv_heads) return SPA_ERR_BAD_SHAPE;
     if (p->head_dim != 64 && p->head_dim != 128) return SPA_ERR_BAD_SHAPE;
     if (p->block_size != 64 && p->block_size != 128) return SPA_ERR_BAD_SHAPE;
-    if ((p->seq_len + p->block_size - 1) / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
+    if (p->kv_prefix_len < 0 || p->kv_prefix_len % p->block_size) return SPA_ERR_BAD_SHAPE;
+    if (((int64_t)p->kv_prefix_len + p->seq_len + p->block_size - 1) / p->block_size > kMaxBlocks) return SPA_ERR_BAD_SHAPE;
     if ((int64_t)p->batch * p->n_q_heads * ((p->seq_len + p->block_size - 1) / p->block_size) > 0x7fffffffLL) return SPA_ERR_BAD_SHAPE;
     if (p->n_sink_blocks < 0 || p->n_local_blocks < 1 || p->top_k_blocks < 0) return SPA_ERR_BAD_PATTERN;
     if (p->lists_per_kv_head != 0 && p->lists_per_kv_head != 1) return SPA_ERR_BAD_PATTERN;
@@ -49,13 +50,13 @@ Workspace carve(const Dims& d) {
     Workspace w;
     size_t off = 0;
     w.qp_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.D * sizeof(float));
-    w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
+    w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * d.D * sizeof(float));
     w.qg_off = off; if (d.shared) off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
     w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
-    w.lvn_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NB * sizeof(float));
+    w.lvn_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * sizeof(float));
     w.vt_off = off;
-    if (d.D == 128) off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.Bs * d.D * sizeof(uint16_t));
+    if (d.D == 128) off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * d.Bs * d.D * sizeof(uint16_t));
     w.total = off;
     return w;
 }
@@ -141,7 +142,7 @@ const char* spa_strerror(int code) {
     switch (code) {
         case SPA_OK: return "ok";
         case SPA_ERR_NULLPTR: return "a required pointer is NULL";
-        case SPA_ERR_BAD_SHAPE: return "unsupported shape (head_dim and block_size must be 64 or 128, at most 4096 blocks per sequence, n_q_heads a multiple of n_kv_heads)";
+        case SPA_ERR_BAD_SHAPE: return "unsupported shape (head_dim and block_size must be 64 or 128, at most 4096 key blocks, kv_prefix_len a non-negative multiple of block_size, n_q_heads a multiple of n_kv_heads)";
         case SPA_ERR_BAD_PATTERN: return "bad static pattern or budget (need n_sink >= 0, n_local >= 1, top_k >= 0, stride >= 0, n_dense >= 0)";
         case SPA_ERR_BAD_STRIDE: return "strides must be non-negative multiples of 8 elements, token stride >= head_dim, pointers 16-byte aligned";
         case SPA_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than spa_workspace_bytes()";

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ v, Strides vs, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, uint16_t* __restrict__ out, Strides os, float* __restrict__ lse,
-    int Hq, int G, int NB, int T, int S, float scale, int shared) {
+    int Hq, int G, int NB, int T, int S, float scale, int shared, int Skv) {
     constexpr int NT = BS * 2;        // threads
     constexpr int KC = BS / 32;       // 32-key chunks of a key tile
     constexpr int DS = D / 16;        // 16-wide slices of head_dim (QK^T reduction)
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     auto fetch = [&](int blk) {
         const uint16_t* kt = kb + (int64_t)blk * BS * ks.t;
         const uint16_t* vt = vb + (int64_t)blk * BS * vs.t;
-        const int last_row = S - 1 - blk * BS;          // >= BS - 1 except in a partial last block
+        const int last_row = Skv - 1 - blk * BS;        // >= BS - 1 except in a partial last block
 #pragma unroll
         for (int p = 0; p < CPT; ++p) {
             int cidx = p * NT + tid;
@@ -228,7 +228,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     int64_t nwg = (int64_t)d.B * d.Hq * d.NB;
     hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st,
                        (const uint16_t*)q, qs, (const uint16_t*)k, ks, (const uint16_t*)v, vs, idx, cnt,
-                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared);
+                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared, d.Skv);
     return hipGetLastError();
 }
 

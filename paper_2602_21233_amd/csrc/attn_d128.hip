@@ -152,7 +152,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale, RowDeal deal, int shared) {
+    float scale, RowDeal deal, int shared, int NBk, int Skv) {
     constexpr int NW = BS / 32;         // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
-    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * NB) * D * BS;
+    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * NBk) * D * BS;      // K, V, V^T may carry a prefix
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     auto issue_k = [&](auto buf_tag, int st, int blk) {
         constexpr int BUF = decltype(buf_tag)::value;
         const int sub = st % NSUB;
-        if ((blk + 1) * BS <= S) {
+        if ((blk + 1) * BS <= Skv) {
             const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + sub * KT) * ks.t);
             static_for<LPW>([&](auto x_tag) {
                 constexpr int X = decltype(x_tag)::value;
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
             // partial last block (only ever the diagonal block of the last query block): key rows past
             // the end re-read the last token; they are masked for every query that exists
             const char* kt = reinterpret_cast<const char*>(kb + (int64_t)blk * BS * ks.t);
-            const int last_row = S - 1 - blk * BS;
+            const int last_row = Skv - 1 - blk * BS;
             static_for<LPW>([&](auto x_tag) {
                 constexpr int X = decltype(x_tag)::value;
                 const int krow = 4 * (wave * LPW + X) + (lane >> 4);
@@ -501,8 +501,8 @@ template <int BS>
 hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* v,
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
                   void* vt, hipStream_t st) {
-    hipLaunchKernelGGL((transpose_v_kernel<BS>), dim3(d.NB, d.B * d.Hkv), dim3(256), 0, st,
-                       (const uint16_t*)v, vs, d.Hkv, d.NB, d.S, (uint16_t*)vt);
+    hipLaunchKernelGGL((transpose_v_kernel<BS>), dim3(d.NBk, d.B * d.Hkv), dim3(256), 0, st,
+                       (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const RowDeal deal = deal_rows(d);
@@ -510,7 +510,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared);
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv);
     return hipGetLastError();
 }
 

@@ -11,7 +11,8 @@ constexpr int kMaxBlocks = 4096;  // NB limit: one score row must fit a wave's L
 
 // Derived sizes every launcher needs.
 struct Dims {
-    int B, Hq, Hkv, G, S, D, Bs, NB, T;
+    int B, Hq, Hkv, G, S, D, Bs, NB, T;   // S, NB: query tokens / query blocks of the call
+    int Skv, NBk, off;                    // key tokens, key blocks, block position of query block 0
     int ns, nl, k;
     int shared;                   // 1: block lists are per KV head (group-shared selection)
     int stride, n_dense, reach;   // strided static columns, dense bottom strip, reach of the strided columns (0 = off)
@@ -23,12 +24,13 @@ inline Dims dims_of(const spa_params& p) {
     d.B = p.batch; d.Hq = p.n_q_heads; d.Hkv = p.n_kv_heads; d.G = p.n_q_heads / p.n_kv_heads;
     d.S = p.seq_len; d.D = p.head_dim; d.Bs = p.block_size; d.NB = (p.seq_len + p.block_size - 1) / p.block_size;   // the last block may be partial
     d.ns = p.n_sink_blocks; d.nl = p.n_local_blocks; d.k = p.top_k_blocks;
+    d.off = p.kv_prefix_len / p.block_size; d.Skv = p.kv_prefix_len + p.seq_len; d.NBk = d.off + d.NB;
     d.shared = p.lists_per_kv_head != 0;
     d.stride = p.stride_blocks; d.n_dense = p.n_dense_q_blocks; d.reach = p.stride_reach_blocks;
-    int64_t far = d.NB - 1;
+    int64_t far = d.NBk - 1;
     if (d.reach > 0 && d.reach - 1 < far) far = d.reach - 1;
     int64_t t = (int64_t)d.ns + d.nl + d.k + (d.stride > 0 ? far / d.stride : 0);
-    d.T = (int)((t < d.NB && d.n_dense <= 0) ? t : d.NB);
+    d.T = (int)((t < d.NBk && d.n_dense <= 0) ? t : d.NBk);
     d.scale = p.softmax_scale;
     return d;
 }

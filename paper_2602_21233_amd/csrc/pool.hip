@@ -19,7 +19,8 @@ template <int D, int BS>
 __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ q, Strides qs,
                                                    int n_q_rows /* B*Hq or 0 */, int Hq,
                                                    const uint16_t* __restrict__ k, Strides ks, int Hkv,
-                                                   float* __restrict__ qp, float* __restrict__ kp, int NB, int S) {
+                                                   float* __restrict__ qp, float* __restrict__ kp, int NBq, int Sq,
+                                                   int NBk, int Skv) {
     constexpr int TPR = D / 8;          // lanes per token row
     constexpr int RPP = 256 / TPR;      // token rows per pass
     constexpr int PASSES = BS / RPP;
@@ -29,16 +30,20 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
     int hy = blockIdx.y;
     const uint16_t* src;
     float* dst;
+    int S;                                   // tokens of this tensor (K may carry a prefix)
     if (hy < n_q_rows) {
+        if (blk >= NBq) return;              // the grid spans the key blocks
         int b = hy / Hq, h = hy % Hq;
         src = q + b * qs.b + h * qs.h + (int64_t)blk * BS * qs.t;
-        dst = qp + ((int64_t)hy * NB + blk) * D;
+        dst = qp + ((int64_t)hy * NBq + blk) * D;
+        S = Sq;
         k = nullptr;
     } else {
         hy -= n_q_rows;
         int b = hy / Hkv, h = hy % Hkv;
         src = k + b * ks.b + h * ks.h + (int64_t)blk * BS * ks.t;
-        dst = kp + ((int64_t)hy * NB + blk) * D;
+        dst = kp + ((int64_t)hy * NBk + blk) * D;
+        S = Skv;
         qs = ks;
     }
     const int tid = threadIdx.x;
@@ -77,9 +82,9 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                   float* kp, hipStream_t st) {
     int nq = q ? d.B * d.Hq : 0, nk = k ? d.B * d.Hkv : 0;
     if (nq + nk == 0) return hipSuccess;
-    dim3 grid(d.NB, nq + nk);
+    dim3 grid(nk ? d.NBk : d.NB, nq + nk);
     hipLaunchKernelGGL((pool_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)q, qs, nq, d.Hq,
-                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S);
+                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S, d.NBk, d.Skv);
     return hipGetLastError();
 }
 
@@ -151,8 +156,8 @@ __global__ __launch_bounds__(256) void group_mean_kernel(const float4* __restric
 
 template <int D, int BS>
 hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
-    dim3 grid(d.NB, d.B * d.Hkv);
-    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NB, d.S, lvn);
+    dim3 grid(d.NBk, d.B * d.Hkv);
+    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, lvn);
     return hipGetLastError();
 }
 

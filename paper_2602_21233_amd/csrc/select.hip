@@ -48,12 +48,12 @@ struct Pattern {
     float inv_stride;
 };
 inline Pattern pattern_of(const Dims& d) {
-    return Pattern{d.ns, d.nl, d.stride, d.n_dense, d.NB, d.reach > 0 ? d.reach : d.NB,
+    return Pattern{d.ns, d.nl, d.stride, d.n_dense, d.NBk, d.reach > 0 ? d.reach : d.NBk,
                    d.stride > 0 ? 1.0f / (float)d.stride : 0.f};
 }
 inline bool extended(const Dims& d) { return d.stride > 0 || d.n_dense > 0; }
 
-// is key block j (0 <= j <= i) static for query block i?
+// is key block j (0 <= j <= i) static for the query block at block position i (pt.NB = key blocks)?
 template <bool EXT>
 __device__ __forceinline__ bool static_block(const Pattern& pt, int i, int j) {
     bool s = j < pt.ns || j >= i - pt.nl + 1;
@@ -128,7 +128,7 @@ __device__ void select_row(const uint32_t* keys, int i, const Pattern& pt, int k
 
 constexpr int kWaves = 4;
 
-// scores come from memory: [rows_total, NB, NB]
+// scores come from memory: [rows_total = heads * NB, NBk]
 // budget of query block i: the uniform k, or the schedule's entry clamped to [0, k]
 __device__ __forceinline__ int row_budget(const int32_t* __restrict__ k_rows, int i, int k) {
     if (k_rows == nullptr) return k;
@@ -149,18 +149,19 @@ __device__ __forceinline__ void head_config(const int32_t* __restrict__ head_pat
 
 template <bool EXT>
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
-    const float* __restrict__ scores, int64_t n_rows, int NB, Pattern pt, int k,
+    const float* __restrict__ scores, int64_t n_rows, int NB /* query blocks */, int NBk, int off, Pattern pt, int k,
     const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern, int Hq, int T,
     int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
     extern __shared__ uint32_t lds_keys[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
     if (row >= n_rows) return;                               // whole wave leaves together
-    const int i = (int)(row % NB);
+    const int iq = (int)(row % NB);
+    const int i = iq + off;                                  // block position in the sequence
     head_config(head_pattern, (int)((row / NB) % Hq), pt, k);
-    const int padded = ((NB + 63) >> 6) << 6;
+    const int padded = ((NBk + 63) >> 6) << 6;
     uint32_t* keys = lds_keys + wave * padded;
-    const float* srow = scores + row * NB;
+    const float* srow = scores + row * NBk;
     const int chunks = (i + 64) >> 6;
     for (int m = 0; m < chunks; ++m) {
         int j = (m << 6) + lane;
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
         keys[j] = key;
     }
     // each wave reads back only its own slice; LDS ops of one wave are ordered
-    select_row<EXT>(keys, i, pt, row_budget(k_rows, i, k), T, idx + row * T, cnt + row);
+    select_row<EXT>(keys, i, pt, row_budget(k_rows, iq, k), T, idx + row * T, cnt + row);
 }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -235,7 +236,8 @@ constexpr int kMfmaWaves = 8;
 
 template <int D, int R, int MAXC, bool EXT>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
-    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB, int n_tiles, Pattern pt,
+    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB /* query blocks */, int NBk,
+    int off /* block position of query block 0 */, int n_tiles, Pattern pt,
     int k, const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern,
     const float* __restrict__ lvn, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
     float* __restrict__ scores_out) {
@@ -254,12 +256,12 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const int b = bh / Hq, h = bh % Hq;
     const int Hkv = Hq / G;
     const float* qbase = qp + (int64_t)bh * NB * D;
-    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * NB * D;
-    const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NB : nullptr;
+    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * NBk * D;
+    const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NBk : nullptr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
-    const int n_jt = (i_last >> 5) + 1;                   // 32-wide key-block tiles with some j <= i_last
+    const int n_jt = ((i_last + off) >> 5) + 1;           // 32-wide key-block tiles with some causal j
 
     // ---- phase 1 ---------------------------------------------------------------------
     bf16x8 q_hi[DS], q_lo[DS];
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     float4 kraw[2 * DS];
     auto fetch_tile = [&](int jt, float4 (&dst)[2 * DS]) {
         const int j = 32 * jt + l32;
-        const float* src = kbase + (int64_t)(j < NB ? j : NB - 1) * D + 8 * half;
+        const float* src = kbase + (int64_t)(j < NBk ? j : NBk - 1) * D + 8 * half;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             dst[2 * s] = *reinterpret_cast<const float4*>(src + 16 * s);
@@ -289,7 +291,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
         const int j = 32 * jt + l32;
         // output-aware ranking: the key block's ln(value magnitude) joins its score
-        const float lv = lvbase != nullptr ? lvbase[j < NB ? j : NB - 1] : 0.f;
+        const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
         float4 knext[2 * DS];
         const bool more = jt + kMfmaWaves < n_jt;             // wave-uniform
         if (more) fetch_tile(jt + kMfmaWaves, knext);
@@ -311,8 +313,8 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
                 const float sc = lvbase != nullptr ? scale * acc[r] + lv : scale * acc[r];
                 S[mrow * LD + j] = sc;
                 const int i = i0 + mrow;
-                if (scores_out != nullptr && i < NB && j < NB)
-                    scores_out[((int64_t)bh * NB + i) * NB + j] = j <= i ? sc : -INFINITY;
+                if (scores_out != nullptr && i < NB && j < NBk)
+                    scores_out[((int64_t)bh * NB + i) * NBk + j] = j <= i + off ? sc : -INFINITY;
             }
         }
         if (more) {
@@ -323,8 +325,8 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     if (scores_out != nullptr) {                          // key blocks past the last computed tile
         const int j_first = 32 * n_jt;
         for (int r = 0; r < R && i0 + r < NB; ++r)
-            for (int j = j_first + (int)threadIdx.x; j < NB; j += kMfmaWaves * 64)
-                scores_out[((int64_t)bh * NB + i0 + r) * NB + j] = -INFINITY;
+            for (int j = j_first + (int)threadIdx.x; j < NBk; j += kMfmaWaves * 64)
+                scores_out[((int64_t)bh * NB + i0 + r) * NBk + j] = -INFINITY;
     }
     __syncthreads();
 
@@ -332,8 +334,9 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     head_config(head_pattern, h, pt, k);
 #pragma nounroll
     for (int r = wave; r < R; r += kMfmaWaves) {
-        const int i = i0 + r;
-        if (i >= NB) break;                               // wave-uniform
+        const int iq = i0 + r;                            // query block of the call
+        if (iq >= NB) break;                              // wave-uniform
+        const int i = iq + off;                           // its block position in the sequence
         const int n = i + 1;
         const float* srow = S + r * LD;
         uint32_t key[MAXC];
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
             int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
             n_cand = n - (n_sink + n_local - overlap);
         }
-        const int k_i = row_budget(k_rows, i, k);
+        const int k_i = row_budget(k_rows, iq, k);
         const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
         int need_eq;
@@ -369,7 +372,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         else find_threshold_regs<MAXC, MAXC>(key, kk, n_cand, thr, need_eq);
 
         // emit static U top-k in ascending block order (keys recomputed from LDS: a rolled loop)
-        const int64_t row = (int64_t)bh * NB + i;
+        const int64_t row = (int64_t)bh * NB + iq;
         int32_t* idx_row = idx + row * T;
         const int chunks = (n + 63) >> 6;
         int eq_seen = 0, out_pos = 0;
@@ -407,14 +410,14 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
     unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
     const void* fn = extended(d) ? (const void*)topk_from_scores_kernel<true> : (const void*)topk_from_scores_kernel<false>;
-    hipError_t e = allow_lds(fn, keys_lds_bytes(d.NB));
+    hipError_t e = allow_lds(fn, keys_lds_bytes(d.NBk));
     if (e != hipSuccess) return e;
     if (extended(d))
-        hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
+        hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NBk), st,
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
     else
-        hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NB), st,
-                           scores, n_rows, d.NB, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
+        hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NBk), st,
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
     return hipGetLastError();
 }
 
@@ -427,7 +430,7 @@ hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const 
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, n_tiles, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale, idx, cnt, scores_or_null);
+                       d.G, d.NB, d.NBk, d.off, n_tiles, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale, idx, cnt, scores_or_null);
     return hipGetLastError();
 }
 
@@ -442,10 +445,10 @@ template <int D>
 hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                          int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
-    if (d.NB <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NB <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
     return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 

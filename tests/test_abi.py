@@ -53,6 +53,7 @@ def test_row_capacity_and_workspace(lib):
     assert m.row_capacity(_params(n_dense_q_blocks=2)) == 8        # a dense strip needs full rows
     assert m.row_capacity(_params(seq_len=1000, top_k_blocks=100)) == 8   # 7 whole blocks + a partial one
     assert m.row_capacity(_params(seq_len=1025, top_k_blocks=100)) == 9
+    assert m.row_capacity(_params(kv_prefix_len=512, top_k_blocks=100)) == 12     # 4 prefix + 8 query blocks
     assert m.row_capacity(_params(top_k_blocks=0, stride_blocks=2, stride_reach_blocks=5)) == 5   # 3 + (5 - 1) // 2
     ws = m.workspace_bytes(_params())
     # pooled Q (4*8*128 fp32) + pooled K (2*8*128 fp32) + lists + transposed V (2*1024*128 bf16),
@@ -65,6 +66,7 @@ def test_row_capacity_and_workspace(lib):
     (dict(n_q_heads=5), -2), (dict(batch=0), -2), (dict(seq_len=128 * 4097), -2),
     (dict(n_local_blocks=0), -3), (dict(n_sink_blocks=-1), -3), (dict(top_k_blocks=-2), -3),
     (dict(stride_blocks=-1), -3), (dict(n_dense_q_blocks=-4), -3), (dict(stride_reach_blocks=-1), -3), (dict(lists_per_kv_head=2), -3),
+    (dict(kv_prefix_len=-128), -2), (dict(kv_prefix_len=100), -2), (dict(kv_prefix_len=128 * 4090), -2),
     (dict(softmax_scale=-1.0), -2),
 ])
 def test_bad_params_rejected_on_host(lib, kw, code):

@@ -604,6 +604,43 @@ def test_ragged_all_blocks_is_dense_causal_attention(spa, oracle):
     _assert_attn_close(out, ref)
 
 
+# ------------------------------------- KV prefix (chunked prefill)
+@pytest.mark.parametrize("Sq,P,D,Bs", [(5 * 64, 3 * 64, 64, 64), (4 * 128 + 50, 6 * 128, 128, 128), (9 * 64 + 1, 64 * 30, 128, 64),
+                                       (128, 128 * 20, 128, 128), (3 * 128, 128, 64, 128)])
+def test_kv_prefix_equals_the_rows_of_the_full_run(spa, oracle, Sq, P, D, Bs):
+    B, Hq, Hkv, ns, nl, k = 1, 4, 2, 1, 2, 3
+    S = P + Sq
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 67 + Sq)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    off = P // Bs
+    NBq, NBk = -(-Sq // Bs), -(-S // Bs)
+    dqc = dq[:, :, P:]                                   # a strided view: the last Sq tokens
+    kr = _schedules(NBk, k)["decay"]
+    for kw_full, kw_chunk in (({}, {}), (dict(top_k_per_block=kr.cuda(), v=dv, stride_blocks=3),
+                                         dict(top_k_per_block=kr[off:].contiguous().cuda(), v=dv, stride_blocks=3))):
+        idx_f, cnt_f, sp_f = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, **kw_full)
+        idx_c, cnt_c, sp_c = spa.select(dqc, dk, Bs, ns, nl, k, return_scores=True, **kw_chunk)
+        assert sp_c.shape == (B, Hq, NBq, NBk) and idx_c.shape[:3] == (B, Hq, NBq)
+        assert torch.equal(sp_c, sp_f[:, :, off:]) and torch.equal(idx_c, idx_f[:, :, off:]) and torch.equal(cnt_c, cnt_f[:, :, off:])
+    qp_c, kp_c = spa.pool(dqc, dk, Bs)
+    qp_f, kp_f = spa.pool(dq, dk, Bs)
+    assert torch.equal(qp_c, qp_f[:, :, off:]) and torch.equal(kp_c, kp_f)
+    # the rule on the GPU's own scores, with the offset, is what the oracle gives
+    g_idx, g_cnt = oracle.topk(sp_c.cpu(), ns, nl, k, kr[off:].contiguous(), stride=3)
+    assert torch.equal(idx_c.cpu(), g_idx) and torch.equal(cnt_c.cpu(), g_cnt)
+    idx_t, cnt_t = spa.topk_from_scores(sp_c, ns, nl, k, top_k_per_block=kr[off:].contiguous().cuda(), stride_blocks=3)
+    assert torch.equal(idx_t, idx_c) and torch.equal(cnt_t, cnt_c)
+    out_f, lse_f = spa.attn(dq, dk, dv, idx_f, cnt_f, Bs, return_lse=True)
+    out_c, lse_c = spa.attn(dqc, dk, dv, idx_c, cnt_c, Bs, return_lse=True)
+    assert torch.equal(out_c, out_f[:, :, P:]) and torch.equal(lse_c, lse_f[:, :, P:])
+    want, want_lse = oracle.attn(q[:, :, P:].contiguous(), kk, v, idx_c.cpu(), cnt_c.cpu(), Bs)
+    _assert_attn_close(out_c, want)
+    assert (lse_c.cpu() - want_lse).abs().max().item() <= 2e-2
+    fused = spa.fused(dqc, dk, dv, Bs, ns, nl, k, top_k_per_block=kr[off:].contiguous().cuda(), output_aware=True,
+                      stride_blocks=3)
+    assert torch.equal(fused, out_c)
+
+
 # ------------------------------------------------------------- HIP graph replay
 def test_fused_call_replays_from_a_hip_graph(spa, oracle):
     """The calls only enqueue kernels on the caller's stream (no allocation, no synchronisation,
