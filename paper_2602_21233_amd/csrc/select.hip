@@ -1,7 +1,9 @@
-// Pooled scores, per-row top-k and merge with the static A-shape pattern
+// Pooled scores, per-row top-k and merge with the static pattern
 // (pattern computation, steps 2-4; Sec. 4.1.1 dynamic sparsity, uniform top-k
 // budget of Sec. 4.1.2 Fig. "Stem" (a) or the per-query-block budget schedule of
-// Token Position-Decay, Fig. "Stem" (b); static A-shape of Sec. 4.1.1).
+// Token Position-Decay, Fig. "Stem" (b); optional value-magnitude term of the
+// Output-Aware Metric, Fig. "Stem" (c); static patterns of Sec. 4.1.1: A-shape,
+// Strided, Dilated, Tri-shape; optional per-head settings and a KV prefix).
 //
 // score_topk_mfma_kernel: one 512-thread workgroup owns R consecutive query
 // blocks of one query head.
@@ -15,8 +17,9 @@
 //   the caller asks for it.
 //   Phase 2 - exact selection.  A wavefront owns a row: lane l holds the keys of
 //   blocks l, l+64, ... in registers as order-preserving uint32, finds the k-th
-//   largest by a bitwise descent (ballot + popcount per step, early exit when a
-//   prefix isolates exactly k), resolves ties at the threshold by block index
+//   largest by a bitwise descent (per-lane counts on the vector ALU and one
+//   cross-lane sum per step, only over the chunks a causal row can fill, early
+//   exit when a prefix isolates exactly k), resolves ties at the threshold by block index
 //   with a running prefix count, and, because the last pass walks the blocks in
 //   ascending order, emits static U top-k already sorted.
 // topk_from_scores_kernel applies the same rule to caller-supplied scores (one
@@ -185,12 +188,6 @@ __device__ __forceinline__ void split_bf16(const float4 a, const float4 b, bf16x
     lo = __builtin_convertvector(x - back, bf16x8);
 }
 
-// Same selection as select_row, with the row's keys in registers: key[m] belongs to
-// block 64*m + lane (0 for static blocks, blocks beyond i, and unused chunks).
-// Threshold search of select_row with the row's keys in registers: key[m] belongs to block
-// 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks (0 never counts,
-// every trial value is >= 1).  Returns thr / need_eq: take key > thr, plus the first need_eq
-// keys equal to thr in block order.
 // sum of v over the 64 lanes (DPP row reductions + row broadcasts), returned wave-uniform
 __device__ __forceinline__ int wave_sum(int v) {
     v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
@@ -202,6 +199,10 @@ __device__ __forceinline__ int wave_sum(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
+// Threshold search of select_row with the row's keys in registers: key[m] belongs to block
+// 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks (0 never counts,
+// every trial value is >= 1).  Returns thr / need_eq: take key > thr, plus the first need_eq
+// keys equal to thr in block order.
 // NC <= MAXC: only key[0 .. NC) can be nonzero for this row (blocks beyond the row hold 0).
 template <int MAXC, int NC>
 __device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC], int kk, int n_cand,
