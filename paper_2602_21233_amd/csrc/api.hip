@@ -50,7 +50,7 @@ Workspace carve(const Dims& d) {
     Workspace w;
     size_t off = 0;
     w.qp_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.D * sizeof(float));
-    w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * d.D * sizeof(float));
+    w.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * ((d.NBk + 31) / 32 * 32) * d.D * sizeof(float));   // whole tiles of 32 blocks
     w.qg_off = off; if (d.shared) off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
     w.idx_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.T * sizeof(int32_t));
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
@@ -83,7 +83,7 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
     float* qp = (float*)((char*)ws + w.qp_off);
     float* kp = (float*)((char*)ws + w.kp_off);
     hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, st);
+    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, true, st);
     if (e != hipSuccess) return SPA_ERR_LAUNCH;
     float* lvn = nullptr;
     if (v_or_null) {
@@ -177,7 +177,7 @@ int sparse_prefill_pool(const spa_params* p, const void* q, const void* k, float
     if (k && (rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
     Dims d = resolved(p);
     return launch_code(launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), q_pooled,
-                                   k_pooled, (hipStream_t)hip_stream));
+                                   k_pooled, false, (hipStream_t)hip_stream));
 }
 
 

@@ -39,14 +39,17 @@ struct Strides { int64_t b, h, t; };
 inline Strides strides_of(const int64_t s[3]) { return Strides{s[0], s[1], s[2]}; }
 
 // Launchers (one per kernel file).  Each returns a hipError_t from the launch.
+// k_tiled: write the pooled K in the score kernel's operand layout (tiles of 32 key blocks,
+// heads ceil(NBk / 32) tiles apart) instead of row major [.., NBk, D].
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                       float* qp, float* kp, hipStream_t st);
+                       float* qp, float* kp, bool k_tiled, hipStream_t st);
 // qg[b, kv head, :] = mean over the G query heads of the group of qp[b, head, :]  (n = NB * D values per head)
 hipError_t launch_group_mean(const Dims& d, const float* qp, float* qg, hipStream_t st);
 // lvn [B*Hkv, NB] fp32: ln of the mean value-vector norm of every key block.
 hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st);
 // k_rows: optional device array of NB per-query-block budgets (clamped to [0, d.k] in the kernel).
 // lvn: optional; added to the score of key block j (output-aware ranking).
+// kp is in the tiled layout launch_pool writes with k_tiled.
 // head_pattern: optional device array [Hq][3] = (n_sink, n_local, top_k) per query head.
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
                              const int32_t* head_pattern, const float* lvn, int32_t* idx, int32_t* cnt,

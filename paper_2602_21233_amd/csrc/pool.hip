@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
                                                    int n_q_rows /* B*Hq or 0 */, int Hq,
                                                    const uint16_t* __restrict__ k, Strides ks, int Hkv,
                                                    float* __restrict__ qp, float* __restrict__ kp, int NBq, int Sq,
-                                                   int NBk, int Skv) {
+                                                   int NBk, int Skv, int k_tiled) {
     constexpr int TPR = D / 8;          // lanes per token row
     constexpr int RPP = 256 / TPR;      // token rows per pass
     constexpr int PASSES = BS / RPP;
@@ -45,6 +45,11 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
         dst = kp + ((int64_t)hy * NBk + blk) * D;
         S = Skv;
         qs = ks;
+        // k_tiled: pooled K goes out in the operand layout of the score kernel instead of row
+        // major: per KV head, tiles of 32 key blocks; inside a tile the 8 dims
+        // 16s + 8h .. +7 of block r sit at float offset ((2s + h) * 32 + r) * 8, so a wavefront
+        // of that kernel reads 2 KB in one piece.  Heads are ceil(NBk / 32) tiles apart.
+        if (k_tiled) dst = kp + ((int64_t)hy * ((NBk + 31) >> 5) + (blk >> 5)) * (32 * D);
     }
     const int tid = threadIdx.x;
     const int row0 = tid / TPR, chunk = tid % TPR;
@@ -73,18 +78,20 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
         float s = 0.f;
 #pragma unroll
         for (int r = 0; r < RPP; ++r) s += part[r][tid];
-        dst[tid] = n_valid == BS ? s * (1.0f / (float)BS) : s / (float)n_valid;
+        const float mean = n_valid == BS ? s * (1.0f / (float)BS) : s / (float)n_valid;
+        if (k != nullptr && k_tiled) dst[(((tid >> 3) * 32) + (blk & 31)) * 8 + (tid & 7)] = mean;
+        else dst[tid] = mean;
     }
 }
 
 template <int D, int BS>
 hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, float* qp,
-                  float* kp, hipStream_t st) {
+                  float* kp, bool k_tiled, hipStream_t st) {
     int nq = q ? d.B * d.Hq : 0, nk = k ? d.B * d.Hkv : 0;
     if (nq + nk == 0) return hipSuccess;
     dim3 grid(nk ? d.NBk : d.NB, nq + nk);
     hipLaunchKernelGGL((pool_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)q, qs, nq, d.Hq,
-                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S, d.NBk, d.Skv);
+                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S, d.NBk, d.Skv, k_tiled ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -179,11 +186,11 @@ hipError_t launch_vnorm(const Dims& d, const void* v, Strides vs, float* lvn, hi
 }
 
 hipError_t launch_pool(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                       float* qp, float* kp, hipStream_t st) {
-    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, qp, kp, st);
-    if (d.D == 128 && d.Bs == 64) return launch<128, 64>(d, q, qs, k, ks, qp, kp, st);
-    if (d.D == 64 && d.Bs == 128) return launch<64, 128>(d, q, qs, k, ks, qp, kp, st);
-    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, qp, kp, st);
+                       float* qp, float* kp, bool k_tiled, hipStream_t st) {
+    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, qp, kp, k_tiled, st);
+    if (d.D == 128 && d.Bs == 64) return launch<128, 64>(d, q, qs, k, ks, qp, kp, k_tiled, st);
+    if (d.D == 64 && d.Bs == 128) return launch<64, 128>(d, q, qs, k, ks, qp, kp, k_tiled, st);
+    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, qp, kp, k_tiled, st);
     return hipErrorInvalidValue;
 }
 

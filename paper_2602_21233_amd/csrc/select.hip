@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const int b = bh / Hq, h = bh % Hq;
     const int Hkv = Hq / G;
     const float* qbase = qp + (int64_t)bh * NB * D;
-    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * NBk * D;
+    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * ((NBk + 31) >> 5) * (32 * D);   // tiled, see fetch_tile
     const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NBk : nullptr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -275,17 +275,20 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
             split_bf16(*reinterpret_cast<const float4*>(src + 16 * s), *reinterpret_cast<const float4*>(src + 16 * s + 4),
                        q_hi[s], q_lo[s]);
     }
-    // The Kp rows of a tile are fetched as one batch of 16-byte loads, and the next tile's batch
-    // is requested before the current one is consumed, so L2 latency is paid once per tile pair
-    // instead of once per 16-dim slice.
+    // The pooled K arrives tiled in operand layout: tile jt of 32 key blocks is 32 * D floats, and
+    // the 8 dims 16s + 8 * half .. +7 of block l32 sit at float ((2s + half) * 32 + l32) * 8, so each
+    // load instruction of a wavefront covers 2 KB in one piece (row-major rows would cost 32 cache
+    // lines per instruction).  A tile is fetched as one batch and the next tile's batch is
+    // requested before the current one is consumed, so L2 latency is paid once per tile pair.
+    // Blocks past NBk in the last tile hold whatever the workspace held: their columns are never
+    // ranked or written out.
     float4 kraw[2 * DS];
     auto fetch_tile = [&](int jt, float4 (&dst)[2 * DS]) {
-        const int j = 32 * jt + l32;
-        const float* src = kbase + (int64_t)(j < NBk ? j : NBk - 1) * D + 8 * half;
+        const float* src = kbase + (int64_t)jt * (32 * D) + (half * 32 + l32) * 8;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
-            dst[2 * s] = *reinterpret_cast<const float4*>(src + 16 * s);
-            dst[2 * s + 1] = *reinterpret_cast<const float4*>(src + 16 * s + 4);
+            dst[2 * s] = *reinterpret_cast<const float4*>(src + s * 512);
+            dst[2 * s + 1] = *reinterpret_cast<const float4*>(src + s * 512 + 4);
         }
     };
     if (wave < n_jt) fetch_tile(wave, kraw);
