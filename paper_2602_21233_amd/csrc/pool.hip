@@ -46,9 +46,11 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
         S = Skv;
         qs = ks;
         // k_tiled: pooled K goes out in the operand layout of the score kernel instead of row
-        // major: per KV head, tiles of 32 key blocks; inside a tile the 8 dims
-        // 16s + 8h .. +7 of block r sit at float offset ((2s + h) * 32 + r) * 8, so a wavefront
-        // of that kernel reads 2 KB in one piece.  Heads are ceil(NBk / 32) tiles apart.
+        // major fp32: per KV head, tiles of 32 key blocks (32 * D * 4 bytes); every value is
+        // already split into its bf16 head and bf16 tail (x = hi + lo), and inside a tile the 8
+        // dims 16s + 8h .. +7 of block r sit at bf16 offset (((2s + h) * 2 + part) * 32 + r) * 8,
+        // part 0 = hi, 1 = lo, so a wavefront of that kernel reads whole 1-KB pieces that are its
+        // MFMA operands as they are.  Heads are ceil(NBk / 32) tiles apart.
         if (k_tiled) dst = kp + ((int64_t)hy * ((NBk + 31) >> 5) + (blk >> 5)) * (32 * D);
     }
     const int tid = threadIdx.x;
@@ -79,8 +81,16 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
 #pragma unroll
         for (int r = 0; r < RPP; ++r) s += part[r][tid];
         const float mean = n_valid == BS ? s * (1.0f / (float)BS) : s / (float)n_valid;
-        if (k != nullptr && k_tiled) dst[(((tid >> 3) * 32) + (blk & 31)) * 8 + (tid & 7)] = mean;
-        else dst[tid] = mean;
+        if (k != nullptr && k_tiled) {
+            const __bf16 hi = (__bf16)mean;                       // round to nearest even, twice
+            const __bf16 lo = (__bf16)(mean - (float)hi);
+            __bf16* t = reinterpret_cast<__bf16*>(dst);
+            const int at = (((tid >> 3) * 2) * 32 + (blk & 31)) * 8 + (tid & 7);
+            t[at] = hi;
+            t[at + 32 * 8] = lo;
+        } else {
+            dst[tid] = mean;
+        }
     }
 }
 

@@ -275,20 +275,21 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
             split_bf16(*reinterpret_cast<const float4*>(src + 16 * s), *reinterpret_cast<const float4*>(src + 16 * s + 4),
                        q_hi[s], q_lo[s]);
     }
-    // The pooled K arrives tiled in operand layout: tile jt of 32 key blocks is 32 * D floats, and
-    // the 8 dims 16s + 8 * half .. +7 of block l32 sit at float ((2s + half) * 32 + l32) * 8, so each
-    // load instruction of a wavefront covers 2 KB in one piece (row-major rows would cost 32 cache
-    // lines per instruction).  A tile is fetched as one batch and the next tile's batch is
-    // requested before the current one is consumed, so L2 latency is paid once per tile pair.
-    // Blocks past NBk in the last tile hold whatever the workspace held: their columns are never
-    // ranked or written out.
-    float4 kraw[2 * DS];
-    auto fetch_tile = [&](int jt, float4 (&dst)[2 * DS]) {
-        const float* src = kbase + (int64_t)jt * (32 * D) + (half * 32 + l32) * 8;
+    // The pooled K arrives tiled in operand layout and already split into bf16 head and tail:
+    // tile jt of 32 key blocks is 32 * D * 4 bytes, and the 8 dims 16s + 8 * half .. +7 of block
+    // l32 sit at bf16 offset (((2s + half) * 2 + part) * 32 + l32) * 8 (part 0 = hi, 1 = lo), so
+    // every load instruction of a wavefront covers 1-KB pieces (row-major rows would cost 32 cache
+    // lines per instruction) and what it loads is the MFMA operand.  A tile is fetched as one
+    // batch and the next tile's batch is requested before the current one is consumed, so L2
+    // latency is paid once per tile pair.  Blocks past NBk in the last tile hold whatever the
+    // workspace held: their columns are never ranked or written out.
+    bf16x8 kraw[2 * DS];                                  // [2s] = hi, [2s + 1] = lo of slice s
+    auto fetch_tile = [&](int jt, bf16x8 (&dst)[2 * DS]) {
+        const __bf16* src = reinterpret_cast<const __bf16*>(kbase + (int64_t)jt * (32 * D)) + (half * 64 + l32) * 8;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
-            dst[2 * s] = *reinterpret_cast<const float4*>(src + s * 512);
-            dst[2 * s + 1] = *reinterpret_cast<const float4*>(src + s * 512 + 4);
+            dst[2 * s] = *reinterpret_cast<const bf16x8*>(src + s * 1024);
+            dst[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
         }
     };
     if (wave < n_jt) fetch_tile(wave, kraw);
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         const int j = 32 * jt + l32;
         // output-aware ranking: the key block's ln(value magnitude) joins its score
         const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
-        float4 knext[2 * DS];
+        bf16x8 knext[2 * DS];
         const bool more = jt + kMfmaWaves < n_jt;             // wave-uniform
         if (more) fetch_tile(jt + kMfmaWaves, knext);
         f32x16 acc;
@@ -304,8 +305,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
-            bf16x8 k_hi, k_lo;
-            split_bf16(kraw[2 * s], kraw[2 * s + 1], k_hi, k_lo);
+            const bf16x8 k_hi = kraw[2 * s], k_lo = kraw[2 * s + 1];
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_lo[s], k_hi, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_lo, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_hi, acc, 0, 0, 0);
