@@ -82,12 +82,17 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
     const int b = bh / Hkv, h = bh % Hkv;
     const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
     const int tid = threadIdx.x;
+    const int n_valid = S - blk * BS < BS ? S - blk * BS : BS;
 #pragma unroll
     for (int p = 0; p < BS * D / 8 / 256; ++p) {
         int c = p * 256 + tid;
         int row = c / (D / 8), col = (c % (D / 8)) * 8;
         uint4 x = make_uint4(0u, 0u, 0u, 0u);           // tokens past the end of a partial last block: zeros
-        if (blk * BS + row < S) x = *reinterpret_cast<const uint4*>(src + (int64_t)row * vs.t + col);
+        if (row < n_valid) {                            // V itself is not read again: non-temporal load
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)row * vs.t + col));
+            x = make_uint4(t[0], t[1], t[2], t[3]);
+        }
         uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row * PITCH + col]);   // PITCH even: 4-byte aligned
         dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
     }
