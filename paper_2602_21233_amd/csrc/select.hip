@@ -17,9 +17,10 @@
 //   the caller asks for it.
 //   Phase 2 - exact selection.  A wavefront owns a row: lane l holds the keys of
 //   blocks l, l+64, ... in registers as order-preserving uint32, finds the k-th
-//   largest by a bitwise descent (per-lane counts on the vector ALU and one
-//   cross-lane sum per step, only over the chunks a causal row can fill, early
-//   exit when a prefix isolates exactly k), resolves ties at the threshold by block index
+//   largest by radix selection, 8 bits per pass (the wavefront histograms the
+//   current digit into 256 LDS counters, a prefix sum over the lanes finds the
+//   bin of the wanted rank; only the chunks a causal row can fill are visited,
+//   a pass that takes its whole bin ends early), resolves ties at the threshold by block index
 //   with a running prefix count, and, because the last pass walks the blocks in
 //   ascending order, emits static U top-k already sorted.
 // topk_from_scores_kernel applies the same rule to caller-supplied scores (one
@@ -199,41 +200,72 @@ __device__ __forceinline__ int wave_sum(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-// Threshold search of select_row with the row's keys in registers: key[m] belongs to block
-// 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks (0 never counts,
-// every trial value is >= 1).  Returns thr / need_eq: take key > thr, plus the first need_eq
-// keys equal to thr in block order.
-// NC <= MAXC: only key[0 .. NC) can be nonzero for this row (blocks beyond the row hold 0).
+constexpr int kMfmaWaves = 8;
+
+// inclusive prefix sum of v over the 64 lanes (Hillis-Steele inside the rows of 16 with DPP row
+// shifts, then the row totals are carried over with the row broadcasts)
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1, lanes shifted out read 0
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, true);   // row_bcast31 into rows 2 and 3
+    return v;
+}
+
+// Exact k-th largest by most-significant-digit radix selection, 8 bits per pass: the wavefront
+// histograms the current digit of the keys that still match the decided prefix into its own 256 LDS
+// counters (LDS atomics), lane l then owns the four bins 255-4l .. 252-4l, a prefix sum over the
+// lanes finds the bin that holds the wanted rank, and that bin's digit extends the prefix.  Four
+// passes replace up to 32 counting steps over all keys; a pass that takes its whole bin ends early.
+// key[m] belongs to block 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks
+// (0 is never counted); NC <= MAXC: only key[0 .. NC) can be nonzero for this row.  Returns
+// thr / need_eq: take key > thr, plus the first need_eq keys equal to thr in block order.
+// hist: this wavefront's 256 counters.
 template <int MAXC, int NC>
-__device__ __forceinline__ void find_threshold_regs(const uint32_t (&key)[MAXC], int kk, int n_cand,
-                                                    uint32_t& thr, int& need_eq) {
+__device__ __forceinline__ void find_threshold_hist(const uint32_t (&key)[MAXC], int kk, int n_cand, uint32_t* hist,
+                                                    int lane, uint32_t& thr, int& need_eq) {
     thr = 0xffffffffu;
     need_eq = 0;
     if (kk <= 0) return;
     if (kk == n_cand) { thr = 0u; return; }
-    uint32_t p = 0u;
-    int c_at_p = n_cand;
+    uint32_t prefix = 0u;     // decided digits, low bits zero
+    int want = kk;            // rank wanted among the keys that match the prefix (1 = largest)
 #pragma nounroll
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t trial = p | (1u << bit);
-        // per-lane counts on the vector ALU, one cross-lane sum per step: the scalar unit is
-        // shared by the whole CU and a ballot + popcount per chunk saturates it
-        int cl = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
-        for (int m = 0; m < NC; ++m) cl += (key[m] >= trial) ? 1 : 0;
-        const int c = wave_sum(cl);
-        if (c >= kk) { p = trial; c_at_p = c; if (c == kk) break; }
+        for (int m = 0; m < NC; ++m) {
+            const uint32_t kv = key[m];
+            // ((kv ^ prefix) >> shift) >> 8 == 0: the digits above this one match (two shifts: shift + 8 may be 32)
+            if (kv != 0u && (((kv ^ prefix) >> shift) >> 8) == 0u) atomicAdd(&hist[(kv >> shift) & 255u], 1u);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint4 h = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // .w = bin 255-4l ... .x = bin 252-4l
+        const int own = (int)(h.x + h.y + h.z + h.w);
+        const int incl = wave_inclusive_scan(own);
+        const int L = __ffsll((unsigned long long)__ballot(incl >= want)) - 1;   // lane whose bins hold the wanted rank
+        const int before = __builtin_amdgcn_readlane(incl - own, L);                 // keys in higher bins
+        const int b3 = __builtin_amdgcn_readlane((int)h.w, L), b2 = __builtin_amdgcn_readlane((int)h.z, L);
+        const int b1 = __builtin_amdgcn_readlane((int)h.y, L), b0 = __builtin_amdgcn_readlane((int)h.x, L);
+        const int rem = want - before;                                               // 1 .. own(L)
+        int digit, above, in_bin;
+        if (rem <= b3) { digit = 255 - 4 * L; above = 0; in_bin = b3; }
+        else if (rem <= b3 + b2) { digit = 254 - 4 * L; above = b3; in_bin = b2; }
+        else if (rem <= b3 + b2 + b1) { digit = 253 - 4 * L; above = b3 + b2; in_bin = b1; }
+        else { digit = 252 - 4 * L; above = b3 + b2 + b1; in_bin = b0; }
+        want = rem - above;                                                          // rank inside the chosen bin
+        prefix |= (uint32_t)digit << shift;
+        if (want == in_bin) {          // the whole bin is taken: every key >= prefix, none below
+            thr = prefix != 0u ? prefix - 1u : 0u;   // (prefix 0 would mean every candidate is taken)
+            return;
+        }
     }
-    if (c_at_p == kk) { thr = p - 1u; return; }
-    int gl = 0;
-#pragma unroll
-    for (int m = 0; m < NC; ++m) gl += (key[m] > p) ? 1 : 0;
-    const int gt = wave_sum(gl);
-    thr = p;
-    need_eq = kk - gt;
+    thr = prefix;                      // the k-th largest key itself; `want` of its copies are taken
+    need_eq = want;
 }
-
-constexpr int kMfmaWaves = 8;
 
 template <int D, int R, int MAXC, bool EXT>
 __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
@@ -244,7 +276,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     float* __restrict__ scores_out) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
-    extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows
+    extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows, then 256 counters per wave
 
     // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
     // (b, head, row tile) order so that one L2 serves few KV heads and their Kp stays resident.
@@ -370,10 +402,11 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
         int need_eq;
         // rows are causal: a row early in the sequence fills only its first chunks of 64 blocks
         const int nc4 = 4 * ((i >> 6) + 1);               // wave-uniform
-        if (nc4 <= MAXC) find_threshold_regs<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, thr, need_eq);
-        else if (nc4 <= 2 * MAXC) find_threshold_regs<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, thr, need_eq);
-        else if (nc4 <= 3 * MAXC) find_threshold_regs<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, thr, need_eq);
-        else find_threshold_regs<MAXC, MAXC>(key, kk, n_cand, thr, need_eq);
+        uint32_t* hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
+        if (nc4 <= MAXC) find_threshold_hist<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
+        else if (nc4 <= 2 * MAXC) find_threshold_hist<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, hist, lane, thr, need_eq);
+        else if (nc4 <= 3 * MAXC) find_threshold_hist<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
+        else find_threshold_hist<MAXC, MAXC>(key, kk, n_cand, hist, lane, thr, need_eq);
 
         // emit static U top-k in ascending block order (keys recomputed from LDS: a rolled loop)
         const int64_t row = (int64_t)bh * NB + iq;
@@ -428,7 +461,7 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
 template <int D, int R, int MAXC, bool EXT>
 hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float);
+    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float) + kMfmaWaves * 256 * sizeof(uint32_t);
     hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT>, lds);
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
