@@ -311,27 +311,29 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     // tile jt of 32 key blocks is 32 * D * 4 bytes, and the 8 dims 16s + 8 * half .. +7 of block
     // l32 sit at bf16 offset (((2s + half) * 2 + part) * 32 + l32) * 8 (part 0 = hi, 1 = lo), so
     // every load instruction of a wavefront covers 1-KB pieces (row-major rows would cost 32 cache
-    // lines per instruction) and what it loads is the MFMA operand.  A tile is fetched as one
-    // batch and the next tile's batch is requested before the current one is consumed, so L2
-    // latency is paid once per tile pair.  Blocks past NBk in the last tile hold whatever the
+    // lines per instruction) and what it loads is the MFMA operand.  One register buffer serves
+    // as a whole-tile pipeline: as soon as the three products of a 16-dim slice have been issued,
+    // the same registers are refilled with that slice of the wave's next tile, so every load has a
+    // full tile of MFMA work to arrive.  Blocks past NBk in the last tile hold whatever the
     // workspace held: their columns are never ranked or written out.
     bf16x8 kraw[2 * DS];                                  // [2s] = hi, [2s + 1] = lo of slice s
-    auto fetch_tile = [&](int jt, bf16x8 (&dst)[2 * DS]) {
-        const __bf16* src = reinterpret_cast<const __bf16*>(kbase + (int64_t)jt * (32 * D)) + (half * 64 + l32) * 8;
+    auto tile_ptr = [&](int jt) {
+        return reinterpret_cast<const __bf16*>(kbase + (int64_t)jt * (32 * D)) + (half * 64 + l32) * 8;
+    };
+    if (wave < n_jt) {
+        const __bf16* src = tile_ptr(wave);
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
-            dst[2 * s] = *reinterpret_cast<const bf16x8*>(src + s * 1024);
-            dst[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
+            kraw[2 * s] = *reinterpret_cast<const bf16x8*>(src + s * 1024);
+            kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
         }
-    };
-    if (wave < n_jt) fetch_tile(wave, kraw);
+    }
     for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
         const int j = 32 * jt + l32;
         // output-aware ranking: the key block's ln(value magnitude) joins its score
         const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
-        bf16x8 knext[2 * DS];
-        const bool more = jt + kMfmaWaves < n_jt;             // wave-uniform
-        if (more) fetch_tile(jt + kMfmaWaves, knext);
+        // the last tile refills from itself: in bounds, never used
+        const __bf16* next = tile_ptr(jt + kMfmaWaves < n_jt ? jt + kMfmaWaves : jt);
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -341,6 +343,8 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_lo[s], k_hi, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_lo, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_hi, acc, 0, 0, 0);
+            kraw[2 * s] = *reinterpret_cast<const bf16x8*>(next + s * 1024);
+            kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(next + s * 1024 + 256);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -352,10 +356,6 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
                 if (scores_out != nullptr && i < NB && j < NBk)
                     scores_out[((int64_t)bh * NB + i) * NBk + j] = j <= i + off ? sc : -INFINITY;
             }
-        }
-        if (more) {
-#pragma unroll
-            for (int x = 0; x < 2 * DS; ++x) kraw[x] = knext[x];
         }
     }
     if (scores_out != nullptr) {                          // key blocks past the last computed tile
