@@ -32,7 +32,9 @@
  *     T = min(NB, n_sink_blocks + n_local_blocks + top_k_blocks
  *                 + (stride_blocks > 0 ? min(NB - 1, reach - 1) / stride_blocks : 0)),
  *     reach = stride_reach_blocks or NB when that is 0,
- *     or NB when n_dense_q_blocks > 0 (spa_row_capacity returns it).
+ *     or NB when n_dense_q_blocks > 0 (spa_row_capacity returns it).  With a KV prefix
+ *     (kv_prefix_len > 0) the key blocks number NBk = kv_prefix_len / block_size + NB and
+ *     NBk takes the place of NB in T; block_idx keeps NB rows.
  *   - block_idx is [batch, n_q_heads, NB, T] int32, contiguous: for query
  *     block i the selected key blocks in ascending order, then -1 padding.
  *     block_cnt is [batch, n_q_heads, NB] int32: the number of valid entries:
@@ -58,7 +60,8 @@ enum {
     SPA_OK = 0,
     SPA_ERR_NULLPTR = -1,             /* a required pointer is NULL                         */
     SPA_ERR_BAD_SHAPE = -2,           /* unsupported sizes, see spa_params                  */
-    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1, or a negative top_k, stride, reach or n_dense */
+    SPA_ERR_BAD_PATTERN = -3,         /* n_sink < 0, n_local < 1, a negative top_k, stride, reach or
+                                         n_dense, lists_per_kv_head not 0 or 1               */
     SPA_ERR_BAD_STRIDE = -4,          /* stride not a multiple of 8 / pointer not 16-B aligned */
     SPA_ERR_WORKSPACE_TOO_SMALL = -5, /* ws_bytes < spa_workspace_bytes()                   */
     SPA_ERR_LAUNCH = -6               /* the HIP runtime rejected a launch                  */
@@ -68,7 +71,7 @@ typedef struct spa_params {
     int32_t batch;          /* >= 1                                                   */
     int32_t n_q_heads;      /* >= 1, multiple of n_kv_heads                           */
     int32_t n_kv_heads;     /* >= 1                                                   */
-    int32_t seq_len;        /* >= 1; ceil(seq_len / block_size) <= 4096               */
+    int32_t seq_len;        /* >= 1 query tokens; at most 4096 key blocks (see kv_prefix_len) */
     int32_t head_dim;       /* 64 or 128                                              */
     int32_t block_size;     /* 64 or 128 tokens                                       */
     int32_t n_sink_blocks;  /* >= 0: key blocks 0 .. n_sink-1 are always selected     */
@@ -81,7 +84,7 @@ typedef struct spa_params {
     int64_t v_stride[3];
     int64_t o_stride[3];
     /* Further static patterns of the library (Sec. 4.1.1 names A-shape, Tri-shape, Dilated and
-     * Strided; readings at block level).  Both 0 for the plain A-shape.                      */
+     * Strided; readings at block level).  All three 0 for the plain A-shape.                 */
     int32_t stride_blocks;    /* >= 0.  s > 0 (Strided): key blocks j with (i - j) % s == 0 are
                                  static too, every s-th block back from the diagonal          */
     int32_t n_dense_q_blocks; /* >= 0.  n > 0 (Tri-shape): the last n query blocks attend to
@@ -122,7 +125,8 @@ int spa_workspace_bytes(const spa_params *p, size_t *bytes);
 /* Pattern computation, step 1 (Sec. 4.1.1): block mean pooling.
  *   q_pooled[b,h,i,:] = mean over the block's tokens of Q[b,h,i*Bs+t,:]   (fp32)
  *   k_pooled likewise.  q_pooled is [batch, n_q_heads, NB, head_dim] and
- *   k_pooled [batch, n_kv_heads, NB, head_dim], contiguous fp32.
+ *   k_pooled [batch, n_kv_heads, NBk, head_dim] (NBk = NB without a KV prefix),
+ *   contiguous fp32; a partial last block is averaged over the tokens it has.
  * Either of (q, q_pooled) or (k, k_pooled) may be NULL as a pair to skip it. */
 int sparse_prefill_pool(const spa_params *p, const void *q, const void *k,
                         float *q_pooled, float *k_pooled, void *hip_stream);
@@ -134,8 +138,9 @@ int sparse_prefill_pool(const spa_params *p, const void *q, const void *k,
  * take per row the top_k_blocks best non-static causal blocks (ties: lowest
  * block index; NaN ranks below every number; -0 equals +0) and unite them with
  * the static blocks.  Writes block_idx / block_cnt.
- * pooled_scores_or_null: if not NULL, [batch, n_q_heads, NB, NB] fp32 receives
- * the scores (entries with j > i are written as -inf).
+ * pooled_scores_or_null: if not NULL, [batch, n_q_heads, NB, NBk] fp32 receives
+ * the scores (entries beyond the causal limit, j > i + NBk - NB, are written as
+ * -inf; NBk = NB without a KV prefix).
  * ws: spa_workspace_bytes() bytes of scratch, 256-byte aligned. */
 int sparse_prefill_select(const spa_params *p, const void *q, const void *k,
                           int32_t *block_idx, int32_t *block_cnt,
@@ -143,7 +148,7 @@ int sparse_prefill_select(const spa_params *p, const void *q, const void *k,
                           void *hip_stream);
 
 /* The top-k + static-merge step alone, on caller-supplied scores
- * [batch, n_q_heads, NB, NB] fp32 (entries with j > i are ignored).  Given the
+ * [batch, n_q_heads, NB, NBk] fp32 (entries beyond the causal limit are ignored).  Given the
  * same scores this produces the same lists as sparse_prefill_select, bit for
  * bit.  Uses of p: shape, pattern. */
 int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_scores,
@@ -152,7 +157,7 @@ int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_sco
 
 /* Sparse attention kernel (Sec. 4.1.1): for query token t of block i,
  *   out[t] = softmax over { s <= t : block(s) in block_idx[b,h,i,:cnt] } of
- *            scale * q_t . k_s, applied to v_s,
+ *            scale * q_t . k_s, applied to v_s     (s, t counted from the start of K/V),
  * bf16 MFMA with fp32 accumulation and fp32 online softmax; out is bf16.
  * lse_or_null: if not NULL, [batch, n_q_heads, seq_len] fp32 receives the
  * natural-log sum of exponentials of the scaled logits of each row.
