@@ -450,8 +450,9 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles t+1 and t+2
 
     // One 64-key sub-tile t = steps 2t and 2t+1.  Reads K(t+1) (look-ahead logits) and V^T(t).
-    auto sub_tile = [&](auto par_tag, int t) {
+    auto sub_tile = [&](auto par_tag, auto plain_tag, int t) {
         constexpr int PAR = decltype(par_tag)::value;      // t % 2
+        constexpr bool PLAIN = decltype(plain_tag)::value != 0;   // far from the end: all loads exist, no masks
         using KB = IC<1 - PAR>;
         using VB = IC<PAR>;
         // K(t+1) and V(t) have been requested; make them visible and retire the previous
@@ -462,14 +463,16 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         f[0] = lds16(ldsK + KB::value * TILE_B + kofs[0]);
         f[1] = lds16(ldsV + VB::value * TILE_B + vofs[0]);
         f[2] = lds16(ldsK + KB::value * TILE_B + kofs[1]);
-        if (t + 2 < n_st) issue_k(IC<PAR>{}, t + 2, blk2);
-        if (t + 1 < n_st) issue_v(IC<1 - PAR>{}, t + 1, blk1);
+        if (PLAIN || t + 2 < n_st) issue_k(IC<PAR>{}, t + 2, blk2);
+        if (PLAIN || t + 1 < n_st) issue_v(IC<1 - PAR>{}, t + 1, blk1);
         blk1 = blk2;
         blk2 = blk_of(t + 3);
         // logits about to be turned into weights: chunk 1 of this sub-tile, then chunk 0 of the next
-        if (t >= n_st - NSUB) mask_diag(sB, t % NSUB, 1);          // the diagonal block is the last of the list
+        if constexpr (!PLAIN)
+            if (t >= n_st - NSUB) mask_diag(sB, t % NSUB, 1);      // the diagonal block is the last of the list
         step(KB{}, VB{}, IC<0>{}, sB, sA, pA0, pA1, pB0, pB1, f);
-        if (t + 1 >= n_st) {
+        if constexpr (PLAIN) {
+        } else if (t + 1 >= n_st) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sA[r] = -INFINITY;        // past the end: look-ahead of a stale buffer
         } else if (t + 1 >= n_st - NSUB) {
@@ -477,10 +480,18 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
         }
         step(KB{}, VB{}, IC<1>{}, sA, sB, pB0, pB1, pA0, pA1, f);
     };
-    for (int t = 0;;) {
-        sub_tile(IC<0>{}, t);
+    // sub-tiles whose two softmaxed chunks lie before the diagonal block and whose loads all exist
+    // run without the mask and end-of-list tests; the last NSUB + 2 (rounded to even) keep them
+    int t = 0;
+    const int t_plain = (n_st - NSUB - 2) & ~1;
+    for (; t < t_plain; t += 2) {
+        sub_tile(IC<0>{}, IC<1>{}, t);
+        sub_tile(IC<1>{}, IC<1>{}, t + 1);
+    }
+    for (;;) {
+        sub_tile(IC<0>{}, IC<0>{}, t);
         if (++t == n_st) break;
-        sub_tile(IC<1>{}, t);
+        sub_tile(IC<1>{}, IC<0>{}, t);
         if (++t == n_st) break;
     }
 
