@@ -127,3 +127,10 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
     assert lib.sparse_prefill_attn(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, fake, 1 << 30, None) == -4
     assert lib.spa_strerror(0).decode() == "ok"
     assert lib.spa_strerror(-99).decode() == "unknown error code"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
