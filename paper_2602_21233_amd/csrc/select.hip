@@ -214,11 +214,32 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
-// Exact k-th largest by most-significant-digit radix selection, 8 bits per pass: the wavefront
-// histograms the current digit of the keys that still match the decided prefix into its own 256 LDS
-// counters (LDS atomics), lane l then owns the four bins 255-4l .. 252-4l, a prefix sum over the
-// lanes finds the bin that holds the wanted rank, and that bin's digit extends the prefix.  Four
-// passes replace up to 32 counting steps over all keys; a pass that takes its whole bin ends early.
+// maximum / minimum of v over the 64 lanes, returned wave-uniform (same lane walk as wave_sum;
+// lanes of rows that a step leaves out combine with the neutral element)
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    auto mx = [](uint32_t a, int b) { return a > (uint32_t)b ? a : (uint32_t)b; };
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, true));
+    v = mx(v, __builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, true));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
+
+// Exact k-th largest key of a row, in two steps.
+// 1. A bound from the lanes: with t = ceil(kk / 64), every lane's t-th largest key is matched or
+//    beaten by t keys of that lane, so at least 64 t >= kk keys reach L = the smallest of the 64
+//    lanes' t-th largest keys: the k-th largest is >= L, keys below L can neither be selected nor
+//    tie with the threshold and drop out.  With 16 keys per lane and kk = 64 that leaves about a
+//    tenth of the row.  (t <= 2 here; a lane without t candidates gives L = 0: no bound.)
+// 2. Most-significant-digit radix selection among the keys in [L, H] (H = the row maximum), up
+//    to 8 bits per pass, starting at the highest bit in which L and H differ (the bits above are
+//    common to all of them): the wavefront histograms the current digit of the keys that still match
+//    the decided prefix into its own 256 LDS counters (LDS atomics), lane l then owns the four bins
+//    255-4l .. 252-4l, a prefix sum over the lanes finds the bin that holds the wanted rank, and
+//    that bin's digit extends the prefix.  A pass that takes its whole bin ends the search.
 // key[m] belongs to block 64*m + lane and is 0 for static blocks, blocks beyond i and unused chunks
 // (0 is never counted); NC <= MAXC: only key[0 .. NC) can be nonzero for this row.  Returns
 // thr / need_eq: take key > thr, plus the first need_eq keys equal to thr in block order.
@@ -230,62 +251,105 @@ __device__ __forceinline__ void find_threshold_hist(const uint32_t (&key)[MAXC],
     need_eq = 0;
     if (kk <= 0) return;
     if (kk == n_cand) { thr = 0u; return; }
-    uint32_t prefix = 0u;     // decided digits, low bits zero
-    int want = kk;            // rank wanted among the keys that match the prefix (1 = largest)
+    uint32_t m1 = 0u, m2 = 0u;           // largest and second largest key of the lane
+#pragma unroll
+    for (int m = 0; m < NC; ++m) {
+        const uint32_t v = key[m];
+        const uint32_t lo = v < m1 ? v : m1;
+        m2 = m2 > lo ? m2 : lo;
+        m1 = m1 > v ? m1 : v;
+    }
+    const uint32_t H = wave_max_u32(m1);
+    uint32_t L = kk <= 64 ? wave_min_u32(m1) : (kk <= 128 ? wave_min_u32(m2) : 0u);
+    if (L == 0u) L = 1u;                 // no bound: every candidate (keys are >= 1) takes part
+    if (L == H) {                        // all keys that matter are equal
+        thr = H;
+        need_eq = kk;
+        return;
+    }
+    const int hb = 31 - __builtin_clz(L ^ H);                 // highest bit in which the keys in [L, H] can differ
+    uint32_t prefix = hb == 31 ? 0u : (H >> (hb + 1)) << (hb + 1);   // decided bits, the rest zero
+    int want = kk;                       // rank wanted among the keys that match the prefix (1 = largest)
+    int top = hb + 1;                    // bits [top, 32) are decided
 #pragma nounroll
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    while (top > 0) {
+        const int shift = top > 8 ? top - 8 : 0;              // this pass decides bits [shift, top)
+        const uint32_t dmask = (1u << (top - shift)) - 1u;
         *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
         for (int m = 0; m < NC; ++m) {
             const uint32_t kv = key[m];
-            // ((kv ^ prefix) >> shift) >> 8 == 0: the digits above this one match (two shifts: shift + 8 may be 32)
-            if (kv != 0u && (((kv ^ prefix) >> shift) >> 8) == 0u) atomicAdd(&hist[(kv >> shift) & 255u], 1u);
+            // kv >= L, and its decided bits match (two shifts: top may be 32)
+            if (kv >= L && (((kv ^ prefix) >> (top - 1)) >> 1) == 0u) atomicAdd(&hist[(kv >> shift) & dmask], 1u);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const uint4 h = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // .w = bin 255-4l ... .x = bin 252-4l
         const int own = (int)(h.x + h.y + h.z + h.w);
         const int incl = wave_inclusive_scan(own);
-        const int L = __ffsll((unsigned long long)__ballot(incl >= want)) - 1;   // lane whose bins hold the wanted rank
-        const int before = __builtin_amdgcn_readlane(incl - own, L);                 // keys in higher bins
-        const int b3 = __builtin_amdgcn_readlane((int)h.w, L), b2 = __builtin_amdgcn_readlane((int)h.z, L);
-        const int b1 = __builtin_amdgcn_readlane((int)h.y, L), b0 = __builtin_amdgcn_readlane((int)h.x, L);
-        const int rem = want - before;                                               // 1 .. own(L)
+        const int Ln = __ffsll((unsigned long long)__ballot(incl >= want)) - 1;  // lane whose bins hold the wanted rank
+        const int before = __builtin_amdgcn_readlane(incl - own, Ln);                // keys in higher bins
+        const int b3 = __builtin_amdgcn_readlane((int)h.w, Ln), b2 = __builtin_amdgcn_readlane((int)h.z, Ln);
+        const int b1 = __builtin_amdgcn_readlane((int)h.y, Ln), b0 = __builtin_amdgcn_readlane((int)h.x, Ln);
+        const int rem = want - before;                                               // 1 .. own(Ln)
         int digit, above, in_bin;
-        if (rem <= b3) { digit = 255 - 4 * L; above = 0; in_bin = b3; }
-        else if (rem <= b3 + b2) { digit = 254 - 4 * L; above = b3; in_bin = b2; }
-        else if (rem <= b3 + b2 + b1) { digit = 253 - 4 * L; above = b3 + b2; in_bin = b1; }
-        else { digit = 252 - 4 * L; above = b3 + b2 + b1; in_bin = b0; }
+        if (rem <= b3) { digit = 255 - 4 * Ln; above = 0; in_bin = b3; }
+        else if (rem <= b3 + b2) { digit = 254 - 4 * Ln; above = b3; in_bin = b2; }
+        else if (rem <= b3 + b2 + b1) { digit = 253 - 4 * Ln; above = b3 + b2; in_bin = b1; }
+        else { digit = 252 - 4 * Ln; above = b3 + b2 + b1; in_bin = b0; }
         want = rem - above;                                                          // rank inside the chosen bin
         prefix |= (uint32_t)digit << shift;
-        if (want == in_bin) {          // the whole bin is taken: every key >= prefix, none below
-            thr = prefix != 0u ? prefix - 1u : 0u;   // (prefix 0 would mean every candidate is taken)
+        if (want == in_bin) {          // the whole bin is taken: every key that reaches both the bin's
+            const uint32_t edge = prefix > L ? prefix : L;    // lower edge and L, none below
+            thr = edge - 1u;           // edge >= L >= 1
             return;
         }
+        top = shift;
     }
     thr = prefix;                      // the k-th largest key itself; `want` of its copies are taken
     need_eq = want;
 }
 
+// Everything the score + top-k step of one workgroup needs besides its rows.
+struct ScoreArgs {
+    const float* qp;              // pooled Q [B*Hq, NB, D] fp32
+    const float* kp;              // pooled K, tiled in operand layout by the pooling kernel
+    int Hq, G, NB /* query blocks */, NBk, off /* block position of query block 0 */;
+    Pattern pt;
+    int k;
+    const int32_t* k_rows;
+    const int32_t* head_pattern;
+    const float* lvn;
+    int T;
+    float scale;
+    int32_t* idx;
+    int32_t* cnt;
+    float* scores_out;
+};
+
+// Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
+// 512-thread workgroup.  S: R * (MAXC * 64 + 8) floats of LDS for the scores, then 256 counters per
+// wavefront.  Ends without a barrier; the caller must not reuse S before one.
+// The split pooled queries (MFMA A operands) are staged in LDS, in the space of the phase-2 counters,
+// instead of being held in 8 * D / 16 registers per lane: the kernel stays within 128 registers.
+// Needs R * D * 4 bytes <= the counters' 8 KB.
 template <int D, int R, int MAXC, bool EXT>
-__global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
-    const float* __restrict__ qp, const float* __restrict__ kp, int Hq, int G, int NB /* query blocks */, int NBk,
-    int off /* block position of query block 0 */, int n_tiles, Pattern pt,
-    int k, const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern,
-    const float* __restrict__ lvn, int T, float scale, int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-    float* __restrict__ scores_out) {
+__device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
-    extern __shared__ float S[];               // [R][LD] scores of this workgroup's rows, then 256 counters per wave
+    const float* __restrict__ qp = a.qp;
+    const float* __restrict__ kp = a.kp;
+    const int Hq = a.Hq, G = a.G, NB = a.NB, NBk = a.NBk, off = a.off, T = a.T;
+    Pattern pt = a.pt;
+    int k = a.k;
+    const int32_t* __restrict__ k_rows = a.k_rows;
+    const int32_t* __restrict__ head_pattern = a.head_pattern;
+    const float* __restrict__ lvn = a.lvn;
+    const float scale = a.scale;
+    int32_t* __restrict__ idx = a.idx;
+    int32_t* __restrict__ cnt = a.cnt;
+    float* __restrict__ scores_out = a.scores_out;
 
-    // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
-    // (b, head, row tile) order so that one L2 serves few KV heads and their Kp stays resident.
-    const int nwg = gridDim.x;
-    int wg = blockIdx.x;
-    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
-    const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
-    const int i0 = tile * R;
-    const int bh = wg / n_tiles;                          // b * Hq + h
     const int b = bh / Hq, h = bh % Hq;
     const int Hkv = Hq / G;
     const float* qbase = qp + (int64_t)bh * NB * D;
@@ -297,15 +361,23 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     const int n_jt = ((i_last + off) >> 5) + 1;           // 32-wide key-block tiles with some causal j
 
     // ---- phase 1 ---------------------------------------------------------------------
-    bf16x8 q_hi[DS], q_lo[DS];
+    // LDS copy of the split queries: the 8 dims 16s + 8 * half .. +7 of row r, part p (0 = hi, 1 = lo)
+    // at bf16 offset ((((s * 2 + p) * R + r) * 2 + half) * 8
+    __bf16* const qlds = reinterpret_cast<__bf16*>(S + R * LD);
     {
-        int row = i0 + (l32 % R);
-        if (row > NB - 1) row = NB - 1;                   // rows past the end are computed but never used
-        const float* src = qbase + (int64_t)row * D + 8 * half;
-#pragma unroll
-        for (int s = 0; s < DS; ++s)
-            split_bf16(*reinterpret_cast<const float4*>(src + 16 * s), *reinterpret_cast<const float4*>(src + 16 * s + 4),
-                       q_hi[s], q_lo[s]);
+        static_assert(R * D * 4 <= kMfmaWaves * 256 * 4, "staged queries must fit the counters' space");
+        const int t = threadIdx.x;
+        if (t < R * DS * 2) {
+            const int r = t % R, s2 = (t / R) >> 1, hf = (t / R) & 1;
+            int row = i0 + r;
+            if (row > NB - 1) row = NB - 1;               // rows past the end are computed but never used
+            const float* src = qbase + (int64_t)row * D + 16 * s2 + 8 * hf;
+            bf16x8 hi, lo;
+            split_bf16(*reinterpret_cast<const float4*>(src), *reinterpret_cast<const float4*>(src + 4), hi, lo);
+            *reinterpret_cast<bf16x8*>(qlds + (((s2 * 2 + 0) * R + r) * 2 + hf) * 8) = hi;
+            *reinterpret_cast<bf16x8*>(qlds + (((s2 * 2 + 1) * R + r) * 2 + hf) * 8) = lo;
+        }
+        __syncthreads();
     }
     // The pooled K arrives tiled in operand layout and already split into bf16 head and tail:
     // tile jt of 32 key blocks is 32 * D * 4 bytes, and the 8 dims 16s + 8 * half .. +7 of block
@@ -340,9 +412,11 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             const bf16x8 k_hi = kraw[2 * s], k_lo = kraw[2 * s + 1];
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_lo[s], k_hi, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_lo, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q_hi[s], k_hi, acc, 0, 0, 0);
+            const bf16x8 qh = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 0) * R + l32 % R) * 2 + half) * 8);
+            const bf16x8 ql = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 1) * R + l32 % R) * 2 + half) * 8);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ql, k_hi, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_lo, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_hi, acc, 0, 0, 0);
             kraw[2 * s] = *reinterpret_cast<const bf16x8*>(next + s * 1024);
             kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(next + s * 1024 + 256);
         }
@@ -432,10 +506,30 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void score_topk_mfma_kernel(
     }
 }
 
+// Two workgroups per CU (4 wavefronts per SIMD): at most 128 registers, which is why the query
+// operands are staged in LDS.
+template <int D, int R, int MAXC, bool EXT>
+__global__ __launch_bounds__(kMfmaWaves * 64, 4) void score_topk_mfma_kernel(ScoreArgs a, int n_tiles) {
+    extern __shared__ __attribute__((aligned(128))) float S[];   // [R][LD] scores of this workgroup's rows, then 256 counters per wave
+    // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
+    // (b, head, row tile) order so that one L2 serves few KV heads and their Kp stays resident.
+    const int nwg = gridDim.x;
+    int wg = blockIdx.x;
+    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
+    score_topk_rows<D, R, MAXC, EXT>(a, wg / n_tiles, tile * R, S);
+}
+
 // Dynamic LDS above the default cap has to be requested per kernel.
 hipError_t allow_lds(const void* kernel, size_t bytes) {
     if (bytes <= 32768) return hipSuccess;
     return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+ScoreArgs score_args(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern,
+                     const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null) {
+    return ScoreArgs{qp, kp, d.Hq, d.G, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale,
+                     idx, cnt, scores_or_null};
 }
 
 size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) * sizeof(uint32_t); }
@@ -466,8 +560,8 @@ hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const 
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
-    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, qp, kp, d.Hq,
-                       d.G, d.NB, d.NBk, d.off, n_tiles, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale, idx, cnt, scores_or_null);
+    const ScoreArgs a = score_args(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null);
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, a, n_tiles);
     return hipGetLastError();
 }
 
@@ -481,12 +575,14 @@ hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const in
 template <int D>
 hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                          int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores must fit the LDS
-    if (d.NBk <= 256) return launch_mfma<D, 32, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 512) return launch_mfma<D, 32, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 1024) return launch_mfma<D, 32, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma<D, 8, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores stay within 66 KB of
+    // LDS, so that two workgroups share a CU (measured at 131072 / 262144 tokens: 125 -> 106 us and
+    // 0.64 -> 0.50 ms against 32 / 16 rows with one workgroup per CU)
+    if (d.NBk <= 256) return launch_mfma<D, 16, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 512) return launch_mfma<D, 16, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 1024) return launch_mfma<D, 16, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (d.NBk <= 2048) return launch_mfma<D, 8, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma<D, 4, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,

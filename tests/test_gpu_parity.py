@@ -369,6 +369,29 @@ def test_select_parity(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k):
     assert agree > 0.98                              # near-ties may flip; reported, loosely gated
 
 
+@pytest.mark.parametrize("NB,D,Bs,ns,nl,k,n_distinct", [
+    (70, 128, 64, 1, 2, 9, 1), (70, 128, 64, 1, 2, 9, 3), (300, 64, 64, 2, 3, 40, 5), (1100, 128, 64, 1, 4, 64, 7),
+    (1100, 128, 64, 1, 4, 100, 2), (1100, 128, 64, 0, 1, 200, 4), (2100, 64, 64, 1, 2, 64, 6)])
+def test_select_with_tied_scores(spa, oracle, NB, D, Bs, ns, nl, k, n_distinct):
+    """Key blocks drawn from a handful of distinct blocks pool to identical vectors, so every row's
+    scores fall into n_distinct groups of exact ties (one group: all equal).  The threshold search of
+    the select kernel must then cut inside a group of equal keys and keep the lowest block indices."""
+    g = torch.Generator().manual_seed(1000 + NB + n_distinct)
+    S = NB * Bs
+    q = torch.randn((1, 2, S, D), generator=g).to(torch.bfloat16)
+    base = torch.randn((n_distinct, Bs, D), generator=g).to(torch.bfloat16)
+    which = torch.randint(0, n_distinct, (NB,), generator=g)
+    kk = base[which].reshape(1, 1, S, D).contiguous()
+    idx, cnt, sp = spa.select(q.cuda(), kk.cuda(), Bs, ns, nl, k, return_scores=True)
+    sp = sp.cpu()
+    # the premise: a row holds at most n_distinct different scores
+    assert len(torch.unique(sp[0, 0, NB - 1, :NB])) <= n_distinct
+    g_idx, g_cnt = oracle.topk(sp, ns, nl, k)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    t_idx, t_cnt = spa.topk_from_scores(sp.cuda(), ns, nl, k)
+    assert torch.equal(t_idx, idx) and torch.equal(t_cnt, cnt)
+
+
 # ------------------------------------------------------------- attention
 def _oracle_lists(oracle, q, k, Bs, ns, nl, topk):
     idx, cnt, *_ = oracle.select(q, k, Bs, ns, nl, topk)
