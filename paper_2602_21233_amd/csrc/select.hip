@@ -449,12 +449,21 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         const int i = iq + off;                           // its block position in the sequence
         const int n = i + 1;
         const float* srow = S + r * LD;
+        // keys and static flags of the row's blocks stay in registers until the lists are written;
+        // rows are causal: a row early in the sequence fills only its first chunks of 64 blocks
+        const int chunks = (n + 63) >> 6;                 // wave-uniform
         uint32_t key[MAXC];
+        uint64_t is_static_bits = 0ull;                   // bit m: block 64 m + lane is static
 #pragma unroll
         for (int m = 0; m < MAXC; ++m) {
-            const int j = (m << 6) + lane;                // < MAXC*64 <= LD: always inside the row
-            const uint32_t kv = rank_key(srow[j]);        // columns past the computed tiles hold junk: masked next
-            key[m] = (j <= i && !static_block<EXT>(pt, i, j)) ? kv : 0u;
+            key[m] = 0u;
+            if (m < chunks) {
+                const int j = (m << 6) + lane;            // < MAXC*64 <= LD: always inside the row
+                const bool st = j <= i && static_block<EXT>(pt, i, j);
+                const uint32_t kv = rank_key(srow[j]);    // columns past the computed tiles hold junk: masked next
+                key[m] = (j <= i && !st) ? kv : 0u;
+                is_static_bits |= st ? (1ull << m) : 0ull;
+            }
         }
         int n_cand;
         if constexpr (EXT) {                              // count the candidates: no closed form worth having
@@ -474,32 +483,30 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
         int need_eq;
-        // rows are causal: a row early in the sequence fills only its first chunks of 64 blocks
-        const int nc4 = 4 * ((i >> 6) + 1);               // wave-uniform
+        const int nc4 = 4 * chunks;
         uint32_t* hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
         if (nc4 <= MAXC) find_threshold_hist<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
         else if (nc4 <= 2 * MAXC) find_threshold_hist<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, hist, lane, thr, need_eq);
         else if (nc4 <= 3 * MAXC) find_threshold_hist<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
         else find_threshold_hist<MAXC, MAXC>(key, kk, n_cand, hist, lane, thr, need_eq);
 
-        // emit static U top-k in ascending block order (keys recomputed from LDS: a rolled loop)
+        // emit static U top-k in ascending block order
         const int64_t row = (int64_t)bh * NB + iq;
         int32_t* idx_row = idx + row * T;
-        const int chunks = (n + 63) >> 6;
         int eq_seen = 0, out_pos = 0;
-#pragma nounroll
-        for (int m = 0; m < chunks; ++m) {
-            const int j = (m << 6) + lane;
-            const bool is_static = j < n && static_block<EXT>(pt, i, j);
-            const uint32_t kv = (j <= i && !is_static) ? rank_key(srow[j]) : 0u;
-            const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
-            const uint64_t eq_mask = __ballot(is_eq);
-            const bool take = is_static || (kv != 0u && kv > thr) ||
-                              (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
-            const uint64_t take_mask = __ballot(take);
-            if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = j;
-            eq_seen += __popcll(eq_mask);
-            out_pos += __popcll(take_mask);
+#pragma unroll
+        for (int m = 0; m < MAXC; ++m) {
+            if (m < chunks) {
+                const uint32_t kv = key[m];
+                const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
+                const uint64_t eq_mask = __ballot(is_eq);
+                const bool take = ((is_static_bits >> m) & 1ull) != 0ull || (kv != 0u && kv > thr) ||
+                                  (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
+                const uint64_t take_mask = __ballot(take);
+                if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = (m << 6) + lane;
+                eq_seen += __popcll(eq_mask);
+                out_pos += __popcll(take_mask);
+            }
         }
         for (int t = out_pos + lane; t < T; t += 64) idx_row[t] = -1;
         if (lane == 0) cnt[row] = out_pos;
