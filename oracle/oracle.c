@@ -194,11 +194,82 @@ int64_t oracle_row_capacity(int64_t NB, int64_t ns, int64_t nl, int64_t k, int64
 
 static int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
+/* Cumulative-mass budget (the rule of the FlexPrefill family, which Sec. 4.1.1 lists among the
+ * dynamic algorithms of the framework and Sec. 4.1.2 under "Other Sparse Attention Strategies";
+ * the paper gives no formula).  Reading: a query block keeps, in ranking order, the fewest
+ * candidates for which the selected blocks (static ones included) hold at least the fraction
+ * gamma of the row's block-level softmax mass, and never more than its count budget.
+ *
+ * A floating-point sum would decide an integer here (how many blocks), so the mass is DEFINED in
+ * integer arithmetic, which any implementation can reproduce bit for bit whatever its order of
+ * summation.  For the causal blocks j <= i of a row with ranking scores x_j (fp32):
+ *   m   = max_j x_j over the scores that are not NaN
+ *   W_j = mass_weight(x_j, m), an integer in [0, 2^19] ~ 2^19 exp(x_j - m), see below
+ *   Z   = sum_j W_j;  Gamma = floor(gamma * 65536 + 0.5) (gamma clamped to [0, 1])
+ *   target = ceil(Gamma * Z / 65536)
+ * and the row takes candidates in ranking order until mass(static) + mass(taken) >= target.
+ *
+ * mass_weight: every step is a single IEEE fp32 operation (no contraction), so the result does
+ * not depend on the machine: t = (x - m) * log2(e); n = nearest integer to t (ties to even);
+ * f = t - n in [-1/2, 1/2]; 2^f by the degree-6 Taylor polynomial of e^(f ln 2) in Horner form
+ * with fused multiply-adds (truncation error < 1.3e-7); w = that times 2^n; W = floor(w * 2^19 + 1/2).
+ * NaN and -inf scores, and anything more than 2^-40 below the maximum, weigh 0. */
+static uint32_t mass_weight(float x, float m) {
+    if (isnan(x) || isnan(m)) return 0u;
+    if (x == m) return 1u << 19;                 /* also covers m = +inf */
+    if (isinf(x) || isinf(m)) return 0u;         /* x = -inf, or finite x under m = +inf */
+    const float t = (x - m) * 1.44269504088896340736f;
+    if (!(t >= -40.0f)) return 0u;
+    const float n = rintf(t);
+    const float f = t - n;
+    float p = 1.5403530393381609954e-4f;
+    p = fmaf(p, f, 1.3333558146428443423e-3f);
+    p = fmaf(p, f, 9.6181291076284771619e-3f);
+    p = fmaf(p, f, 5.5504108664821579953e-2f);
+    p = fmaf(p, f, 2.4022650695910071233e-1f);
+    p = fmaf(p, f, 6.9314718055994530942e-1f);
+    p = fmaf(p, f, 1.0f);
+    const float w = ldexpf(p, (int)n);
+    return (uint32_t)(w * 524288.0f + 0.5f);
+}
+
+/* The weights alone, for the tests: W [n_rows_total, NBq, NBk] uint32 (0 beyond the causal limit). */
+int oracle_mass_weights(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk, uint32_t *W) {
+    if (NBk < NBq) return -1;
+    const int64_t off = NBk - NBq;
+    for (int64_t r = 0; r < n_heads_total * NBq; ++r) {
+        const int64_t i = r % NBq + off;
+        const float *srow = sp + r * NBk;
+        float m = -INFINITY;
+        for (int64_t j = 0; j <= i; ++j)
+            if (!isnan(srow[j]) && srow[j] > m) m = srow[j];
+        for (int64_t j = 0; j < NBk; ++j) W[r * NBk + j] = j <= i ? mass_weight(srow[j], m) : 0u;
+    }
+    return 0;
+}
+
+int oracle_topk_mass(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk, int64_t ns_max,
+                     int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
+                     int64_t n_dense, int64_t reach, const int32_t *head_pattern, int64_t Hq,
+                     double gamma, int32_t *idx, int32_t *cnt);
+
 int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk, int64_t ns_max,
                 int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
                 int64_t n_dense, int64_t reach, const int32_t *head_pattern, int64_t Hq,
                 int32_t *idx, int32_t *cnt) {
+    return oracle_topk_mass(sp, n_heads_total, NBq, NBk, ns_max, nl_max, k_max, k_row, stride, n_dense, reach,
+                            head_pattern, Hq, -1.0, idx, cnt);
+}
+
+/* gamma < 0: count budgets only (oracle_topk); gamma in [0, 1]: the cumulative-mass budget on top. */
+int oracle_topk_mass(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk, int64_t ns_max,
+                     int64_t nl_max, int64_t k_max, const int32_t *k_row, int64_t stride,
+                     int64_t n_dense, int64_t reach, const int32_t *head_pattern, int64_t Hq,
+                     double gamma, int32_t *idx, int32_t *cnt) {
     if (ns_max < 0 || nl_max < 1 || k_max < 0 || stride < 0 || n_dense < 0 || reach < 0) return -1;
+    if (gamma > 1.0) gamma = 1.0;
+    const int use_mass = gamma >= 0.0;
+    const uint64_t Gamma = use_mass ? (uint64_t)floor(gamma * 65536.0 + 0.5) : 0;
     if (head_pattern && Hq < 1) return -1;
     if (NBk < NBq) return -1;
     const int64_t ns0 = ns_max, nl0 = nl_max, k0 = k_max, off = NBk - NBq;
@@ -236,7 +307,21 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk
                 k_i = clamp64(k_row[iq], 0, k0);
                 if (k_i > k) k_i = k;
             }
+            uint64_t have = 0, target = 0;        /* mass selected so far, mass wanted */
+            float m = -INFINITY;
+            if (use_mass) {
+                uint64_t Z = 0;
+                for (int64_t j = 0; j <= i; ++j)
+                    if (!isnan(srow[j]) && srow[j] > m) m = srow[j];
+                for (int64_t j = 0; j <= i; ++j) {
+                    const uint64_t w = mass_weight(srow[j], m);
+                    Z += w;
+                    if (sel[j]) have += w;
+                }
+                target = (Gamma * Z + 65535) >> 16;
+            }
             for (int64_t pick = 0; pick < k_i; ++pick) {
+                if (use_mass && have >= target) break;   /* the mass budget is met */
                 int64_t best = -1;
                 for (int64_t j = 0; j <= i; ++j) {
                     if (sel[j]) continue;
@@ -244,6 +329,7 @@ int oracle_topk(const float *sp, int64_t n_heads_total, int64_t NBq, int64_t NBk
                 }
                 if (best < 0) break; /* candidates exhausted */
                 sel[best] = 1;
+                if (use_mass) have += mass_weight(srow[best], m);
             }
             int64_t c = 0;
             for (int64_t j = 0; j <= i; ++j)

@@ -37,6 +37,8 @@ def _load():
         lib.oracle_pool.argtypes = [vp, i64, i64, i64, i64, vp]
         lib.oracle_scores.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, f32, vp]
         lib.oracle_topk.argtypes = [vp, i64, i64, i64, i64, i64, i64, vp, i64, i64, i64, vp, i64, vp, vp]
+        lib.oracle_topk_mass.argtypes = [vp, i64, i64, i64, i64, i64, i64, vp, i64, i64, i64, vp, i64, ctypes.c_double, vp, vp]
+        lib.oracle_mass_weights.argtypes = [vp, i64, i64, i64, vp]
         lib.oracle_row_capacity.argtypes = [i64] * 7
         lib.oracle_row_capacity.restype = ctypes.c_int64
         lib.oracle_vnorm.argtypes = [vp, i64, i64, i64, i64, vp]
@@ -44,7 +46,8 @@ def _load():
         lib.oracle_attn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64, f32,
                                     vp, vp, vp, i64, vp, vp]
         for f in (lib.oracle_pool, lib.oracle_scores, lib.oracle_topk, lib.oracle_attn,
-                  lib.oracle_num_threads, lib.oracle_vnorm, lib.oracle_scores_oam):
+                  lib.oracle_num_threads, lib.oracle_vnorm, lib.oracle_scores_oam, lib.oracle_topk_mass,
+                  lib.oracle_mass_weights):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -115,14 +118,28 @@ def scores_oam(sp: torch.Tensor, vn: torch.Tensor) -> torch.Tensor:
     return out
 
 
+def mass_weights(sp: torch.Tensor) -> torch.Tensor:
+    """Integer softmax weights of the cumulative-mass budget: sp [B,Hq,NBq,NBk] fp32 -> int64
+    [B,Hq,NBq,NBk], W ~ 2^19 exp(score - row max) for the causal blocks, 0 beyond."""
+    B, Hq, NB, NBk = sp.shape
+    sp = sp.contiguous()
+    assert sp.dtype == torch.float32
+    w = torch.empty((B, Hq, NB, NBk), dtype=torch.int32)
+    _check(_load().oracle_mass_weights(sp.data_ptr(), B * Hq, NB, NBk, w.data_ptr()), "mass_weights")
+    return w.to(torch.int64) & 0xffffffff
+
+
 def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | None = None,
-         stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0):
+         stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0,
+         gamma: float | None = None):
     """sp [B,Hq,NBq,NBk] fp32 -> idx [B,Hq,NBq,T] int32 (pad -1), cnt [B,Hq,NBq] int32; NBk > NBq
     is a KV prefix of NBk - NBq blocks (pattern and capacity then refer to positions in NBk).
     k_per_row: optional [NB] int32 position-dependent budget (clamped to [0, k]).
     stride / n_dense: strided static columns and the dense bottom strip of the Tri-shape.
     head_pattern: optional [Hq,3] int32 (n_sink, n_local, top_k) per query head; ns, nl, k are
-    then the maxima."""
+    then the maxima.
+    gamma: optional cumulative-mass budget in [0, 1]: a row stops taking candidates once the selected
+    blocks hold that fraction of its block-level softmax mass (count budgets stay as caps)."""
     B, Hq, NB, NBk = sp.shape
     sp = sp.contiguous()
     assert sp.dtype == torch.float32
@@ -139,15 +156,20 @@ def topk(sp: torch.Tensor, ns: int, nl: int, k: int, k_per_row: torch.Tensor | N
         head_pattern = head_pattern.to(torch.int32).contiguous()
         assert head_pattern.shape == (Hq, 3) and head_pattern.device.type == "cpu"
         hp_ptr = head_pattern.data_ptr()
-    _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, NBk, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr, Hq,
-                               idx.data_ptr(), cnt.data_ptr()), "topk")
+    if gamma is None:
+        _check(_load().oracle_topk(sp.data_ptr(), B * Hq, NB, NBk, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr, Hq,
+                                   idx.data_ptr(), cnt.data_ptr()), "topk")
+    else:
+        # the budget is stated as an fp32 number, like the library's parameter
+        _check(_load().oracle_topk_mass(sp.data_ptr(), B * Hq, NB, NBk, ns, nl, k, kr_ptr, stride, n_dense, reach, hp_ptr,
+                                        Hq, float(np.float32(gamma)), idx.data_ptr(), cnt.data_ptr()), "topk_mass")
     return idx, cnt
 
 
 def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, topk_blocks: int,
            scale: float | None = None, k_per_row: torch.Tensor | None = None, v: torch.Tensor | None = None,
            stride: int = 0, n_dense: int = 0, head_pattern: torch.Tensor | None = None, reach: int = 0,
-           group_shared: bool = False):
+           group_shared: bool = False, gamma: float | None = None):
     """Pool, score, top-k, merge.  Returns (idx, cnt, sp, qp, kp).  With v the ranking score is
     the output-aware one (scores_oam) and sp is that score.
 
@@ -164,7 +186,7 @@ def select(q: torch.Tensor, k: torch.Tensor, block_size: int, ns: int, nl: int, 
     sp = scores(qp, kp, scale)
     if v is not None:
         sp = scores_oam(sp, vnorm(v, block_size))
-    idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row, stride, n_dense, head_pattern, reach)
+    idx, cnt = topk(sp, ns, nl, topk_blocks, k_per_row, stride, n_dense, head_pattern, reach, gamma)
     return idx, cnt, sp, qp, kp
 
 
