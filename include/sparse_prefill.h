@@ -249,11 +249,27 @@ int sparse_prefill_fused_stem(const spa_params *p, const void *q, const void *k,
  *                    in the kernels to [0, p->n_sink_blocks], [1, p->n_local_blocks],
  *                    [0, p->top_k_blocks]: the spa_params values are then the maxima and fix the row
  *                    capacity.  With a schedule, head h draws min(schedule[i], top_k of h) blocks.
+ *   mass_gamma       cumulative-mass budget, the rule of the FlexPrefill family that Sec. 4.1.1 lists
+ *                    among the framework's dynamic algorithms (no formula in the paper).  0 = off.
+ *                    gamma in (0, 1] (larger values count as 1): query block i takes, in ranking
+ *                    order, the fewest candidates for which the selected blocks (static ones
+ *                    included) hold at least the fraction gamma of the row's block-level softmax mass,
+ *                    and never more than its count budget (top_k_blocks, schedule, per-head top_k),
+ *                    which keeps fixing the row capacity.  So that the number of blocks does not
+ *                    hinge on the order of a floating-point sum, the mass is defined in integers:
+ *                    with x_j the ranking scores of the causal blocks j <= i and m their maximum,
+ *                    W_j = floor(2^19 w_j + 1/2), w_j = 2^((x_j - m) log2 e) evaluated in fp32 as
+ *                    2^n p(f), n the integer nearest to the exponent, f the rest, p the degree-6
+ *                    Taylor polynomial of e^(f ln 2) in Horner form (NaN, -inf and exponents below
+ *                    -40 weigh 0); target = ceil(Gamma sum_j W_j / 65536), Gamma = floor(65536 gamma
+ *                    + 1/2); candidates are taken until mass(static) + mass(taken) >= target.
+ *                    A negative or NaN gamma returns SPA_ERR_BAD_PATTERN.
  * The _tpd and _stem calls above are these calls with the corresponding fields set. */
 typedef struct spa_select_opts {
     const int32_t *top_k_per_block;
     const void *v;
     const int32_t *head_pattern;
+    float mass_gamma;
 } spa_select_opts;
 
 int sparse_prefill_select_ex(const spa_params *p, const void *q, const void *k,

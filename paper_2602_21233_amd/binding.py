@@ -38,7 +38,8 @@ class SpaParams(ctypes.Structure):
 
 
 class SpaSelectOpts(ctypes.Structure):
-    _fields_ = [("top_k_per_block", ctypes.c_void_p), ("v", ctypes.c_void_p), ("head_pattern", ctypes.c_void_p)]
+    _fields_ = [("top_k_per_block", ctypes.c_void_p), ("v", ctypes.c_void_p), ("head_pattern", ctypes.c_void_p),
+                ("mass_gamma", ctypes.c_float)]
 
 
 def library_path() -> str:
@@ -144,8 +145,9 @@ def _head_pattern(hp, n_q_heads):
     return hp
 
 
-def _opts(top_k_per_block=None, v=None, head_pattern=None) -> SpaSelectOpts:
+def _opts(top_k_per_block=None, v=None, head_pattern=None, mass_gamma=None) -> SpaSelectOpts:
     o = SpaSelectOpts()
+    o.mass_gamma = 0.0 if mass_gamma is None else float(mass_gamma)
     o.top_k_per_block = None if top_k_per_block is None else top_k_per_block.data_ptr()
     o.v = None if v is None else v.data_ptr()
     o.head_pattern = None if head_pattern is None else head_pattern.data_ptr()
@@ -193,10 +195,11 @@ def value_norms(v, block_size):
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
            return_scores=False, workspace=None, top_k_per_block=None, v=None, stride_blocks=0,
-           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, group_shared=False):
+           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, group_shared=False, mass_gamma=None):
     """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
     tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
-    without a schedule).  Returns (block_idx, block_cnt[, scores])."""
+    without a schedule); sparse_prefill_select_ex with head_pattern or mass_gamma (cumulative-mass
+    budget).  Returns (block_idx, block_cnt[, scores])."""
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
@@ -210,9 +213,9 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     NBk = -(-k.shape[2] // block_size)               # key blocks (more than NB with a KV prefix)
     sp = torch.empty((B, Hq, NB, NBk), dtype=torch.float32, device=q.device) if return_scores else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if head_pattern is not None:
+    if head_pattern is not None or mass_gamma is not None:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
-        o = _opts(kr, v, _head_pattern(head_pattern, Hq))
+        o = _opts(kr, v, None if head_pattern is None else _head_pattern(head_pattern, Hq), mass_gamma)
         _check(load_library().sparse_prefill_select_ex(ctypes.byref(p), _ptr(q), _ptr(k), ctypes.byref(o), _ptr(idx),
                                                        _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
     elif v is not None:
@@ -232,8 +235,9 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
 
 
 def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_per_block=None,
-                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0):
-    """sparse_prefill_topk_from_scores (…_tpd with a schedule) on [B,Hq,NB,NB] fp32 device scores."""
+                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, mass_gamma=None):
+    """sparse_prefill_topk_from_scores (…_tpd with a schedule, …_ex with head_pattern or mass_gamma) on
+    [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
         raise TypeError("expected contiguous fp32 scores on the GPU")
     B, Hq, NB, NBk = scores.shape                    # NBk > NB: a KV prefix of NBk - NB blocks
@@ -245,9 +249,9 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
     T = row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
-    if head_pattern is not None:
+    if head_pattern is not None or mass_gamma is not None:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, scores.device)
-        o = _opts(kr, None, _head_pattern(head_pattern, Hq))
+        o = _opts(kr, None, None if head_pattern is None else _head_pattern(head_pattern, Hq), mass_gamma)
         _check(load_library().sparse_prefill_topk_from_scores_ex(ctypes.byref(p), _ptr(scores), ctypes.byref(o),
                                                                  _ptr(idx), _ptr(cnt), _stream(scores)))
     elif top_k_per_block is None:
@@ -294,7 +298,7 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
           return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
           output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0,
-          group_shared=False):
+          group_shared=False, mass_gamma=None):
     """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
     current stream."""
     _dev_bf16(q, k, v)
@@ -309,9 +313,10 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     cnt = torch.empty((B, Hl, NB), dtype=torch.int32, device=q.device) if return_lists else None
     lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
     ws = _workspace(p, q.device) if workspace is None else workspace
-    if head_pattern is not None:
+    if head_pattern is not None or mass_gamma is not None:
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
-        o = _opts(kr, v if output_aware else None, _head_pattern(head_pattern, Hl))
+        o = _opts(kr, v if output_aware else None, None if head_pattern is None else _head_pattern(head_pattern, Hl),
+                  mass_gamma)
         _check(load_library().sparse_prefill_fused_ex(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), ctypes.byref(o),
                                                       _ptr(out), _ptr(lse), _ptr(idx), _ptr(cnt), _ptr(ws),
                                                       ws.numel(), _stream(q)))

@@ -63,12 +63,21 @@ Workspace carve(const Dims& d) {
 
 int launch_code(hipError_t e) { return e == hipSuccess ? SPA_OK : SPA_ERR_LAUNCH; }
 
+// mass_gamma: 0 = no cumulative-mass budget; (0, 1] (larger: 1) = the budget; negative or NaN: error
+int set_mass_budget(Dims& d, float mass_gamma) {
+    if (!(mass_gamma >= 0.0f)) return SPA_ERR_BAD_PATTERN;
+    if (mass_gamma == 0.0f) return SPA_OK;
+    const double g = mass_gamma > 1.0f ? 1.0 : (double)mass_gamma;
+    d.gamma_q16 = (int)floor(g * 65536.0 + 0.5);
+    return SPA_OK;
+}
+
 }  // namespace
 
 namespace {
 // v_or_null: values for the output-aware ranking score, or nullptr for the plain pooled score
 int select_impl(const spa_params* p, const void* q, const void* k, const void* v_or_null, const int32_t* k_rows,
-                const int32_t* head_pattern, int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
+                const int32_t* head_pattern, float mass_gamma, int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
                 void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
@@ -78,6 +87,7 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
     if (v_or_null && (rc = check_tensor(v_or_null, p->v_stride, p->head_dim))) return rc;
     if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
     Dims d = resolved(p);
+    if ((rc = set_mass_budget(d, mass_gamma))) return rc;
     Workspace w = carve(d);
     if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
     float* qp = (float*)((char*)ws + w.qp_off);
@@ -103,19 +113,20 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
 }
 
 int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_rows,
-              const int32_t* head_pattern, int32_t* block_idx,
+              const int32_t* head_pattern, float mass_gamma, int32_t* block_idx,
               int32_t* block_cnt, void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
     if (!pooled_scores || !block_idx || !block_cnt) return SPA_ERR_NULLPTR;
     Dims d = resolved(p);
+    if ((rc = set_mass_budget(d, mass_gamma))) return rc;
     if (d.shared) { d.Hq = d.Hkv; d.G = 1; }
     return launch_code(launch_topk_from_scores(d, pooled_scores, k_rows, head_pattern, block_idx, block_cnt,
                                                (hipStream_t)hip_stream));
 }
 
 int fused_impl(const spa_params* p, const void* q, const void* k, const void* v, const int32_t* k_rows,
-               const int32_t* head_pattern, bool output_aware, void* out, float* lse_or_null, int32_t* block_idx_or_null,
+               const int32_t* head_pattern, float mass_gamma, bool output_aware, void* out, float* lse_or_null, int32_t* block_idx_or_null,
                int32_t* block_cnt_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc = check_shape(p);
     if (rc) return rc;
@@ -129,7 +140,7 @@ int fused_impl(const spa_params* p, const void* q, const void* k, const void* v,
     if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
     int32_t* idx = block_idx_or_null ? block_idx_or_null : (int32_t*)((char*)ws + w.idx_off);
     int32_t* cnt = block_cnt_or_null ? block_cnt_or_null : (int32_t*)((char*)ws + w.cnt_off);
-    rc = select_impl(p, q, k, output_aware ? v : nullptr, k_rows, head_pattern, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
+    rc = select_impl(p, q, k, output_aware ? v : nullptr, k_rows, head_pattern, mass_gamma, idx, cnt, nullptr, ws, ws_bytes, hip_stream);
     if (rc) return rc;
     return sparse_prefill_attn(p, q, k, v, idx, cnt, out, lse_or_null, ws, ws_bytes, hip_stream);
 }
@@ -184,7 +195,7 @@ int sparse_prefill_pool(const spa_params* p, const void* q, const void* k, float
 int sparse_prefill_select(const spa_params* p, const void* q, const void* k, int32_t* block_idx,
                           int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
                           void* hip_stream) {
-    return select_impl(p, q, k, nullptr, nullptr, nullptr, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
+    return select_impl(p, q, k, nullptr, nullptr, nullptr, 0.0f, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
                        hip_stream);
 }
 
@@ -192,20 +203,20 @@ int sparse_prefill_select_tpd(const spa_params* p, const void* q, const void* k,
                               int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws,
                               size_t ws_bytes, void* hip_stream) {
     if (!top_k_per_block) return SPA_ERR_NULLPTR;
-    return select_impl(p, q, k, nullptr, top_k_per_block, nullptr, block_idx, block_cnt, pooled_scores_or_null, ws,
+    return select_impl(p, q, k, nullptr, top_k_per_block, nullptr, 0.0f, block_idx, block_cnt, pooled_scores_or_null, ws,
                        ws_bytes, hip_stream);
 }
 
 int sparse_prefill_topk_from_scores(const spa_params* p, const float* pooled_scores, int32_t* block_idx,
                                     int32_t* block_cnt, void* hip_stream) {
-    return topk_impl(p, pooled_scores, nullptr, nullptr, block_idx, block_cnt, hip_stream);
+    return topk_impl(p, pooled_scores, nullptr, nullptr, 0.0f, block_idx, block_cnt, hip_stream);
 }
 
 int sparse_prefill_topk_from_scores_tpd(const spa_params* p, const float* pooled_scores,
                                         const int32_t* top_k_per_block, int32_t* block_idx, int32_t* block_cnt,
                                         void* hip_stream) {
     if (!top_k_per_block) return SPA_ERR_NULLPTR;
-    return topk_impl(p, pooled_scores, top_k_per_block, nullptr, block_idx, block_cnt, hip_stream);
+    return topk_impl(p, pooled_scores, top_k_per_block, nullptr, 0.0f, block_idx, block_cnt, hip_stream);
 }
 
 int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const void* v,
@@ -235,7 +246,7 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
                          float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null,
                          void* ws, size_t ws_bytes, void* hip_stream) {
-    return fused_impl(p, q, k, v, nullptr, nullptr, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws,
+    return fused_impl(p, q, k, v, nullptr, nullptr, 0.0f, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null, ws,
                       ws_bytes, hip_stream);
 }
 
@@ -244,7 +255,7 @@ int sparse_prefill_fused_tpd(const spa_params* p, const void* q, const void* k, 
                              int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws, size_t ws_bytes,
                              void* hip_stream) {
     if (!top_k_per_block) return SPA_ERR_NULLPTR;
-    return fused_impl(p, q, k, v, top_k_per_block, nullptr, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null,
+    return fused_impl(p, q, k, v, top_k_per_block, nullptr, 0.0f, false, out, lse_or_null, block_idx_or_null, block_cnt_or_null,
                       ws, ws_bytes, hip_stream);
 }
 
@@ -261,7 +272,7 @@ int sparse_prefill_select_stem(const spa_params* p, const void* q, const void* k
                                const int32_t* top_k_per_block_or_null, int32_t* block_idx, int32_t* block_cnt,
                                float* ranking_scores_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
     if (!v) return SPA_ERR_NULLPTR;
-    return select_impl(p, q, k, v, top_k_per_block_or_null, nullptr, block_idx, block_cnt, ranking_scores_or_null, ws,
+    return select_impl(p, q, k, v, top_k_per_block_or_null, nullptr, 0.0f, block_idx, block_cnt, ranking_scores_or_null, ws,
                        ws_bytes, hip_stream);
 }
 
@@ -269,32 +280,32 @@ int sparse_prefill_fused_stem(const spa_params* p, const void* q, const void* k,
                               const int32_t* top_k_per_block_or_null, void* out, float* lse_or_null,
                               int32_t* block_idx_or_null, int32_t* block_cnt_or_null, void* ws, size_t ws_bytes,
                               void* hip_stream) {
-    return fused_impl(p, q, k, v, top_k_per_block_or_null, nullptr, true, out, lse_or_null, block_idx_or_null,
+    return fused_impl(p, q, k, v, top_k_per_block_or_null, nullptr, 0.0f, true, out, lse_or_null, block_idx_or_null,
                       block_cnt_or_null, ws, ws_bytes, hip_stream);
 }
 
 int sparse_prefill_select_ex(const spa_params* p, const void* q, const void* k, const spa_select_opts* opts,
                              int32_t* block_idx, int32_t* block_cnt, float* ranking_scores_or_null, void* ws,
                              size_t ws_bytes, void* hip_stream) {
-    const spa_select_opts none = {nullptr, nullptr, nullptr};
+    const spa_select_opts none = {nullptr, nullptr, nullptr, 0.0f};
     const spa_select_opts* o = opts ? opts : &none;
-    return select_impl(p, q, k, o->v, o->top_k_per_block, o->head_pattern, block_idx, block_cnt,
+    return select_impl(p, q, k, o->v, o->top_k_per_block, o->head_pattern, o->mass_gamma, block_idx, block_cnt,
                        ranking_scores_or_null, ws, ws_bytes, hip_stream);
 }
 
 int sparse_prefill_topk_from_scores_ex(const spa_params* p, const float* scores, const spa_select_opts* opts,
                                        int32_t* block_idx, int32_t* block_cnt, void* hip_stream) {
-    const spa_select_opts none = {nullptr, nullptr, nullptr};
+    const spa_select_opts none = {nullptr, nullptr, nullptr, 0.0f};
     const spa_select_opts* o = opts ? opts : &none;
-    return topk_impl(p, scores, o->top_k_per_block, o->head_pattern, block_idx, block_cnt, hip_stream);
+    return topk_impl(p, scores, o->top_k_per_block, o->head_pattern, o->mass_gamma, block_idx, block_cnt, hip_stream);
 }
 
 int sparse_prefill_fused_ex(const spa_params* p, const void* q, const void* k, const void* v,
                             const spa_select_opts* opts, void* out, float* lse_or_null, int32_t* block_idx_or_null,
                             int32_t* block_cnt_or_null, void* ws, size_t ws_bytes, void* hip_stream) {
-    const spa_select_opts none = {nullptr, nullptr, nullptr};
+    const spa_select_opts none = {nullptr, nullptr, nullptr, 0.0f};
     const spa_select_opts* o = opts ? opts : &none;
-    return fused_impl(p, q, k, v, o->top_k_per_block, o->head_pattern, o->v != nullptr, out, lse_or_null,
+    return fused_impl(p, q, k, v, o->top_k_per_block, o->head_pattern, o->mass_gamma, o->v != nullptr, out, lse_or_null,
                       block_idx_or_null, block_cnt_or_null, ws, ws_bytes, hip_stream);
 }
 

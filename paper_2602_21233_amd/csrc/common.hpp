@@ -17,6 +17,7 @@ struct Dims {
     int shared;                   // 1: block lists are per KV head (group-shared selection)
     int stride, n_dense, reach;   // strided static columns, dense bottom strip, reach of the strided columns (0 = off)
     float scale;
+    int gamma_q16;                // cumulative-mass budget in 16-bit fixed point, -1 = none
 };
 
 inline Dims dims_of(const spa_params& p) {
@@ -32,6 +33,7 @@ inline Dims dims_of(const spa_params& p) {
     int64_t t = (int64_t)d.ns + d.nl + d.k + (d.stride > 0 ? far / d.stride : 0);
     d.T = (int)((t < d.NBk && d.n_dense <= 0) ? t : d.NBk);
     d.scale = p.softmax_scale;
+    d.gamma_q16 = -1;
     return d;
 }
 

@@ -151,12 +151,16 @@ __device__ __forceinline__ void head_config(const int32_t* __restrict__ head_pat
     k = c < 0 ? 0 : (c > k ? k : c);
 }
 
+// cumulative-mass budget of a row, defined further down
+template <bool EXT, typename ScoreFn>
+__device__ int mass_budget_row(ScoreFn score, int i, const Pattern& pt, uint32_t gamma_q16, uint32_t* hist, int lane);
+
 template <bool EXT>
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
     const float* __restrict__ scores, int64_t n_rows, int NB /* query blocks */, int NBk, int off, Pattern pt, int k,
     const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern, int Hq, int T,
-    int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
-    extern __shared__ uint32_t lds_keys[];
+    int32_t* __restrict__ idx, int32_t* __restrict__ cnt, int gamma_q16 /* -1: no mass budget */) {
+    extern __shared__ uint32_t lds_keys[];       // [kWaves][padded NBk] keys, then 256 counters per wave (mass budget)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
     if (row >= n_rows) return;                               // whole wave leaves together
@@ -174,7 +178,13 @@ __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
         keys[j] = key;
     }
     // each wave reads back only its own slice; LDS ops of one wave are ordered
-    select_row<EXT>(keys, i, pt, row_budget(k_rows, iq, k), T, idx + row * T, cnt + row);
+    int k_i = row_budget(k_rows, iq, k);
+    if (gamma_q16 >= 0) {
+        uint32_t* hist = lds_keys + kWaves * padded + 256 * wave;
+        const int k_m = mass_budget_row<EXT>([&](int j) { return srow[j]; }, i, pt, (uint32_t)gamma_q16, hist, lane);
+        k_i = k_m < k_i ? k_m : k_i;
+    }
+    select_row<EXT>(keys, i, pt, k_i, T, idx + row * T, cnt + row);
 }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -310,6 +320,115 @@ __device__ __forceinline__ void find_threshold_hist(const uint32_t (&key)[MAXC],
     need_eq = want;
 }
 
+// ---- cumulative-mass budget (the rule of the FlexPrefill family, named among the dynamic algorithms
+// in Sec. 4.1.1 / "Other Sparse Attention Strategies" of Sec. 4.1.2; no formula in the paper) ----------
+// A row takes, in ranking order, the fewest candidates for which the selected blocks (static ones
+// included) hold the fraction gamma of the row's block-level softmax mass.  The mass is defined in
+// integers so that the number of blocks does not depend on the order of a floating-point sum:
+//   W_j = mass_weight(x_j, m) in [0, 2^19], m = the row's largest score that is not NaN,
+//   target = ceil(Gamma * sum_j W_j / 65536), Gamma = gamma in 16-bit fixed point.
+// mass_weight ~ 2^19 exp(x - m): every step is one IEEE fp32 operation, written with the
+// never-contracted intrinsics, so that a CPU gets the same bits from the same sequence.
+__device__ __forceinline__ uint32_t mass_weight(float x, float m) {
+    if (x != x || m != m) return 0u;
+    if (x == m) return 1u << 19;                          // also m = +inf
+    if (__builtin_isinf(x) || __builtin_isinf(m)) return 0u;
+    const float t = __fmul_rn(__fsub_rn(x, m), 1.44269504088896340736f);
+    if (!(t >= -40.0f)) return 0u;
+    const float n = __builtin_rintf(t);                   // ties to even
+    const float f = __fsub_rn(t, n);
+    float p = 1.5403530393381609954e-4f;                  // Taylor coefficients of e^(f ln 2), degree 6 .. 0
+    p = __fmaf_rn(p, f, 1.3333558146428443423e-3f);
+    p = __fmaf_rn(p, f, 9.6181291076284771619e-3f);
+    p = __fmaf_rn(p, f, 5.5504108664821579953e-2f);
+    p = __fmaf_rn(p, f, 2.4022650695910071233e-1f);
+    p = __fmaf_rn(p, f, 6.9314718055994530942e-1f);
+    p = __fmaf_rn(p, f, 1.0f);
+    const float w = ldexpf(p, (int)n);
+    return (uint32_t)__fadd_rn(__fmul_rn(w, 524288.0f), 0.5f);
+}
+
+// the score a rank key came from (keys >= 2; -0 has become +0)
+__device__ __forceinline__ float score_of_key(uint32_t key) {
+    uint32_t u = key - 1u;
+    u = (u & 0x80000000u) ? (u ^ 0x80000000u) : ~u;
+    return __uint_as_float(u);
+}
+
+// Number of candidates the mass budget lets the query block at block position i take (before the
+// count budgets cap it).  One full wavefront; score(j) returns the ranking score of key block j <= i.
+// hist: 256 LDS counters of this wavefront.  gamma_q16 = Gamma.
+template <bool EXT, typename ScoreFn>
+__device__ int mass_budget_row(ScoreFn score, int i, const Pattern& pt, uint32_t gamma_q16, uint32_t* hist, int lane) {
+    const int chunks = (i + 64) >> 6;
+    float mloc = -INFINITY;
+    for (int c = 0; c < chunks; ++c) {
+        const int j = (c << 6) + lane;
+        const float x = j <= i ? score(j) : -INFINITY;
+        if (x == x && x > mloc) mloc = x;
+    }
+    // wave maximum of floats through the order-preserving keys (mloc is never NaN)
+    const uint32_t mk = wave_max_u32(rank_key(mloc));
+    const float m = mk >= 2u ? score_of_key(mk) : -INFINITY;
+    int z_l = 0, ms_l = 0;                                 // lane sums; a row's total is < 2^31
+    for (int c = 0; c < chunks; ++c) {
+        const int j = (c << 6) + lane;
+        if (j <= i) {
+            const int w = (int)mass_weight(score(j), m);
+            z_l += w;
+            if (static_block<EXT>(pt, i, j)) ms_l += w;
+        }
+    }
+    const uint32_t Z = (uint32_t)wave_sum(z_l), Ms = (uint32_t)wave_sum(ms_l);
+    const uint32_t target = (uint32_t)(((uint64_t)gamma_q16 * Z + 65535ull) >> 16);
+    if (Ms >= target) return 0;
+    uint32_t need = target - Ms;                           // mass still wanted from the candidates, >= 1
+    // weighted radix selection: the key at which the mass of the better-ranked candidates reaches `need`
+    uint32_t prefix = 0u;
+#pragma nounroll
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        for (int c = 0; c < chunks; ++c) {
+            const int j = (c << 6) + lane;
+            if (j <= i && !static_block<EXT>(pt, i, j)) {
+                const float x = score(j);
+                const uint32_t kv = rank_key(x);
+                if ((((kv ^ prefix) >> shift) >> 8) == 0u) {
+                    const uint32_t w = mass_weight(x, m);
+                    if (w != 0u) atomicAdd(&hist[(kv >> shift) & 255u], w);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint4 h = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // .w = bin 255-4l ... .x = bin 252-4l
+        const int own = (int)(h.x + h.y + h.z + h.w);
+        const int incl = wave_inclusive_scan(own);
+        const int Ln = __ffsll((unsigned long long)__ballot((uint32_t)incl >= need)) - 1;   // exists: candidates' mass >= need
+        const uint32_t before = (uint32_t)__builtin_amdgcn_readlane(incl - own, Ln);
+        const uint32_t b3 = (uint32_t)__builtin_amdgcn_readlane((int)h.w, Ln), b2 = (uint32_t)__builtin_amdgcn_readlane((int)h.z, Ln);
+        const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane((int)h.y, Ln);
+        const uint32_t rem = need - before;
+        uint32_t digit, above;
+        if (rem <= b3) { digit = 255 - 4 * Ln; above = 0; }
+        else if (rem <= b3 + b2) { digit = 254 - 4 * Ln; above = b3; }
+        else if (rem <= b3 + b2 + b1) { digit = 253 - 4 * Ln; above = b3 + b2; }
+        else { digit = 252 - 4 * Ln; above = b3 + b2 + b1; }
+        need = rem - above;                                // mass wanted from the chosen bin, >= 1
+        prefix |= digit << shift;
+    }
+    // prefix = the key tau of the last block taken; all of the better keys, plus as many copies of tau
+    // (equal keys have equal weights) as it takes to cover what is left
+    int n_above = 0;
+    for (int c = 0; c < chunks; ++c) {
+        const int j = (c << 6) + lane;
+        const bool gt = j <= i && !static_block<EXT>(pt, i, j) && rank_key(score(j)) > prefix;
+        n_above += __popcll(__ballot(gt));
+    }
+    const uint32_t w_tau = mass_weight(score_of_key(prefix), m);
+    return n_above + (int)((need + w_tau - 1u) / w_tau);
+}
+
 // Everything the score + top-k step of one workgroup needs besides its rows.
 struct ScoreArgs {
     const float* qp;              // pooled Q [B*Hq, NB, D] fp32
@@ -325,6 +444,7 @@ struct ScoreArgs {
     int32_t* idx;
     int32_t* cnt;
     float* scores_out;
+    uint32_t gamma_q16;           // cumulative-mass budget in 16-bit fixed point (MASS kernels only)
 };
 
 // Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
@@ -333,7 +453,7 @@ struct ScoreArgs {
 // The split pooled queries (MFMA A operands) are staged in LDS, in the space of the phase-2 counters,
 // instead of being held in 8 * D / 16 registers per lane: the kernel stays within 128 registers.
 // Needs R * D * 4 bytes <= the counters' 8 KB.
-template <int D, int R, int MAXC, bool EXT>
+template <int D, int R, int MAXC, bool EXT, bool MASS>
 __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
@@ -479,12 +599,16 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
             int overlap = n_sink - first_local; if (overlap < 0) overlap = 0;
             n_cand = n - (n_sink + n_local - overlap);
         }
-        const int k_i = row_budget(k_rows, iq, k);
+        int k_i = row_budget(k_rows, iq, k);
+        uint32_t* hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
+        if constexpr (MASS) {                             // the mass budget on top of the count budgets
+            const int k_m = mass_budget_row<EXT>([&](int j) { return srow[j]; }, i, pt, a.gamma_q16, hist, lane);
+            k_i = k_m < k_i ? k_m : k_i;
+        }
         const int kk = k_i < n_cand ? k_i : n_cand;
         uint32_t thr;
         int need_eq;
         const int nc4 = 4 * chunks;
-        uint32_t* hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
         if (nc4 <= MAXC) find_threshold_hist<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
         else if (nc4 <= 2 * MAXC) find_threshold_hist<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, hist, lane, thr, need_eq);
         else if (nc4 <= 3 * MAXC) find_threshold_hist<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
@@ -515,7 +639,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
 
 // Two workgroups per CU (4 wavefronts per SIMD): at most 128 registers, which is why the query
 // operands are staged in LDS.
-template <int D, int R, int MAXC, bool EXT>
+template <int D, int R, int MAXC, bool EXT, bool MASS>
 __global__ __launch_bounds__(kMfmaWaves * 64, 4) void score_topk_mfma_kernel(ScoreArgs a, int n_tiles) {
     extern __shared__ __attribute__((aligned(128))) float S[];   // [R][LD] scores of this workgroup's rows, then 256 counters per wave
     // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
@@ -524,7 +648,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64, 4) void score_topk_mfma_kernel(Sco
     int wg = blockIdx.x;
     if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
     const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
-    score_topk_rows<D, R, MAXC, EXT>(a, wg / n_tiles, tile * R, S);
+    score_topk_rows<D, R, MAXC, EXT, MASS>(a, wg / n_tiles, tile * R, S);
 }
 
 // Dynamic LDS above the default cap has to be requested per kernel.
@@ -536,7 +660,7 @@ hipError_t allow_lds(const void* kernel, size_t bytes) {
 ScoreArgs score_args(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern,
                      const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null) {
     return ScoreArgs{qp, kp, d.Hq, d.G, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale,
-                     idx, cnt, scores_or_null};
+                     idx, cnt, scores_or_null, d.gamma_q16 >= 0 ? (uint32_t)d.gamma_q16 : 0u};
 }
 
 size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) * sizeof(uint32_t); }
@@ -548,35 +672,41 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     int64_t n_rows = (int64_t)d.B * d.Hq * d.NB;
     unsigned grid = (unsigned)((n_rows + kWaves - 1) / kWaves);
     const void* fn = extended(d) ? (const void*)topk_from_scores_kernel<true> : (const void*)topk_from_scores_kernel<false>;
-    hipError_t e = allow_lds(fn, keys_lds_bytes(d.NBk));
+    const size_t lds = keys_lds_bytes(d.NBk) + (d.gamma_q16 >= 0 ? kWaves * 256 * sizeof(uint32_t) : 0);
+    hipError_t e = allow_lds(fn, lds);
     if (e != hipSuccess) return e;
     if (extended(d))
-        hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NBk), st,
-                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
+        hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), lds, st,
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16);
     else
-        hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), keys_lds_bytes(d.NBk), st,
-                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt);
+        hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), lds, st,
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16);
     return hipGetLastError();
 }
 
-template <int D, int R, int MAXC, bool EXT>
+template <int D, int R, int MAXC, bool EXT, bool MASS>
 hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
     constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float) + kMfmaWaves * 256 * sizeof(uint32_t);
-    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT>, lds);
+    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT, MASS>, lds);
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     const ScoreArgs a = score_args(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null);
-    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT>), grid, dim3(kMfmaWaves * 64), lds, st, a, n_tiles);
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT, MASS>), grid, dim3(kMfmaWaves * 64), lds, st, a, n_tiles);
     return hipGetLastError();
 }
 
 template <int D, int R, int MAXC>
 hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    if (extended(d)) return launch_mfma_e<D, R, MAXC, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma_e<D, R, MAXC, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    const bool mass = d.gamma_q16 >= 0;
+    if (extended(d)) {
+        if (mass) return launch_mfma_e<D, R, MAXC, true, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+        return launch_mfma_e<D, R, MAXC, true, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    }
+    if (mass) return launch_mfma_e<D, R, MAXC, false, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    return launch_mfma_e<D, R, MAXC, false, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 
 template <int D>

@@ -120,6 +120,15 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
     assert lib.sparse_prefill_select_ex(ctypes.byref(p), fake, fake, ctypes.byref(o), fake, fake, None, fake,
                                         1 << 30, None) == -4
     assert lib.sparse_prefill_topk_from_scores_ex(ctypes.byref(p), None, None, fake, fake, None) == -1
+    # cumulative-mass budget: negative or NaN is an error, found before any launch
+    for bad_gamma in (-0.5, float("nan")):
+        o2 = binding.SpaSelectOpts()
+        o2.mass_gamma = bad_gamma
+        assert lib.sparse_prefill_select_ex(ctypes.byref(p), fake, fake, ctypes.byref(o2), fake, fake, None, fake,
+                                            1 << 30, None) == -3
+        assert lib.sparse_prefill_topk_from_scores_ex(ctypes.byref(p), fake, ctypes.byref(o2), fake, fake, None) == -3
+        assert lib.sparse_prefill_fused_ex(ctypes.byref(p), fake, fake, fake, ctypes.byref(o2), fake, None, fake, fake,
+                                           fake, 1 << 30, None) == -3
     assert lib.sparse_prefill_fused_ex(ctypes.byref(p), fake, fake, fake, None, fake, None, fake, None, fake,
                                        1 << 30, None) == -1
     bad = _params()

@@ -392,6 +392,59 @@ def test_select_with_tied_scores(spa, oracle, NB, D, Bs, ns, nl, k, n_distinct):
     assert torch.equal(t_idx, idx) and torch.equal(t_cnt, cnt)
 
 
+# ------------------------------------------------ cumulative-mass budget
+@pytest.mark.parametrize("NB", [1, 19, 65, 300, 1100])
+@pytest.mark.parametrize("ns,nl,k,gamma", [(1, 2, 40, 0.9), (0, 1, 400, 0.5), (2, 3, 9, 0.99), (1, 4, 64, 0.75),
+                                           (1, 2, 2000, 1.0)])
+def test_topk_mass_budget_bit_exact(spa, oracle, NB, ns, nl, k, gamma):
+    g = torch.Generator().manual_seed(NB * 7 + k)
+    sp = torch.randn((1, 3, NB, NB), generator=g) * 2.0
+    idx, cnt = spa.topk_from_scores(sp.cuda(), ns, nl, k, mass_gamma=gamma)
+    o_idx, o_cnt = oracle.topk(sp, ns, nl, k, gamma=gamma)
+    assert torch.equal(cnt.cpu(), o_cnt) and torch.equal(idx.cpu(), o_idx)
+
+
+def test_topk_mass_budget_ties_special_values_and_caps(spa, oracle):
+    g = torch.Generator().manual_seed(77)
+    NB = 200
+    sp = torch.randint(-3, 4, (1, 4, NB, NB), generator=g).float() * 0.5     # few distinct values: ties at every cut
+    sp[0, 1, :, 5::7] = float("nan")
+    sp[0, 1, :, 3::11] = float("-inf")
+    sp[0, 2, 100:, 40] = float("inf")
+    sp[0, 3] = -0.0
+    sp[0, 3, :, ::2] = 0.0
+    sched = torch.randint(0, 30, (NB,), generator=g).to(torch.int32)
+    hp = torch.tensor([[1, 2, 30], [0, 1, 11], [2, 3, 0], [1, 1, 25]], dtype=torch.int32)
+    for gamma in (0.3, 0.8, 0.999):
+        idx, cnt = spa.topk_from_scores(sp.cuda(), 2, 3, 30, mass_gamma=gamma)
+        o_idx, o_cnt = oracle.topk(sp, 2, 3, 30, gamma=gamma)
+        assert torch.equal(cnt.cpu(), o_cnt) and torch.equal(idx.cpu(), o_idx), gamma
+        idx, cnt = spa.topk_from_scores(sp.cuda(), 2, 3, 30, top_k_per_block=sched.cuda(), head_pattern=hp.cuda(),
+                                        mass_gamma=gamma, stride_blocks=9)
+        o_idx, o_cnt = oracle.topk(sp, 2, 3, 30, k_per_row=sched, head_pattern=hp, gamma=gamma, stride=9)
+        assert torch.equal(cnt.cpu(), o_cnt) and torch.equal(idx.cpu(), o_idx), gamma
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,NB,D,Bs,ns,nl,k,gamma", [
+    (2, 4, 2, 21, 128, 64, 1, 4, 12, 0.9), (1, 6, 2, 70, 128, 128, 2, 3, 40, 0.8), (1, 2, 1, 300, 64, 64, 1, 2, 64, 0.95),
+    (1, 2, 2, 1100, 128, 64, 1, 4, 100, 0.7), (1, 1, 1, 2100, 64, 64, 1, 2, 64, 0.9)])
+def test_select_and_fused_mass_budget(spa, oracle, B, Hq, Hkv, NB, D, Bs, ns, nl, k, gamma):
+    """The select kernel's own scores, then the oracle's rule on them: identical lists; the count is
+    below the count-only call where the mass is concentrated; the fused call attends to those lists."""
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 31)
+    kk = (kk.float() * 3.0).to(torch.bfloat16)                       # sharper rows: the mass budget bites
+    idx, cnt, sp = spa.select(q.cuda(), kk.cuda(), Bs, ns, nl, k, return_scores=True, mass_gamma=gamma)
+    g_idx, g_cnt = oracle.topk(sp.cpu(), ns, nl, k, gamma=gamma)
+    assert torch.equal(idx.cpu(), g_idx) and torch.equal(cnt.cpu(), g_cnt)
+    idx_c, cnt_c = spa.select(q.cuda(), kk.cuda(), Bs, ns, nl, k)
+    assert (cnt <= cnt_c).all() and (cnt < cnt_c).any()
+    if NB <= 70:
+        out, f_idx, f_cnt = spa.fused(q.cuda(), kk.cuda(), v.cuda(), Bs, ns, nl, k, return_lists=True, mass_gamma=gamma)
+        assert torch.equal(f_idx, idx) and torch.equal(f_cnt, cnt)
+        want, _ = oracle.attn(q, kk, v, g_idx, g_cnt, Bs)
+        _assert_attn_close(out, want, "fused with a mass budget")
+
+
 # ------------------------------------------------------------- attention
 def _oracle_lists(oracle, q, k, Bs, ns, nl, topk):
     idx, cnt, *_ = oracle.select(q, k, Bs, ns, nl, topk)
