@@ -216,3 +216,53 @@ def attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, c
                                block_size, T, scale, idx.data_ptr(), cnt.data_ptr(), rows_ptr, n,
                                out.data_ptr(), lse.data_ptr()), "attn")
     return out, lse
+
+
+# ---- ragged batches: every entry is a batch-1 problem of its own length ---------------------------
+def select_ragged(q: torch.Tensor, k: torch.Tensor, seq_lens, block_size: int, ns: int, nl: int, topk_blocks: int,
+                  **kw):
+    """Entry b has seq_lens[b] query tokens and P + seq_lens[b] key tokens (P = k.shape[2] - q.shape[2],
+    a KV prefix common to all entries); q, k keep their padded shapes.  Each entry is selected by a
+    batch-1 call of select() on its own slice.  Returns padded (idx [B,H,NB,T], cnt [B,H,NB]) with
+    T of the padded call; rows past an entry's last block have count 0 and -1 entries."""
+    B, Hq, S, _ = q.shape
+    P = k.shape[2] - S
+    NB = -(-S // block_size)
+    NBk = -(-(P + S) // block_size)
+    Hl = k.shape[1] if kw.get("group_shared") else Hq
+    T = row_capacity(NBk, ns, nl, topk_blocks, kw.get("stride", 0), kw.get("n_dense", 0), kw.get("reach", 0))
+    idx = torch.full((B, Hl, NB, T), -1, dtype=torch.int32)
+    cnt = torch.zeros((B, Hl, NB), dtype=torch.int32)
+    for b in range(B):
+        n = int(seq_lens[b])
+        if n <= 0:
+            continue
+        kw_b = dict(kw)
+        if kw_b.get("v") is not None:
+            kw_b["v"] = kw_b["v"][b:b + 1, :, :P + n]
+        if kw_b.get("k_per_row") is not None:
+            kw_b["k_per_row"] = kw_b["k_per_row"][:-(-n // block_size)]
+        i_b, c_b, *_ = select(q[b:b + 1, :, :n], k[b:b + 1, :, :P + n], block_size, ns, nl, topk_blocks, **kw_b)
+        idx[b, :, :i_b.shape[2], :i_b.shape[3]] = i_b[0]
+        cnt[b, :, :c_b.shape[2]] = c_b[0]
+    return idx, cnt
+
+
+def attn_ragged(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, idx: torch.Tensor, cnt: torch.Tensor, seq_lens,
+                block_size: int, scale: float | None = None):
+    """Attention of every entry on its own slice with its own lists.  Returns out [B,Hq,S,D] and
+    lse [B,Hq,S] fp32, NaN where an entry has no token."""
+    B, Hq, S, D = q.shape
+    P = k.shape[2] - S
+    out = torch.full((B, Hq, S, D), float("nan"), dtype=torch.float32)
+    lse = torch.full((B, Hq, S), float("nan"), dtype=torch.float32)
+    for b in range(B):
+        n = int(seq_lens[b])
+        if n <= 0:
+            continue
+        nb = -(-n // block_size)
+        o_b, l_b = attn(q[b:b + 1, :, :n], k[b:b + 1, :, :P + n], v[b:b + 1, :, :P + n], idx[b:b + 1, :, :nb],
+                        cnt[b:b + 1, :, :nb], block_size, scale)
+        out[b, :, :n] = o_b[0]
+        lse[b, :, :n] = l_b[0]
+    return out, lse
