@@ -107,6 +107,16 @@ typedef struct spa_params {
                                  head axis (also for sparse_prefill_attn and, per KV head, for
                                  spa_select_opts.head_pattern).  The heads of a group then walk the
                                  same key blocks at the same time, which the L2 turns into reuse */
+    const int32_t *seq_lens;   /* NULL, or a DEVICE array of `batch` int32 (ragged batch): entry b has
+                                 seq_lens[b] query tokens (clamped to [0, seq_len]) and kv_prefix_len +
+                                 seq_lens[b] key tokens; the tensors keep their padded shapes and
+                                 strides, seq_len stays the padded length that fixes NB and T.  Entry b
+                                 is processed exactly as a batch-1 call of its own length would be
+                                 (its last block may be partial; a Tri-shape strip means the entry's
+                                 own last query blocks).  Rows of block_idx / block_cnt past an entry's
+                                 last block get count 0 and -1 entries; tokens past an entry's length
+                                 are not read, and their out / lse / pooled / score entries are not
+                                 written                                                          */
 } spa_params;
 
 /* Human-readable text for a return code.  Never NULL. */

@@ -34,7 +34,7 @@ class SpaParams(ctypes.Structure):
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
                 ("stride_blocks", ctypes.c_int32), ("n_dense_q_blocks", ctypes.c_int32),
                 ("stride_reach_blocks", ctypes.c_int32), ("kv_prefix_len", ctypes.c_int32),
-                ("lists_per_kv_head", ctypes.c_int32)]
+                ("lists_per_kv_head", ctypes.c_int32), ("seq_lens", ctypes.c_void_p)]
 
 
 class SpaSelectOpts(ctypes.Structure):
@@ -94,8 +94,15 @@ def _strides(t):
 
 def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, n_sink_blocks,
                 n_local_blocks, top_k_blocks, softmax_scale=None, q=None, k=None, v=None, out=None,
-                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0, lists_per_kv_head=0, kv_prefix_len=0) -> SpaParams:
+                stride_blocks=0, n_dense_q_blocks=0, stride_reach_blocks=0, lists_per_kv_head=0, kv_prefix_len=0,
+                seq_lens=None) -> SpaParams:
+    """seq_lens: optional int32 device tensor [batch] (ragged batch); the caller keeps it alive."""
     p = SpaParams()
+    if seq_lens is not None:
+        if seq_lens.dtype != torch.int32 or not seq_lens.is_cuda or not seq_lens.is_contiguous() \
+                or tuple(seq_lens.shape) != (batch,):
+            raise TypeError("seq_lens must be a contiguous int32 device tensor of shape [batch]")
+        p.seq_lens = seq_lens.data_ptr()
     p.batch, p.n_q_heads, p.n_kv_heads = batch, n_q_heads, n_kv_heads
     p.seq_len, p.head_dim, p.block_size = seq_len, head_dim, block_size
     p.n_sink_blocks, p.n_local_blocks, p.top_k_blocks = n_sink_blocks, n_local_blocks, top_k_blocks
@@ -109,13 +116,13 @@ def make_params(*, batch, n_q_heads, n_kv_heads, seq_len, head_dim, block_size, 
 
 
 def _params_from(q, k, block_size, ns, nl, topk, scale, v=None, out=None, stride_blocks=0,
-                 n_dense_q_blocks=0, stride_reach_blocks=0, group_shared=False) -> SpaParams:
+                 n_dense_q_blocks=0, stride_reach_blocks=0, group_shared=False, seq_lens=None) -> SpaParams:
     B, Hq, S, D = q.shape
     return make_params(batch=B, n_q_heads=Hq, n_kv_heads=k.shape[1], seq_len=S, head_dim=D,
                        block_size=block_size, n_sink_blocks=ns, n_local_blocks=nl, top_k_blocks=topk,
                        softmax_scale=scale, q=q, k=k, v=v, out=out, stride_blocks=stride_blocks,
                        n_dense_q_blocks=n_dense_q_blocks, stride_reach_blocks=stride_reach_blocks,
-                       lists_per_kv_head=group_shared, kv_prefix_len=k.shape[2] - S)
+                       lists_per_kv_head=group_shared, kv_prefix_len=k.shape[2] - S, seq_lens=seq_lens)
 
 
 def _ptr(t):
@@ -170,10 +177,11 @@ def _workspace(p: SpaParams, device):
     return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
 
 
-def pool(q, k, block_size):
-    """sparse_prefill_pool: returns (q_pooled, k_pooled) fp32."""
+def pool(q, k, block_size, seq_lens=None):
+    """sparse_prefill_pool: returns (q_pooled, k_pooled) fp32 (blocks past a ragged entry's end are
+    left as allocated)."""
     _dev_bf16(q, k)
-    p = _params_from(q, k, block_size, 0, 1, 0, None)
+    p = _params_from(q, k, block_size, 0, 1, 0, None, seq_lens=seq_lens)
     B, Hq, S, D = q.shape
     NB = -(-S // block_size)
     qp = torch.empty((B, Hq, NB, D), dtype=torch.float32, device=q.device)
@@ -195,7 +203,8 @@ def value_norms(v, block_size):
 
 def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
            return_scores=False, workspace=None, top_k_per_block=None, v=None, stride_blocks=0,
-           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, group_shared=False, mass_gamma=None):
+           n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, group_shared=False, mass_gamma=None,
+           seq_lens=None):
     """sparse_prefill_select; sparse_prefill_select_tpd when top_k_per_block (int32 [NB] device
     tensor) is given; sparse_prefill_select_stem when v is given (output-aware ranking, with or
     without a schedule); sparse_prefill_select_ex with head_pattern or mass_gamma (cumulative-mass
@@ -203,7 +212,7 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     _dev_bf16(q, k)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
-                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared)
+                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared, seq_lens=seq_lens)
     B, Hq, S, _ = q.shape
     if group_shared:
         Hq = k.shape[1]                              # one list per KV head
@@ -235,7 +244,8 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
 
 
 def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_per_block=None,
-                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, mass_gamma=None):
+                     stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0, mass_gamma=None,
+                     seq_lens=None):
     """sparse_prefill_topk_from_scores (…_tpd with a schedule, …_ex with head_pattern or mass_gamma) on
     [B,Hq,NB,NB] fp32 device scores."""
     if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous():
@@ -245,7 +255,7 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
                     kv_prefix_len=(NBk - NB) * 64,
                     n_sink_blocks=n_sink_blocks, n_local_blocks=n_local_blocks, top_k_blocks=top_k_blocks,
                     stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
-                    stride_reach_blocks=stride_reach_blocks)
+                    stride_reach_blocks=stride_reach_blocks, seq_lens=seq_lens)   # seq_lens in tokens of 64-token blocks
     T = row_capacity(p)
     idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=scores.device)
     cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=scores.device)
@@ -265,7 +275,7 @@ def topk_from_scores(scores, n_sink_blocks, n_local_blocks, top_k_blocks, top_k_
 
 
 def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
-         workspace=None, pattern=None, group_shared=False):
+         workspace=None, pattern=None, group_shared=False, seq_lens=None):
     """sparse_prefill_attn: returns out bf16 [B,Hq,S,D] (and lse fp32 [B,Hq,S]).
     pattern: optional (n_sink, n_local, top_k, stride_blocks, n_dense_q_blocks[, stride_reach_blocks]) the lists were made
     with; it only tells the library how uneven the rows are (scheduling hint)."""
@@ -276,12 +286,12 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
     # the pattern fields only fix T here; the lists themselves carry the selection
     if pattern is None:
         p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, v=v, out=out,
-                         group_shared=group_shared)
+                         group_shared=group_shared, seq_lens=seq_lens)
     else:
         ns, nl, tk, stride, n_dense, *rest = pattern
         p = _params_from(q, k, block_size, ns, nl, tk, softmax_scale, v=v, out=out, stride_blocks=stride,
                          n_dense_q_blocks=n_dense, stride_reach_blocks=rest[0] if rest else 0,
-                         group_shared=group_shared)
+                         group_shared=group_shared, seq_lens=seq_lens)
     if block_idx.shape[1] != (k.shape[1] if group_shared else Hq):
         raise TypeError("block_idx has the wrong number of heads for this call")
     if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
@@ -298,7 +308,7 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
           return_lse=False, return_lists=False, workspace=None, out=None, top_k_per_block=None,
           output_aware=False, stride_blocks=0, n_dense_q_blocks=0, head_pattern=None, stride_reach_blocks=0,
-          group_shared=False, mass_gamma=None):
+          group_shared=False, mass_gamma=None, seq_lens=None):
     """sparse_prefill_fused (…_tpd with a schedule, …_stem with output_aware): select + attn on the
     current stream."""
     _dev_bf16(q, k, v)
@@ -306,7 +316,7 @@ def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, soft
     out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v, out=out,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
-                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared)
+                     stride_reach_blocks=stride_reach_blocks, group_shared=group_shared, seq_lens=seq_lens)
     NB, T = -(-S // block_size), row_capacity(p)
     Hl = k.shape[1] if group_shared else Hq          # heads in the lists
     idx = torch.empty((B, Hl, NB, T), dtype=torch.int32, device=q.device) if return_lists else None

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ v, Strides vs, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, uint16_t* __restrict__ out, Strides os, float* __restrict__ lse,
-    int Hq, int G, int NB, int T, int S, float scale, int shared, int Skv) {
+    int Hq, int G, int NB, int T, int S, float scale, int shared, int Skv, const int32_t* __restrict__ seq_lens) {
     constexpr int NT = BS * 2;        // threads
     constexpr int KC = BS / 32;       // 32-key chunks of a key tile
     constexpr int DS = D / 16;        // 16-wide slices of head_dim (QK^T reduction)
@@ -63,6 +63,10 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const int kvh = rest % Hkv;
     const int b = rest / Hkv;
     const int h = kvh * G + g;
+    // ragged batch: this entry's own length; query blocks past it leave (the whole workgroup, before any barrier)
+    const int Sb = entry_len(seq_lens, b, S);
+    if (i * BS >= Sb) return;
+    const int Skvb = Skv - S + Sb;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     {
         // rows past the end of a partial last block read the last token (never stored)
         int qr = 32 * wave + l32;
-        if (i * BS + qr > S - 1) qr = S - 1 - i * BS;
+        if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
         const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
         for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     auto fetch = [&](int blk) {
         const uint16_t* kt = kb + (int64_t)blk * BS * ks.t;
         const uint16_t* vt = vb + (int64_t)blk * BS * vs.t;
-        const int last_row = Skv - 1 - blk * BS;        // >= BS - 1 except in a partial last block
+        const int last_row = Skvb - 1 - blk * BS;       // >= BS - 1 except in a partial last block
 #pragma unroll
         for (int p = 0; p < CPT; ++p) {
             int cidx = p * NT + tid;
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(BS * 2) void attn_kernel(
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / l_tot;
     const int qpos = 32 * wave + l32;
-    if (i * BS + qpos >= S) return;                     // token past the end of a partial last block
+    if (i * BS + qpos >= Sb) return;                     // token past the end of a partial last block
     uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + qpos) * os.t;
 #pragma unroll
     for (int dc = 0; dc < DC; ++dc)
@@ -228,7 +232,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     int64_t nwg = (int64_t)d.B * d.Hq * d.NB;
     hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st,
                        (const uint16_t*)q, qs, (const uint16_t*)k, ks, (const uint16_t*)v, vs, idx, cnt,
-                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared, d.Skv);
+                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared, d.Skv, d.seq_lens);
     return hipGetLastError();
 }
 

@@ -75,14 +75,17 @@ __device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) 
 // V [B,Hkv,S,D] (strided) -> Vt [B,Hkv,NB,D,BS] contiguous.
 template <int BS>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv,
-                                                          int NB, int S, uint16_t* __restrict__ vt) {
+                                                          int NB, int S, uint16_t* __restrict__ vt,
+                                                          const int32_t* __restrict__ seq_lens, int Sq) {
     constexpr int PITCH = D + 2;
     __shared__ uint16_t tile[BS * PITCH];
     const int blk = blockIdx.x, bh = blockIdx.y;
     const int b = bh / Hkv, h = bh % Hkv;
     const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
     const int tid = threadIdx.x;
-    const int n_valid = S - blk * BS < BS ? S - blk * BS : BS;
+    const int Sb = S - Sq + entry_len(seq_lens, b, Sq);    // ragged batch: key tokens of this entry
+    if (blk * BS >= Sb) return;                            // block past its end: never read by the attention kernel
+    const int n_valid = Sb - blk * BS < BS ? Sb - blk * BS : BS;
 #pragma unroll
     for (int p = 0; p < BS * D / 8 / 256; ++p) {
         int c = p * 256 + tid;
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale, RowDeal deal, int shared, int NBk, int Skv) {
+    float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens) {
     constexpr int NW = BS / 32;         // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int LPW = 16 / NW;        // 1-KB load instructions per wave per operand per sub-tile
@@ -193,6 +196,10 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     const int kvh = head_slot % Hkv;
     const int b = head_slot / Hkv;
     const int h = kvh * G + g;
+    // ragged batch: this entry's own length; query blocks past it leave (the whole workgroup, before any barrier)
+    const int Sb = entry_len(seq_lens, b, S);
+    if (i * BS >= Sb) return;
+    const int Skv = Skv_max - S + Sb;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -271,7 +278,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     {
         // rows past the end of a partial last block read the last token (their results are never stored)
         int qr = 32 * wave + l32;
-        if (i * BS + qr > S - 1) qr = S - 1 - i * BS;
+        if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
         const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
@@ -498,7 +505,7 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_d128_kernel(
     // ---- epilogue ----------------------------------------------------------------
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
-    if (i * BS + q_in_blk >= S) return;                  // token past the end of a partial last block
+    if (i * BS + q_in_blk >= Sb) return;                  // token past the end of a partial last block
     uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
 #pragma unroll
     for (int dc = 0; dc < 4; ++dc)
@@ -518,7 +525,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
                   void* vt, hipStream_t st) {
     hipLaunchKernelGGL((transpose_v_kernel<BS>), dim3(d.NBk, d.B * d.Hkv), dim3(256), 0, st,
-                       (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt);
+                       (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt, d.seq_lens, d.S);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const RowDeal deal = deal_rows(d);
@@ -526,7 +533,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_d128_kernel<BS>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv);
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens);
     return hipGetLastError();
 }
 

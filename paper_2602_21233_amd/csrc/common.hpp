@@ -18,6 +18,7 @@ struct Dims {
     int stride, n_dense, reach;   // strided static columns, dense bottom strip, reach of the strided columns (0 = off)
     float scale;
     int gamma_q16;                // cumulative-mass budget in 16-bit fixed point, -1 = none
+    const int32_t* seq_lens;      // device array [B] of per-entry token counts (ragged batch), or nullptr
 };
 
 inline Dims dims_of(const spa_params& p) {
@@ -34,7 +35,15 @@ inline Dims dims_of(const spa_params& p) {
     d.T = (int)((t < d.NBk && d.n_dense <= 0) ? t : d.NBk);
     d.scale = p.softmax_scale;
     d.gamma_q16 = -1;
+    d.seq_lens = p.seq_lens;
     return d;
+}
+
+// Ragged batch: tokens of batch entry b (the tensors keep their padded length S)
+__device__ __forceinline__ int entry_len(const int32_t* __restrict__ seq_lens, int b, int S) {
+    if (seq_lens == nullptr) return S;
+    const int v = seq_lens[b];
+    return v < 0 ? 0 : (v > S ? S : v);
 }
 
 struct Strides { int64_t b, h, t; };

@@ -28,7 +28,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
                                                    int n_q_rows /* B*Hq or 0 */, int Hq,
                                                    const uint16_t* __restrict__ k, Strides ks, int Hkv,
                                                    float* __restrict__ qp, float* __restrict__ kp, int NBq, int Sq,
-                                                   int NBk, int Skv, int k_tiled) {
+                                                   int NBk, int Skv, int k_tiled,
+                                                   const int32_t* __restrict__ seq_lens) {
     constexpr int TPR = D / 8;          // lanes per token row
     constexpr int RPP = 256 / TPR;      // token rows per pass
     constexpr int PASSES = BS / RPP;
@@ -40,8 +41,9 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
     float* dst;
     int S;                                   // tokens of this tensor (K may carry a prefix)
     if (hy < n_q_rows) {
-        if (blk >= NBq) return;              // the grid spans the key blocks
         int b = hy / Hq, h = hy % Hq;
+        Sq = entry_len(seq_lens, b, Sq);     // ragged batch: this entry's own length
+        if (blk * BS >= Sq) return;          // the grid spans the key blocks of the longest entry
         src = q + b * qs.b + h * qs.h + (int64_t)blk * BS * qs.t;
         dst = qp + ((int64_t)hy * NBq + blk) * D;
         S = Sq;
@@ -49,6 +51,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
     } else {
         hy -= n_q_rows;
         int b = hy / Hkv, h = hy % Hkv;
+        Skv = Skv - Sq + entry_len(seq_lens, b, Sq);
+        if (blk * BS >= Skv) return;
         src = k + b * ks.b + h * ks.h + (int64_t)blk * BS * ks.t;
         dst = kp + ((int64_t)hy * NBk + blk) * D;
         S = Skv;
@@ -109,7 +113,7 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
     if (nq + nk == 0) return hipSuccess;
     dim3 grid(nk ? d.NBk : d.NB, nq + nk);
     hipLaunchKernelGGL((pool_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)q, qs, nq, d.Hq,
-                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S, d.NBk, d.Skv, k_tiled ? 1 : 0);
+                       (const uint16_t*)k, ks, d.Hkv, qp, kp, d.NB, d.S, d.NBk, d.Skv, k_tiled ? 1 : 0, d.seq_lens);
     return hipGetLastError();
 }
 
@@ -120,7 +124,8 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
 // order.  A block of all-zero values gives -inf.
 template <int D, int BS>
 __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv, int NB,
-                                                    int S, float* __restrict__ lvn) {
+                                                    int S, float* __restrict__ lvn,
+                                                    const int32_t* __restrict__ seq_lens, int Sq) {
     constexpr int TPR = D / 8;
     constexpr int RPP = 256 / TPR;
     constexpr int PASSES = BS / RPP;
@@ -130,6 +135,8 @@ __global__ __launch_bounds__(256) void vnorm_kernel(const uint16_t* __restrict__
     const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
     const int tid = threadIdx.x;
     const int row0 = tid / TPR, chunk = tid % TPR;
+    S = S - Sq + entry_len(seq_lens, b, Sq);                        // ragged batch: key tokens of this entry
+    if (blk * BS >= S) return;
     const int n_valid = S - blk * BS < BS ? S - blk * BS : BS;      // partial last block
     uint4 raw[PASSES];
 #pragma unroll
@@ -182,7 +189,7 @@ __global__ __launch_bounds__(256) void group_mean_kernel(const float4* __restric
 template <int D, int BS>
 hipError_t launch_vn(const Dims& d, const void* v, Strides vs, float* lvn, hipStream_t st) {
     dim3 grid(d.NBk, d.B * d.Hkv);
-    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, lvn);
+    hipLaunchKernelGGL((vnorm_kernel<D, BS>), grid, dim3(256), 0, st, (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, lvn, d.seq_lens, d.S);
     return hipGetLastError();
 }
 

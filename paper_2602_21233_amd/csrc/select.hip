@@ -159,13 +159,21 @@ template <bool EXT>
 __global__ __launch_bounds__(kWaves * 64) void topk_from_scores_kernel(
     const float* __restrict__ scores, int64_t n_rows, int NB /* query blocks */, int NBk, int off, Pattern pt, int k,
     const int32_t* __restrict__ k_rows, const int32_t* __restrict__ head_pattern, int Hq, int T,
-    int32_t* __restrict__ idx, int32_t* __restrict__ cnt, int gamma_q16 /* -1: no mass budget */) {
+    int32_t* __restrict__ idx, int32_t* __restrict__ cnt, int gamma_q16 /* -1: no mass budget */,
+    const int32_t* __restrict__ seq_lens, int S, int Bs) {
     extern __shared__ uint32_t lds_keys[];       // [kWaves][padded NBk] keys, then 256 counters per wave (mass budget)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
     if (row >= n_rows) return;                               // whole wave leaves together
     const int iq = (int)(row % NB);
     const int i = iq + off;                                  // block position in the sequence
+    const int NB_b = (entry_len(seq_lens, (int)(row / NB / Hq), S) + Bs - 1) / Bs;   // ragged batch
+    if (iq >= NB_b) {                                        // a row past its entry's end: empty list
+        for (int t = lane; t < T; t += 64) idx[row * T + t] = -1;
+        if (lane == 0) cnt[row] = 0;
+        return;
+    }
+    pt.NB = off + NB_b;
     head_config(head_pattern, (int)((row / NB) % Hq), pt, k);
     const int padded = ((NBk + 63) >> 6) << 6;
     uint32_t* keys = lds_keys + wave * padded;
@@ -445,6 +453,8 @@ struct ScoreArgs {
     int32_t* cnt;
     float* scores_out;
     uint32_t gamma_q16;           // cumulative-mass budget in 16-bit fixed point (MASS kernels only)
+    const int32_t* seq_lens;      // ragged batch: tokens per batch entry, or nullptr
+    int S, Bs;                    // padded query tokens, block size (to turn seq_lens into block counts)
 };
 
 // Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
@@ -562,10 +572,20 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
 
     // ---- phase 2 ---------------------------------------------------------------------
     head_config(head_pattern, h, pt, k);
+    // ragged batch: this entry's own block count; its rows beyond get empty lists, and the dense
+    // strip of the Tri-shape means the entry's own last rows
+    const int NB_b = (entry_len(a.seq_lens, b, a.S) + a.Bs - 1) / a.Bs;
+    pt.NB = off + NB_b;
 #pragma nounroll
     for (int r = wave; r < R; r += kMfmaWaves) {
         const int iq = i0 + r;                            // query block of the call
         if (iq >= NB) break;                              // wave-uniform
+        if (iq >= NB_b) {
+            const int64_t row = (int64_t)bh * NB + iq;
+            for (int t = lane; t < T; t += 64) idx[row * T + t] = -1;
+            if (lane == 0) cnt[row] = 0;
+            continue;
+        }
         const int i = iq + off;                           // its block position in the sequence
         const int n = i + 1;
         const float* srow = S + r * LD;
@@ -660,7 +680,7 @@ hipError_t allow_lds(const void* kernel, size_t bytes) {
 ScoreArgs score_args(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern,
                      const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null) {
     return ScoreArgs{qp, kp, d.Hq, d.G, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale,
-                     idx, cnt, scores_or_null, d.gamma_q16 >= 0 ? (uint32_t)d.gamma_q16 : 0u};
+                     idx, cnt, scores_or_null, d.gamma_q16 >= 0 ? (uint32_t)d.gamma_q16 : 0u, d.seq_lens, d.S, d.Bs};
 }
 
 size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) * sizeof(uint32_t); }
@@ -677,10 +697,10 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     if (e != hipSuccess) return e;
     if (extended(d))
         hipLaunchKernelGGL(topk_from_scores_kernel<true>, dim3(grid), dim3(kWaves * 64), lds, st,
-                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16);
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16, d.seq_lens, d.S, d.Bs);
     else
         hipLaunchKernelGGL(topk_from_scores_kernel<false>, dim3(grid), dim3(kWaves * 64), lds, st,
-                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16);
+                           scores, n_rows, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, d.Hq, d.T, idx, cnt, d.gamma_q16, d.seq_lens, d.S, d.Bs);
     return hipGetLastError();
 }
 

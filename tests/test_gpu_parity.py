@@ -718,6 +718,71 @@ def test_kv_prefix_equals_the_rows_of_the_full_run(spa, oracle, Sq, P, D, Bs):
 
 
 # ------------------------------------------------------------- HIP graph replay
+# ------------------------------------------------------------ ragged batches
+@pytest.mark.parametrize("lens,P,Hq,Hkv,D,Bs,kw", [
+    ([5 * 64, 3 * 64 + 1, 40], 0, 2, 1, 64, 64, {}),
+    ([6 * 128, 6 * 128 - 77, 129, 1], 0, 4, 2, 128, 128, {}),
+    ([9 * 64 + 5, 64, 5 * 64], 2 * 64, 4, 2, 128, 64, {}),
+    ([7 * 128, 3 * 128 + 50], 128, 4, 1, 128, 128, dict(n_dense_q_blocks=2, stride_blocks=3)),
+    ([20 * 64, 11 * 64 + 9], 0, 4, 2, 128, 64, dict(group_shared=True)),
+    ([20 * 64, 0, 11 * 64 + 9], 0, 2, 2, 128, 64, dict(mass_gamma=0.8)),
+    ([9 * 64 + 5, 3 * 64], 64, 4, 2, 128, 64, dict(output_aware=True)),
+])
+def test_ragged_batch_equals_single_sequence_calls(spa, oracle, lens, P, Hq, Hkv, D, Bs, kw):
+    """Every entry of a ragged batch comes out exactly as a batch-1 call on its own tokens does
+    (bit for bit: same kernels, same order of arithmetic), and against the oracle within the
+    attention tolerance; padded rows get empty lists and padded tokens are not written."""
+    B, S = len(lens), max(lens)
+    g = torch.Generator().manual_seed(sum(lens) + D)
+    q = torch.randn((B, Hq, S, D), generator=g).to(torch.bfloat16)
+    k = torch.randn((B, Hkv, P + S, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, Hkv, P + S, D), generator=g).to(torch.bfloat16)
+    ns, nl, tk = 1, 2, 3
+    dq, dk, dv = q.cuda(), k.cuda(), v.cuda()
+    dl = torch.tensor(lens, dtype=torch.int32).cuda()
+    sentinel = 12352.0                                   # exact in bf16
+    out = torch.full_like(dq, sentinel)
+    res = spa.fused(dq, dk, dv, Bs, ns, nl, tk, return_lse=True, return_lists=True, out=out, seq_lens=dl, **kw)
+    _, lse, idx, cnt = res
+    # the same through the two-call path
+    sel_kw = dict(kw)
+    if sel_kw.pop("output_aware", False):
+        sel_kw["v"] = dv
+    idx2, cnt2 = spa.select(dq, dk, Bs, ns, nl, tk, seq_lens=dl, **sel_kw)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    pattern = (ns, nl, tk, kw.get("stride_blocks", 0), kw.get("n_dense_q_blocks", 0))
+    out2 = spa.attn(dq, dk, dv, idx, cnt, Bs, pattern=pattern, group_shared=kw.get("group_shared", False), seq_lens=dl)
+    o_kw = dict(stride=kw.get("stride_blocks", 0), n_dense=kw.get("n_dense_q_blocks", 0),
+                group_shared=kw.get("group_shared", False), gamma=kw.get("mass_gamma"),
+                v=v if kw.get("output_aware") else None)
+    for b, n in enumerate(lens):
+        nb = -(-n // Bs)
+        assert (cnt[b, :, nb:] == 0).all() and (idx[b, :, nb:] == -1).all(), b
+        assert (out[b, :, n:].float() == sentinel).all(), b                    # padding untouched
+        if n == 0:
+            continue
+        assert torch.equal(out2[b, :, :n], out[b, :, :n])
+        o1, l1, i1, c1 = spa.fused(dq[b:b + 1, :, :n].contiguous(), dk[b:b + 1, :, :P + n].contiguous(),
+                                   dv[b:b + 1, :, :P + n].contiguous(), Bs, ns, nl, tk, return_lse=True,
+                                   return_lists=True, **kw)
+        assert torch.equal(cnt[b, :, :nb], c1[0]) and torch.equal(idx[b, :, :nb, :i1.shape[3]], i1[0]), b
+        assert (idx[b, :, :nb, i1.shape[3]:] == -1).all()
+        assert torch.equal(out[b, :, :n], o1[0]) and torch.equal(lse[b, :, :n], l1[0]), b
+    # against the oracle: attention on the GPU's lists, entry by entry
+    want, want_lse = oracle.attn_ragged(q, k, v, idx.cpu().repeat_interleave(Hq // Hkv, 1) if kw.get("group_shared") else idx.cpu(),
+                                        cnt.cpu().repeat_interleave(Hq // Hkv, 1) if kw.get("group_shared") else cnt.cpu(),
+                                        lens, Bs)
+    for b, n in enumerate(lens):
+        if n:
+            _assert_attn_close(out[b, :, :n], want[b, :, :n], f"entry {b}")
+            assert (lse[b, :, :n].cpu() - want_lse[b, :, :n]).abs().max().item() <= 2e-2
+    # and the lists against the oracle's own selection (near-ties may flip; counts are exact)
+    o_idx, o_cnt = oracle.select_ragged(q, k, lens, Bs, ns, nl, tk, **o_kw)
+    if kw.get("mass_gamma") is None:
+        assert torch.equal(cnt.cpu(), o_cnt)
+    assert (idx.cpu() == o_idx).float().mean().item() > 0.97
+
+
 def test_fused_call_replays_from_a_hip_graph(spa, oracle):
     """The calls only enqueue kernels on the caller's stream (no allocation, no synchronisation,
     no memset), so a fused call can be captured once and replayed; every replay, with eager work
