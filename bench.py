@@ -7,12 +7,13 @@ heads, head_dim 128, block 128, sink 1 + local 4 + top-k 64).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N] [--no-cpu-baseline]
-                    [--variant uniform|tpd|stem|strided|trishape|shared]
+                    [--variant uniform|tpd|stem|strided|trishape|shared|mass]
 
 --variant (default uniform = the headline) times the same workload under the other selection
 rules the library has: a position-decaying budget (tpd), that plus the output-aware ranking
-score (stem), strided static columns, or a Tri-shape dense strip; FLOPs are then counted on the
-block pairs the lists actually hold.
+score (stem), strided static columns, a Tri-shape dense strip, group-shared lists, or a cumulative-mass
+budget of 0.9 under the same count cap (mass); FLOPs are then counted on the block pairs the lists
+actually hold.
 """
 import argparse
 import json
@@ -74,7 +75,8 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1200)
-    ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared"), default="uniform")
+    ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared", "mass"),
+                    default="uniform")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (heads shard across GPUs with no exchange; "
@@ -104,6 +106,8 @@ def main():
         sel_kw["top_k_per_block"] = inputs.decay_schedule(w).cuda()
     if args.variant == "stem":
         sel_kw["v"] = dv
+    if args.variant == "mass":
+        sel_kw["mass_gamma"] = 0.9
     if args.variant == "strided":
         pat_kw = dict(stride_blocks=16)
     if args.variant == "trishape":
