@@ -218,7 +218,7 @@ __device__ __forceinline__ int wave_sum(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-constexpr int kMfmaWaves = 8;
+constexpr int kMfmaWaves = 8;   // wavefronts of a score/top-k workgroup unless stated (NWV)
 
 // inclusive prefix sum of v over the 64 lanes (Hillis-Steele inside the rows of 16 with DPP row
 // shifts, then the row totals are carried over with the row broadcasts)
@@ -463,7 +463,7 @@ struct ScoreArgs {
 // The split pooled queries (MFMA A operands) are staged in LDS, in the space of the phase-2 counters,
 // instead of being held in 8 * D / 16 registers per lane: the kernel stays within 128 registers.
 // Needs R * D * 4 bytes <= the counters' 8 KB.
-template <int D, int R, int MAXC, bool EXT, bool MASS>
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV>
 __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
@@ -495,7 +495,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
     // at bf16 offset ((((s * 2 + p) * R + r) * 2 + half) * 8
     __bf16* const qlds = reinterpret_cast<__bf16*>(S + R * LD);
     {
-        static_assert(R * D * 4 <= kMfmaWaves * 256 * 4, "staged queries must fit the counters' space");
+        static_assert(R * D * 4 <= NWV * 256 * 4, "staged queries must fit the counters' space");
         const int t = threadIdx.x;
         if (t < R * DS * 2) {
             const int r = t % R, s2 = (t / R) >> 1, hf = (t / R) & 1;
@@ -530,12 +530,12 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
             kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
         }
     }
-    for (int jt = wave; jt < n_jt; jt += kMfmaWaves) {
+    for (int jt = wave; jt < n_jt; jt += NWV) {
         const int j = 32 * jt + l32;
         // output-aware ranking: the key block's ln(value magnitude) joins its score
         const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
         // the last tile refills from itself: in bounds, never used
-        const __bf16* next = tile_ptr(jt + kMfmaWaves < n_jt ? jt + kMfmaWaves : jt);
+        const __bf16* next = tile_ptr(jt + NWV < n_jt ? jt + NWV : jt);
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -565,7 +565,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
     if (scores_out != nullptr) {                          // key blocks past the last computed tile
         const int j_first = 32 * n_jt;
         for (int r = 0; r < R && i0 + r < NB; ++r)
-            for (int j = j_first + (int)threadIdx.x; j < NBk; j += kMfmaWaves * 64)
+            for (int j = j_first + (int)threadIdx.x; j < NBk; j += NWV * 64)
                 scores_out[((int64_t)bh * NB + i0 + r) * NBk + j] = -INFINITY;
     }
     __syncthreads();
@@ -577,7 +577,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
     const int NB_b = (entry_len(a.seq_lens, b, a.S) + a.Bs - 1) / a.Bs;
     pt.NB = off + NB_b;
 #pragma nounroll
-    for (int r = wave; r < R; r += kMfmaWaves) {
+    for (int r = wave; r < R; r += NWV) {
         const int iq = i0 + r;                            // query block of the call
         if (iq >= NB) break;                              // wave-uniform
         if (iq >= NB_b) {
@@ -659,8 +659,8 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
 
 // Two workgroups per CU (4 wavefronts per SIMD): at most 128 registers, which is why the query
 // operands are staged in LDS.
-template <int D, int R, int MAXC, bool EXT, bool MASS>
-__global__ __launch_bounds__(kMfmaWaves * 64, 4) void score_topk_mfma_kernel(ScoreArgs a, int n_tiles) {
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV>
+__global__ __launch_bounds__(NWV * 64, 4) void score_topk_mfma_kernel(ScoreArgs a, int n_tiles) {
     extern __shared__ __attribute__((aligned(128))) float S[];   // [R][LD] scores of this workgroup's rows, then 256 counters per wave
     // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
     // (b, head, row tile) order so that one L2 serves few KV heads and their Kp stays resident.
@@ -668,7 +668,7 @@ __global__ __launch_bounds__(kMfmaWaves * 64, 4) void score_topk_mfma_kernel(Sco
     int wg = blockIdx.x;
     if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
     const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
-    score_topk_rows<D, R, MAXC, EXT, MASS>(a, wg / n_tiles, tile * R, S);
+    score_topk_rows<D, R, MAXC, EXT, MASS, NWV>(a, wg / n_tiles, tile * R, S);
 }
 
 // Dynamic LDS above the default cap has to be requested per kernel.
@@ -704,16 +704,16 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     return hipGetLastError();
 }
 
-template <int D, int R, int MAXC, bool EXT, bool MASS>
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV = (R * (MAXC * 64 + 8) * 4 > 80 * 1024 ? 16 : 8)>
 hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                        int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float) + kMfmaWaves * 256 * sizeof(uint32_t);
-    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT, MASS>, lds);
+    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float) + NWV * 256 * sizeof(uint32_t);
+    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV>, lds);
     if (e != hipSuccess) return e;
     const int n_tiles = (d.NB + R - 1) / R;
     dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
     const ScoreArgs a = score_args(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null);
-    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT, MASS>), grid, dim3(kMfmaWaves * 64), lds, st, a, n_tiles);
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV>), grid, dim3(NWV * 64), lds, st, a, n_tiles);
     return hipGetLastError();
 }
 
@@ -732,13 +732,15 @@ hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const in
 template <int D>
 hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
                          int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    // rows per workgroup shrink as rows get longer: R * (NB padded) fp32 scores stay within 66 KB of
-    // LDS, so that two workgroups share a CU (measured at 131072 / 262144 tokens: 125 -> 106 us and
-    // 0.64 -> 0.50 ms against 32 / 16 rows with one workgroup per CU)
+    // rows per workgroup shrink as rows get longer: up to 1024 blocks R * (NB padded) fp32 scores stay
+    // within 66 KB of LDS, so that two 8-wave workgroups share a CU (measured at 131072 tokens:
+    // 125 -> 106 us against 32 rows with one 8-wave workgroup per CU)
     if (d.NBk <= 256) return launch_mfma<D, 16, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
     if (d.NBk <= 512) return launch_mfma<D, 16, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
     if (d.NBk <= 1024) return launch_mfma<D, 16, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 2048) return launch_mfma<D, 8, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    // 1025 .. 2048 blocks: 16 rows (131 KB) by one 16-wave workgroup per CU, same occupancy and half the
+    // re-reads of the pooled K against 8 rows by two 8-wave workgroups (0.99 -> 0.95 ms at 262144 tokens)
+    if (d.NBk <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
     return launch_mfma<D, 4, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
 }
 
