@@ -173,7 +173,7 @@ def main():
         "select_hbm": {"achieved": select_bytes / (sel_avg * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                        "frac": select_bytes / (sel_avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "bytes": select_bytes},
-        "roofline": {"bound": "mfma", "kernel": "attn_d128_kernel<128>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128,128>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": read_traffic_note("attn_kernel"), "traffic_unit": "bytes/launch",
                      "timed": "events around sparse_prefill_attn on its stream: the attention kernel plus the "

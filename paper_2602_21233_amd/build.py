@@ -7,12 +7,12 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparse_prefill.so")
-SOURCES = ("api.hip", "pool.hip", "select.hip", "attn.hip", "attn_d128.hip")
+SOURCES = ("api.hip", "pool.hip", "select.hip", "attn.hip")
 HEADERS = ("common.hpp", os.path.join("..", "..", "include", "sparse_prefill.h"))
 
-# The attention kernels never produce NaN from finite inputs; telling the compiler so
+# The attention kernel never produces NaN from finite inputs; telling the compiler so
 # removes the NaN-quieting v_max x,x pairs it otherwise puts around every fmaxf.
-EXTRA = {"attn.hip": ["-fno-honor-nans"], "attn_d128.hip": ["-fno-honor-nans"]}
+EXTRA = {"attn.hip": ["-fno-honor-nans"]}
 
 # Packed-FP32 VALU forms are switched off for device code on purpose.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-function",

@@ -56,7 +56,7 @@ Workspace carve(const Dims& d) {
     w.cnt_off = off; off = align_up(off + (size_t)d.B * d.Hq * d.NB * sizeof(int32_t));
     w.lvn_off = off; off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * sizeof(float));
     w.vt_off = off;
-    if (d.D == 128) off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * d.Bs * d.D * sizeof(uint16_t));
+    off = align_up(off + (size_t)d.B * d.Hkv * d.NBk * d.Bs * d.D * sizeof(uint16_t));
     w.total = off;
     return w;
 }
@@ -234,13 +234,9 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
     Workspace w = carve(d);
     if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
-    if (d.D == 128)
-        return launch_code(launch_attn_d128(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), v,
-                                            strides_of(p->v_stride), block_idx, block_cnt, out,
-                                            strides_of(p->o_stride), lse_or_null, (char*)ws + w.vt_off, st));
     return launch_code(launch_attn(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), v,
                                    strides_of(p->v_stride), block_idx, block_cnt, out,
-                                   strides_of(p->o_stride), lse_or_null, st));
+                                   strides_of(p->o_stride), lse_or_null, (char*)ws + w.vt_off, st));
 }
 
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,

@@ -1,19 +1,32 @@
-// Block-sparse causal attention over selected key blocks (the "sparse attention
-// kernel" stage of Sec. 4.1.1 of the AngelSlim report), for gfx950.
+// Block-sparse causal attention for gfx950 (the "sparse attention kernel" stage of
+// Sec. 4.1.1 of the AngelSlim report), head_dim 128 or 64, blocks of 128 or 64 tokens.
 //
-// One workgroup owns one (batch, query head, query block); each of its
-// BS/32 wavefronts owns 32 query rows.  For every selected key block the K and V
-// tiles are staged in LDS and the wave computes the TRANSPOSED logits tile
-//   S^T[key, query] = K . Q^T      (v_mfma_f32_32x32x16_bf16, A = K from LDS,
-//                                   B = Q^T held in registers for the whole kernel)
-// so that one lane holds 64 of the 128 logits of a single query: the online
-// softmax needs one cross-lane exchange (lane ^ 32) per statistic, the rescale
-// factor is a per-lane scalar, and exp(S^T) is already in the B-operand layout
-// of the second product
-//   O^T[d, query] += V^T . P^T     (A = V^T read from the row-major V tile with
-//                                   the LDS transpose load ds_read_b64_tr_b16).
-// The list of key blocks is ascending and ends with the diagonal block, so only
-// the last iteration applies the causal mask.
+// Transposed formulation: S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, one
+// workgroup per (batch, head, query block), one wavefront per 32 query rows.  A lane then
+// owns the logits of one query: the rescale factor is a per-lane scalar and exp(S^T) is
+// already the B operand of the second product.  Built around what the LDS can deliver:
+//   * V is transposed once per call into a workspace ([.., block, d, token]) by
+//     transpose_v_kernel, so both MFMA A operands (K rows, V^T rows) are plain
+//     16-byte LDS reads; the LDS transpose read is ~4x slower per byte.
+//   * key blocks are consumed as 64-key sub-tiles, staged by direct
+//     global->LDS loads (global_load_lds_dwordx4, no VGPR round trip) into a
+//     double buffer: the loads of sub-tile n+1 fly during the math of sub-tile n
+//     and there is one barrier per sub-tile.  64 KB of LDS per workgroup leaves
+//     room for two workgroups per CU, so one's softmax overlaps the other's MFMA.
+//   * direct loads land lane-contiguous, so bank conflicts are avoided by an
+//     XOR swizzle applied on the global side (which 16-byte chunk a lane
+//     fetches) instead of row padding.
+//   * K rows are assigned to MFMA rows with bits 2 and 3 of the row index
+//     swapped; the logits a lane ends up holding are then 8 consecutive keys per
+//     16-key slice, which is exactly the B-operand order of the second product.
+//   * no running maximum: weights are 2^(x*c - m*c - 7) against a reference m that is only
+//     raised when some weight reaches 2 (the logit outgrew m by 2^8), which shows as the top
+//     exponent bit of the bf16 weight; the final normalisation makes the result independent
+//     of m.
+//   * a step (32 keys) overlaps three chains: logits of chunk n+2 (MFMA), weights of chunk
+//     n+1 (VALU), O^T += V^T P^T of chunk n (MFMA); its instruction order is fixed by hand.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace spa {
@@ -21,230 +34,548 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
 
-__device__ __forceinline__ bf16x8 lds_read_tr_pair(const uint16_t* p0, const uint16_t* p1) {
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p1);
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+constexpr int KT = 64;                 // keys per staged sub-tile
+
+__device__ __forceinline__ int swz_v(int row) { return (row >> 1) & 7; }                        // 128-B rows
+// K rows are 2 * head_dim bytes: 256 B (16 chunks of 16 B) or 128 B (8 chunks, same rule as V^T rows)
+template <int HD>
+__device__ __forceinline__ int swz_k(int row) {
+    if constexpr (HD == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    else return (row >> 1) & 7;
+}
+// value held by lane ^ 32, via v_permlane32_swap (no LDS round trip)
+__device__ __forceinline__ float other_half(float x) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+    u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    // r[0]: lanes 32..63 now hold lanes 0..31's value; r[1]: lanes 0..31 hold lanes 32..63's value
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+// 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): the wave's 64
+// lanes fill 1 KB starting at LDS byte address lds_addr + IMM, lane l from sbase + voff(l).  Written as
+// inline assembly on purpose: the compiler models the builtin form as an access whose completion
+// order is unknown, and from then on turns every wait for an LDS read into a wait for all of
+// them, which defeats the read-ahead in the pipeline step.  The kernel waits for these loads
+// itself (s_waitcnt vmcnt(0) before the barrier that publishes a sub-tile).
+#pragma clang diagnostic ignored "-Winline-asm"
+template <int IMM>
+__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, uint32_t voff, const void* sbase) {
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase), "i"(IMM)
+                 : "memory", "m0", "scc");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(size_t)(lds_void*)p; }
+__device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
+
+// ---------------------------------------------------------------------------
+// V [B,Hkv,S,D] (strided) -> Vt [B,Hkv,NB,D,BS] contiguous.
+template <int BS, int D>
+__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv,
+                                                          int NB, int S, uint16_t* __restrict__ vt,
+                                                          const int32_t* __restrict__ seq_lens, int Sq) {
+    constexpr int PITCH = D + 2;
+    __shared__ uint16_t tile[BS * PITCH];
+    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / Hkv, h = bh % Hkv;
+    const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
+    const int tid = threadIdx.x;
+    const int Sb = S - Sq + entry_len(seq_lens, b, Sq);    // ragged batch: key tokens of this entry
+    if (blk * BS >= Sb) return;                            // block past its end: never read by the attention kernel
+    const int n_valid = Sb - blk * BS < BS ? Sb - blk * BS : BS;
+#pragma unroll
+    for (int p = 0; p < BS * D / 8 / 256; ++p) {
+        int c = p * 256 + tid;
+        int row = c / (D / 8), col = (c % (D / 8)) * 8;
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);           // tokens past the end of a partial last block: zeros
+        if (row < n_valid) {                            // V itself is not read again: non-temporal load
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (int64_t)row * vs.t + col));
+            x = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row * PITCH + col]);   // PITCH even: 4-byte aligned
+        dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+    }
+    __syncthreads();
+    uint16_t* dstb = vt + (((int64_t)bh * NB + blk) * D) * BS;
+    constexpr int CPR = BS / 8;         // 16-byte chunks per output row
+#pragma unroll
+    for (int p = 0; p < BS * D / 8 / 256; ++p) {
+        int c = p * 256 + tid;
+        int d = c / CPR, t0 = (c % CPR) * 8;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[e] = (uint32_t)tile[(t0 + 2 * e) * PITCH + d] | ((uint32_t)tile[(t0 + 2 * e + 1) * PITCH + d] << 16);
+        *reinterpret_cast<uint4*>(dstb + (int64_t)d * BS + t0) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Instruction order inside a pipeline step is written out by hand: every group between two
+// fences holds one MFMA, the LDS read of an operand needed three MFMAs later and a few softmax
+// VALU instructions, and the scheduler may not move anything across a fence.  Left to itself the
+// compiler (register pressure is high) sinks each LDS read to just before the MFMA that uses it
+// and clusters the VALU work, so the wave stalls on the LDS latency once per MFMA.
+#define SPA_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// How the query blocks of a head are dealt to the 8 XCDs (workgroup ids go round robin over the
+// XCDs and are dispatched in id order, so the XCDs advance through their sequences in step: what
+// has to be equal is the work of the rows that sit at the same position of the 8 sequences).
+//   - the n_dense rows of a Tri-shape strip (each visits up to NB blocks) are dealt one by one;
+//   - the other rows are dealt in runs of `run` consecutive rows, last row first.  Neighbouring
+//     rows share their local-window blocks in the XCD's L2, which favours runs; rows whose length
+//     varies with the position (budget schedule, strided columns, the short first rows) favour a
+//     fine deal.  run = 8 for the plain A-shape, 1 for the extended patterns.
+// seq_len = workgroups per (head, XCD) in the grid; surplus workgroups exit at once.
+struct RowDeal {
+    int n_dense, run, seq_len;
+};
+
+RowDeal deal_rows(const Dims& d) {
+    RowDeal r;
+    r.n_dense = d.n_dense < d.NB ? d.n_dense : d.NB;
+    r.run = (d.stride > 0 || d.n_dense > 0) ? 1 : 8;
+    const int runs = (d.NB - r.n_dense + r.run - 1) / r.run;
+    r.seq_len = (((r.n_dense + 7) >> 3) + ((runs + 7) >> 3) * r.run) * d.G;
+    return r;
+}
+
+template <int N>
+using IC = std::integral_constant<int, N>;
+// f(IC<0>{}), ..., f(IC<N-1>{})
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(IC<N - 1>{});
+    }
 }
 
 template <int BS, int D>
-__global__ __launch_bounds__(BS * 2) void attn_kernel(
+__global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
-    const uint16_t* __restrict__ v, Strides vs, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, uint16_t* __restrict__ out, Strides os, float* __restrict__ lse,
-    int Hq, int G, int NB, int T, int S, float scale, int shared, int Skv, const int32_t* __restrict__ seq_lens) {
-    constexpr int NT = BS * 2;        // threads
-    constexpr int KC = BS / 32;       // 32-key chunks of a key tile
-    constexpr int DS = D / 16;        // 16-wide slices of head_dim (QK^T reduction)
-    constexpr int DC = D / 32;        // 32-wide chunks of head_dim (rows of O^T)
-    constexpr int LDK = D + 8;        // K row pitch: +16 B  -> conflict-free 16-byte column reads
-    constexpr int LDV = D + 32;       // V row pitch: +64 B  -> conflict-free transpose reads
-    constexpr int CPT = D / 16;       // 16-byte chunks per thread per tile
-    __shared__ __attribute__((aligned(16))) uint16_t sK[BS * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[BS * LDV];
+    const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+    uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
+    float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens) {
+    constexpr int NW = BS / 32;         // wavefronts
+    constexpr int NSUB = BS / KT;       // sub-tiles per key block
+    constexpr int DS = D / 16;          // 16-dim slices of a key row = MFMAs of one logits tile
+    constexpr int DT = D / 32;          // 32-row tiles of O^T = MFMAs per 16 keys of the second product
+    constexpr int NG = 2 * DS;          // MFMAs (= instruction groups) of a pipeline step
+    constexpr int TILE = KT * D;        // elements of one K (or V^T) sub-tile: 16 KB / 8 KB
+    constexpr int CPR = D / 8;          // 16-byte chunks of a K row
+    constexpr int RPI = 64 / CPR;       // K rows filled by one 1-KB load instruction
+    constexpr int LPW = TILE / 512 / NW;  // 1-KB load instructions per wave per operand per sub-tile
+    constexpr int TILE_B = TILE * 2;    // bytes of a sub-tile
+    constexpr int CHUNK_B = 32 * D * 2; // bytes of a 32-key chunk of a K sub-tile
+    constexpr int DTILE_B = 32 * KT * 2;  // bytes of 32 d rows of a V^T sub-tile
+    __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][TILE];   // K sub-tile t in buffer t % 2
+    __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][TILE];   // V^T likewise
 
-    // Workgroup -> (b, kv head, query block, head in group).  Consecutive
-    // workgroup ids go round-robin over the 8 XCDs, so give each XCD one
-    // contiguous slice of the logical order: the G heads of a group and
-    // neighbouring query blocks, which share most of their key blocks, then
-    // meet in the same L2.
-    const int nwg = gridDim.x;
-    int wg = blockIdx.x;
-    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
-    const int g = wg % G;
-    int rest = wg / G;
-    const int i = rest % NB;
-    rest /= NB;
+    // Workgroup -> (b, kv head, query block, head in group).  In time, the whole chip works
+    // through one KV head after the other, so that the K and V^T of the current head (tens of MB)
+    // stay in the memory-side cache; in space, see RowDeal.  All G heads of a group follow each
+    // other, they share most of their key blocks.
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int head_slot = slot / deal.seq_len;            // b * Hkv + kv head
+    const int within = slot % deal.seq_len;
+    const int pos = within / G;                           // position in this XCD's row sequence
+    const int n_single = (deal.n_dense + 7) >> 3;
+    int i;
+    if (pos < n_single) {
+        const int hidx = pos * 8 + xcd;
+        if (hidx >= deal.n_dense) return;                 // the whole workgroup leaves, before any barrier
+        i = NB - 1 - hidx;
+    } else {
+        const int rr = pos - n_single;
+        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
+        if (ridx >= NB - deal.n_dense) return;
+        i = NB - deal.n_dense - 1 - ridx;
+    }
+    const int g = within % G;
     const int Hkv = Hq / G;
-    const int kvh = rest % Hkv;
-    const int b = rest / Hkv;
+    const int kvh = head_slot % Hkv;
+    const int b = head_slot / Hkv;
     const int h = kvh * G + g;
     // ragged batch: this entry's own length; query blocks past it leave (the whole workgroup, before any barrier)
     const int Sb = entry_len(seq_lens, b, S);
     if (i * BS >= Sb) return;
-    const int Skvb = Skv - S + Sb;
+    const int Skv = Skv_max - S + Sb;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
-    const int t16 = lane & 15, dsub = (lane >> 4) & 1;
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
-    const uint16_t* vb = v + b * vs.b + kvh * vs.h;
+    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * NBk) * D * BS;      // K, V, V^T may carry a prefix
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
     const int n_sel = cnt[row_id];
+    const int n_st = n_sel * NSUB;
 
-    // Q^T fragments (B operand): lane holds query row 32*wave + l32, dims 16s + 8*half .. +7.
+    // Direct global->LDS loads: instruction `inst` of a sub-tile fills 1 KB of LDS in lane order
+    // (4 K rows of 256 B or 8 of 128 B, 8 V^T rows of 128 B); the lane picks the global 16-byte chunk whose
+    // swizzled position it is writing.  Per-lane byte offsets are fixed for the whole kernel; the
+    // tile base is wave-uniform, so each load is base (SGPRs) + 32-bit lane offset.
+    uint32_t k_offb[LPW], v_offb[LPW];
+#pragma unroll
+    for (int x = 0; x < LPW; ++x) {
+        const int inst = wave * LPW + x;
+        const int krow = RPI * inst + lane / CPR;
+        const int vrow = 8 * inst + (lane >> 3);
+        k_offb[x] = 2u * ((uint32_t)krow * (uint32_t)ks.t + (uint32_t)(((lane % CPR) ^ swz_k<D>(krow)) << 3));
+        v_offb[x] = 2u * (uint32_t)(vrow * BS + (((lane & 7) ^ swz_v(vrow)) << 3));
+    }
+    // K and V^T sub-tiles are staged separately: K runs one sub-tile ahead of V^T because the
+    // logits are produced two 32-key chunks before the second product consumes them.
+    const uint32_t k_dst = lds_address(&smemK[0][0]) + wave * LPW * 1024;   // this wave's 1-KB slots
+    const uint32_t v_dst = lds_address(&smemV[0][0]) + wave * LPW * 1024;
+    auto issue_k = [&](auto buf_tag, int st, int blk) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        const int sub = st % NSUB;
+        if ((blk + 1) * BS <= Skv) {
+            const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + sub * KT) * ks.t);
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                lds_dma16<BUF * TILE_B + X * 1024>(k_dst, k_offb[X], kt);
+            });
+        } else {
+            // partial last block (only ever the diagonal block of the last query block): key rows past
+            // the end re-read the last token; they are masked for every query that exists
+            const char* kt = reinterpret_cast<const char*>(kb + (int64_t)blk * BS * ks.t);
+            const int last_row = Skv - 1 - blk * BS;
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                const int krow = RPI * (wave * LPW + X) + lane / CPR;
+                int row = sub * KT + krow;
+                if (row > last_row) row = last_row;
+                const uint32_t off = 2u * ((uint32_t)row * (uint32_t)ks.t + (uint32_t)(((lane % CPR) ^ swz_k<D>(krow)) << 3));
+                lds_dma16<BUF * TILE_B + X * 1024>(k_dst, off, kt);
+            });
+        }
+    };
+    auto issue_v = [&](auto buf_tag, int st, int blk) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + (st % NSUB) * KT);
+        static_for<LPW>([&](auto x_tag) {
+            constexpr int X = decltype(x_tag)::value;
+            lds_dma16<BUF * TILE_B + X * 1024>(v_dst, v_offb[X], vtt);
+        });
+    };
+    auto blk_of = [&](int st) {        // key block of sub-tile st (clamped: never read past the list)
+        const int e = st / NSUB;
+        return sel[e < n_sel ? e : n_sel - 1];
+    };
+
+    issue_k(IC<0>{}, 0, sel[0]);
+    issue_v(IC<0>{}, 0, sel[0]);
+    if (n_st > 1) issue_k(IC<1>{}, 1, blk_of(1));
+
+    // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
     bf16x8 qf[DS];
     {
-        // rows past the end of a partial last block read the last token (never stored)
+        // rows past the end of a partial last block read the last token (their results are never stored)
         int qr = 32 * wave + l32;
         if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
         const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
         for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
     }
-
-    f32x16 oacc[DC];
+    // Per-lane LDS byte offsets.  K (A operand of S^T = K Q^T): the lane's key row of chunk 0 and
+    // its 8-dim slice s; chunk 1 and the buffer add constants.  The row assignment swaps bits 2
+    // and 3, see the file header.  V^T (A operand of O^T += V^T P^T): d row l32 (+32 per d tile, a
+    // constant) and the 8-key slice x of the sub-tile.
+    int kofs[DS], vofs[4];
+    {
+        const int row = swap_bits23(l32);
 #pragma unroll
-    for (int dc = 0; dc < DC; ++dc)
+        for (int s = 0; s < DS; ++s) kofs[s] = 2 * (row * D + (((2 * s + half) ^ swz_k<D>(row)) << 3));
+#pragma unroll
+        for (int x = 0; x < 4; ++x) vofs[x] = 2 * (l32 * KT + (((2 * x + half) ^ swz_v(l32)) << 3));
+    }
+    const char* const ldsK = reinterpret_cast<const char*>(&smemK[0][0]);
+    const char* const ldsV = reinterpret_cast<const char*>(&smemV[0][0]);
+    auto lds16 = [](const char* p) { return *reinterpret_cast<const bf16x8*>(p); };
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dc = 0; dc < DT; ++dc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
-    float m_run = -INFINITY;   // running max of the raw (unscaled) logits of this lane's query
-    float l_run = 0.f;         // this lane's half of the running sum of exponentials
+    // Weights are w = 2^(x*c - mcb) with mcb = m_run*c + 7: m_run is the reference maximum (raw
+    // logit) and the 2^-7 bias puts "w >= 2", i.e. "the logit outgrew the reference by 2^8", on
+    // the top exponent bit of the bf16 weight, where one OR over the packed weights finds it.
+    float m_run = -INFINITY;
+    float mcb = 0.f;
+    float l_run = 0.f;           // this lane's half of the running denominator (sum of bf16 weights)
     const float c = scale * 1.44269504088896340736f;
+    const int q_in_blk = 32 * wave + l32;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-    // tile staging: thread -> CPT 16-byte chunks of the K tile and of the V tile
-    uint4 kreg[CPT], vreg[CPT];
-    auto fetch = [&](int blk) {
-        const uint16_t* kt = kb + (int64_t)blk * BS * ks.t;
-        const uint16_t* vt = vb + (int64_t)blk * BS * vs.t;
-        const int last_row = Skvb - 1 - blk * BS;       // >= BS - 1 except in a partial last block
-#pragma unroll
-        for (int p = 0; p < CPT; ++p) {
-            int cidx = p * NT + tid;
-            int row = cidx / (D / 8), col = (cidx % (D / 8)) * 8;
-            if (row > last_row) row = last_row;         // keys past the end: re-read the last token, always masked
-            kreg[p] = *reinterpret_cast<const uint4*>(kt + (int64_t)row * ks.t + col);
-            vreg[p] = *reinterpret_cast<const uint4*>(vt + (int64_t)row * vs.t + col);
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int p = 0; p < CPT; ++p) {
-            int cidx = p * NT + tid;
-            int row = cidx / (D / 8), col = (cidx % (D / 8)) * 8;
-            *reinterpret_cast<uint4*>(&sK[row * LDK + col]) = kreg[p];
-            *reinterpret_cast<uint4*>(&sV[row * LDV + col]) = vreg[p];
-        }
-    };
-
-    fetch(sel[0]);
-    for (int e = 0; e < n_sel; ++e) {
-        __syncthreads();                 // every wave is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (e + 1 < n_sel) fetch(sel[e + 1]);
-
-        // ---- S^T = K Q^T --------------------------------------------------
-        f32x16 sacc[KC];
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kc][r] = 0.f;
-            const uint16_t* krow = &sK[(32 * kc + l32) * LDK + 8 * half];
-#pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + 16 * s);
-                sacc[kc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc[kc], 0, 0, 0);
-            }
-        }
-        // ---- causal mask on the diagonal block (always the last entry) -----
-        if (e == n_sel - 1) {
-            const int qpos = 32 * wave + l32;
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int kpos = 32 * kc + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (kpos > qpos) sacc[kc][r] = -INFINITY;
-                }
-        }
-        // ---- online softmax ------------------------------------------------
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kc][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);            // finite: the diagonal key is always visible
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        const float mc = m_new * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
+    // causal mask inside the diagonal block: register r of a chunk holds key
+    // 64*sub + 32*kc + 16*(r>>3) + 8*half + (r&7) of the block
+    auto mask_diag = [&](f32x16& s, int sub, int kc) {
+        if (KT * sub + 32 * kc + 31 > 32 * wave) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float pv = __builtin_amdgcn_exp2f(fmaf(sacc[kc][r], c, -mc));
-                sacc[kc][r] = pv;
-                psum += pv;
+                const int kpos = KT * sub + 32 * kc + 16 * (r >> 3) + 8 * half + (r & 7);
+                if (kpos > q_in_blk) s[r] = -INFINITY;
             }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        }
+    };
+    auto weights = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        f32x8 e0, e1;
 #pragma unroll
-        for (int dc = 0; dc < DC; ++dc)
+        for (int x = 0; x < 8; ++x) {
+            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
+            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
+        }
+        p0 = __builtin_convertvector(e0, bf16x8);
+        p1 = __builtin_convertvector(e1, bf16x8);
+        lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
+        }
+    };
+    // Slow path: raise the reference maximum to cover the chunk `s`, rescale what has been
+    // accumulated and recompute the chunk's weights.  Rare after the first chunk; wave-uniform.
+    // A lane whose chunk is fully masked keeps its reference (alpha = 1).
+    auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+        mx = fmaxf(mx, other_half(mx));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        m_run = m_new;
+        mcb = m_new * c + 7.0f;
+        l_run *= alpha;
+#pragma unroll
+        for (int dc = 0; dc < DT; ++dc)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
+        weights(s, p0, p1, lsum);
+    };
 
-        // ---- O^T += V^T P^T -------------------------------------------------
+    // The pipeline step n (chunk n = 32 keys) runs three independent chains side by side:
+    //   MFMA   s_nxt = logits of chunk n+2 (same chunk position KC of the next sub-tile, K buffer KB)
+    //   VALU   pn    = weights of chunk n+1 from its logits s_cur (produced by step n-1)
+    //   MFMA   O^T  += V^T(chunk n, V buffer VB) pc^T, pc = weights of chunk n (made by step n-1)
+    // f[0..3]: rotating MFMA A operands, read from LDS three MFMAs ahead of their use.  The NG
+    // operands of a step in MFMA order are K slice 0, V^T (keys 0-15, d tile 0), K slice 1,
+    // V^T (0-15, 1), ..., K slice DS-1, V^T (16-31, DT-1) (head_dim 128: 16 of them, 64: 8).  On
+    // entry f[0..2] hold operands 0..2; a KC = 0 step leaves the first three operands of the KC = 1
+    // step behind.
+    auto step = [&](auto kb_tag, auto vb_tag, auto kc_tag, const f32x16& s_cur, f32x16& s_nxt, const bf16x8& pc0,
+                    const bf16x8& pc1, bf16x8& pn0, bf16x8& pn1, bf16x8 (&f)[4]) {
+        constexpr int KB = decltype(kb_tag)::value, VB = decltype(vb_tag)::value, KC = decltype(kc_tag)::value;
+        const char* const kbase = ldsK + KB * TILE_B + KC * CHUNK_B;
+        const char* const vbase = ldsV + VB * TILE_B;
+        auto operand = [&](auto j_tag) {            // operand j of this step (j < NG) or of the next one
+            constexpr int J = decltype(j_tag)::value;
+            constexpr int j = J % NG;
+            constexpr int kc = KC + J / NG;         // only used with J >= NG when KC == 0
+            const char* const kb2 = ldsK + KB * TILE_B + kc * CHUNK_B;
+            if constexpr (j % 2 == 0) return lds16(kb2 + kofs[j / 2]);
+            else return lds16(vbase + vofs[2 * kc + (j / 2) / DT] + ((j / 2) % DT) * DTILE_B);
+        };
+        (void)kbase;
+        f32x16 zero;
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                f32x8 pf;
-#pragma unroll
-                for (int x = 0; x < 8; ++x) pf[x] = sacc[kc][8 * u + x];
-                bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-                // keys of this 16-key slice held by this lane: base0 + 0..3 and base0 + 8 + 0..3
-                const int key0 = 32 * kc + 16 * u + 4 * half + (t16 >> 2);
-                const uint16_t* v0 = &sV[key0 * LDV + 16 * dsub + 4 * (t16 & 3)];
-                const uint16_t* v1 = v0 + 8 * LDV;
-#pragma unroll
-                for (int dc = 0; dc < DC; ++dc) {
-                    bf16x8 a = lds_read_tr_pair(v0 + 32 * dc, v1 + 32 * dc);
-                    oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[dc], 0, 0, 0);
-                }
+        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+        f32x8 e;
+        float l_new = l_run;
+        uint32_t ovf = 0u;
+        // Group g holds MFMA g of the step, the LDS read of operand g + 3 and a share of the softmax
+        // arithmetic of the chunk's logits: its 16 logits form two halves of 8 (keys 0-15 / 16-31),
+        // each turned into weights over NG / 2 consecutive groups: scaled differences (8 fma), powers
+        // of two (8 exp2), conversion to bf16, denominator and overflow test.
+        auto group = [&](auto g_tag) {
+            constexpr int g = decltype(g_tag)::value;
+            if constexpr (g % 2 == 0) {
+                if constexpr (g == 0) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], zero, 0, 0, 0);
+                else s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], s_nxt, 0, 0, 0);
+            } else {
+                constexpr int dc = (g / 2) % DT;
+                if constexpr (g < NG / 2) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc0, oacc[dc], 0, 0, 0);
+                else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc1, oacc[dc], 0, 0, 0);
             }
+            if constexpr (g + 3 < NG || KC == 0) f[(g + 3) % 4] = operand(IC<g + 3>{});
+            constexpr int HG = NG / 2;               // groups per half of the chunk's 16 logits
+            constexpr int hb = (g / HG) * 8;         // which half
+            constexpr int gg = g % HG;
+            constexpr bool first_half = g < HG;
+            auto scale_sub = [&](int x0, int n) {
+#pragma unroll
+                for (int x = x0; x < x0 + n; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
+            };
+            auto exps = [&](int x0, int n) {
+#pragma unroll
+                for (int x = x0; x < x0 + n; ++x) e[x] = __builtin_amdgcn_exp2f(e[x]);
+            };
+            auto convert = [&]() {
+                if constexpr (first_half) pn0 = __builtin_convertvector(e, bf16x8);
+                else pn1 = __builtin_convertvector(e, bf16x8);
+            };
+            auto sum_and_test = [&]() {
+                const bf16x8 pw = first_half ? pn0 : pn1;
+                const u32x4 bits = __builtin_bit_cast(u32x4, pw);
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
+                ovf |= bits[0] | bits[1] | bits[2] | bits[3];
+                if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
+            };
+            if constexpr (HG == 8) {                 // head_dim 128: 8 groups per half
+                if constexpr (gg < 2) scale_sub(4 * gg, 4);
+                else if constexpr (gg < 6) exps(2 * (gg - 2), 2);
+                else if constexpr (gg == 6) convert();
+                else sum_and_test();
+            } else {                                 // head_dim 64: 4 groups per half
+                static_assert(HG == 4 || HG == 8, "head_dim 64 or 128");
+                if constexpr (gg == 0) scale_sub(0, 8);
+                else if constexpr (gg == 1) exps(0, 4);
+                else if constexpr (gg == 2) exps(4, 4);
+                else { convert(); sum_and_test(); }
+            }
+            SPA_FENCE();
+        };
+        SPA_FENCE();
+        static_for<NG>([&](auto g_tag) { group(g_tag); });
+        // some weight >= 2 (or inf/NaN): the chunk outgrew the reference maximum
+        if (__any((ovf & 0x40004000u) != 0u)) {
+            float lsum;
+            raise_reference(s_cur, pn0, pn1, lsum);
+            l_new = l_run + lsum;
+        }
+        l_run = l_new;
+    };
+
+    // ---- prologue: logits of the two chunks of sub-tile 0, weights of chunk 0 -----------
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+    __syncthreads();
+    f32x16 sA, sB;                                 // logits of even / odd chunks
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sA[r] = 0.f; sB[r] = 0.f; }
+#pragma unroll
+    for (int sidx = 0; sidx < DS; ++sidx) {
+        sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + kofs[sidx]), qf[sidx], sA, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + CHUNK_B + kofs[sidx]), qf[sidx], sB, 0, 0, 0);
+    }
+    bf16x8 pA0, pA1, pB0, pB1;                     // weights of even / odd chunks
+    {
+        if (n_st <= NSUB) mask_diag(sA, 0, 0);     // the only block is the diagonal one
+        float lsum;
+        raise_reference(sA, pA0, pA1, lsum);
+        l_run = lsum;
+    }
+    int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles t+1 and t+2
+
+    // One 64-key sub-tile t = steps 2t and 2t+1.  Reads K(t+1) (look-ahead logits) and V^T(t).
+    auto sub_tile = [&](auto par_tag, auto plain_tag, int t) {
+        constexpr int PAR = decltype(par_tag)::value;      // t % 2
+        constexpr bool PLAIN = decltype(plain_tag)::value != 0;   // far from the end: all loads exist, no masks
+        using KB = IC<1 - PAR>;
+        using VB = IC<PAR>;
+        // K(t+1) and V(t) have been requested; make them visible and retire the previous
+        // sub-tile's readers of the buffers refilled below.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        bf16x8 f[4];
+        f[0] = lds16(ldsK + KB::value * TILE_B + kofs[0]);
+        f[1] = lds16(ldsV + VB::value * TILE_B + vofs[0]);
+        f[2] = lds16(ldsK + KB::value * TILE_B + kofs[1]);
+        if (PLAIN || t + 2 < n_st) issue_k(IC<PAR>{}, t + 2, blk2);
+        if (PLAIN || t + 1 < n_st) issue_v(IC<1 - PAR>{}, t + 1, blk1);
+        blk1 = blk2;
+        blk2 = blk_of(t + 3);
+        // logits about to be turned into weights: chunk 1 of this sub-tile, then chunk 0 of the next
+        if constexpr (!PLAIN)
+            if (t >= n_st - NSUB) mask_diag(sB, t % NSUB, 1);      // the diagonal block is the last of the list
+        step(KB{}, VB{}, IC<0>{}, sB, sA, pA0, pA1, pB0, pB1, f);
+        if constexpr (PLAIN) {
+        } else if (t + 1 >= n_st) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sA[r] = -INFINITY;        // past the end: look-ahead of a stale buffer
+        } else if (t + 1 >= n_st - NSUB) {
+            mask_diag(sA, (t + 1) % NSUB, 0);
+        }
+        step(KB{}, VB{}, IC<1>{}, sA, sB, pB0, pB1, pA0, pA1, f);
+    };
+    // sub-tiles whose two softmaxed chunks lie before the diagonal block and whose loads all exist
+    // run without the mask and end-of-list tests; the last NSUB + 2 (rounded to even) keep them
+    int t = 0;
+    const int t_plain = (n_st - NSUB - 2) & ~1;
+    for (; t < t_plain; t += 2) {
+        sub_tile(IC<0>{}, IC<1>{}, t);
+        sub_tile(IC<1>{}, IC<1>{}, t + 1);
+    }
+    for (;;) {
+        sub_tile(IC<0>{}, IC<0>{}, t);
+        if (++t == n_st) break;
+        sub_tile(IC<1>{}, IC<0>{}, t);
+        if (++t == n_st) break;
     }
 
-    // ---- epilogue: normalise, write O (bf16) and LSE ---------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    // ---- epilogue ----------------------------------------------------------------
+    const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
-    const int qpos = 32 * wave + l32;
-    if (i * BS + qpos >= Sb) return;                     // token past the end of a partial last block
-    uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + qpos) * os.t;
+    if (i * BS + q_in_blk >= Sb) return;                  // token past the end of a partial last block
+    uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
 #pragma unroll
-    for (int dc = 0; dc < DC; ++dc)
+    for (int dc = 0; dc < DT; ++dc)
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
-            typedef __attribute__((ext_vector_type(4))) float f32x4;
             f32x4 o4;
 #pragma unroll
             for (int x = 0; x < 4; ++x) o4[x] = oacc[dc][4 * rq + x] * inv;
-            bf16x4 ob = __builtin_convertvector(o4, bf16x4);
-            *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = ob;
+            *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
         }
     if (lse != nullptr && half == 0)
-        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + qpos] = m_run * scale + __logf(l_tot);
+        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
 }
 
 template <int BS, int D>
 hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* v,
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
-                  hipStream_t st) {
-    int64_t nwg = (int64_t)d.B * d.Hq * d.NB;
-    hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st,
-                       (const uint16_t*)q, qs, (const uint16_t*)k, ks, (const uint16_t*)v, vs, idx, cnt,
-                       (uint16_t*)out, os, lse, d.Hq, d.G, d.NB, d.T, d.S, d.scale, d.shared, d.Skv, d.seq_lens);
+                  void* vt, hipStream_t st) {
+    hipLaunchKernelGGL((transpose_v_kernel<BS, D>), dim3(d.NBk, d.B * d.Hkv), dim3(256), 0, st,
+                       (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt, d.seq_lens, d.S);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const RowDeal deal = deal_rows(d);
+    const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
+    if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
+                       (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                       const void* v, Strides vs, const int32_t* idx, const int32_t* cnt, void* out,
-                       Strides os, float* lse, hipStream_t st) {
-    if (d.Bs == 128 && d.D == 128) return launch<128, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, st);
-    if (d.Bs == 64 && d.D == 128) return launch<64, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, st);
-    if (d.Bs == 128 && d.D == 64) return launch<128, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, st);
-    if (d.Bs == 64 && d.D == 64) return launch<64, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, st);
+                            const void* v, Strides vs, const int32_t* idx, const int32_t* cnt, void* out,
+                            Strides os, float* lse, void* vt, hipStream_t st) {
+    if (vt == nullptr) return hipErrorInvalidValue;
+    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
+    if (d.D == 128 && d.Bs == 64) return launch<64, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
+    if (d.D == 64 && d.Bs == 128) return launch<128, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
+    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
     return hipErrorInvalidValue;
 }
 

@@ -67,12 +67,9 @@ hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, co
                              float* scores_or_null, hipStream_t st);
 hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows,
                                    const int32_t* head_pattern, int32_t* idx, int32_t* cnt, hipStream_t st);
+// vt is scratch for V transposed per block, B*Hkv*NBk*Bs*D bf16.
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
-                       void* out, Strides os, float* lse, hipStream_t st);
-// head_dim 128 fast path; vt is scratch for V transposed per block, B*Hkv*S*D bf16.
-hipError_t launch_attn_d128(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                            const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
-                            void* out, Strides os, float* lse, void* vt, hipStream_t st);
+                       void* out, Strides os, float* lse, void* vt, hipStream_t st);
 
 }  // namespace spa

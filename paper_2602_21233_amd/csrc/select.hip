@@ -218,7 +218,6 @@ __device__ __forceinline__ int wave_sum(int v) {
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-constexpr int kMfmaWaves = 8;   // wavefronts of a score/top-k workgroup unless stated (NWV)
 
 // inclusive prefix sum of v over the 64 lanes (Hillis-Steele inside the rows of 16 with DPP row
 // shifts, then the row totals are carried over with the row broadcasts)
