@@ -93,7 +93,11 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
     float* qp = (float*)((char*)ws + w.qp_off);
     float* kp = (float*)((char*)ws + w.kp_off);
     hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e = launch_pool(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, true, st);
+    // Group-shared lists rank the mean of the group's pooled queries, which needs them in memory; all other
+    // calls pool K only and let the score kernel pool its own query blocks from Q (the Q stream then hides
+    // the scoring and selection)
+    const bool q_in_kernel = !d.shared;
+    hipError_t e = launch_pool(d, q_in_kernel ? nullptr : q, strides_of(p->q_stride), k, strides_of(p->k_stride), qp, kp, true, st);
     if (e != hipSuccess) return SPA_ERR_LAUNCH;
     float* lvn = nullptr;
     if (v_or_null) {
@@ -109,7 +113,8 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
         d.G = 1;
         qp = qg;
     }
-    return launch_code(launch_score_topk(d, qp, kp, k_rows, head_pattern, lvn, block_idx, block_cnt, pooled_scores_or_null, st));
+    return launch_code(launch_score_topk(d, qp, kp, k_rows, head_pattern, lvn, block_idx, block_cnt, pooled_scores_or_null,
+                                         q_in_kernel ? q : nullptr, strides_of(p->q_stride), st));
 }
 
 int topk_impl(const spa_params* p, const float* pooled_scores, const int32_t* k_rows,

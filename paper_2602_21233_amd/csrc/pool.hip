@@ -12,17 +12,6 @@
 namespace spa {
 namespace {
 
-// 16 bytes that will not be read again soon: a non-temporal load keeps them from displacing
-// other data in the caches (measured: 232 -> 220 us for the pooling pass at 131072 tokens)
-__device__ __forceinline__ uint4 stream_load16(const uint16_t* p) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return make_uint4(t[0], t[1], t[2], t[3]);
-}
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
 template <int D, int BS>
 __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ q, Strides qs,
                                                    int n_q_rows /* B*Hq or 0 */, int Hq,

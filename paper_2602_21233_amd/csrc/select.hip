@@ -25,10 +25,23 @@
 //   ascending order, emits static U top-k already sorted.
 // topk_from_scores_kernel applies the same rule to caller-supplied scores (one
 // wavefront per row, keys in LDS).
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace spa {
 namespace {
+
+template <int N>
+using IC_sel = std::integral_constant<int, N>;
+// f(IC_sel<0>{}), ..., f(IC_sel<N-1>{})
+template <int N, typename F>
+__device__ __forceinline__ void static_for_sel(F&& f) {
+    if constexpr (N > 0) {
+        static_for_sel<N - 1>(f);
+        f(IC_sel<N - 1>{});
+    }
+}
 
 // Total order used for ranking: larger score first, -0 == +0, NaN below
 // everything (including -inf).  The +1 keeps 0 free to mean "not a candidate".
@@ -454,6 +467,8 @@ struct ScoreArgs {
     uint32_t gamma_q16;           // cumulative-mass budget in 16-bit fixed point (MASS kernels only)
     const int32_t* seq_lens;      // ragged batch: tokens per batch entry, or nullptr
     int S, Bs;                    // padded query tokens, block size (to turn seq_lens into block counts)
+    const uint16_t* q;            // QPOOL kernels: the queries themselves (pooled in the kernel), layout qs
+    Strides qs;
 };
 
 // Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
@@ -462,7 +477,12 @@ struct ScoreArgs {
 // The split pooled queries (MFMA A operands) are staged in LDS, in the space of the phase-2 counters,
 // instead of being held in 8 * D / 16 registers per lane: the kernel stays within 128 registers.
 // Needs R * D * 4 bytes <= the counters' 8 KB.
-template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV>
+// QPOOL: the workgroup pools its R query blocks from Q itself (the block mean pooling of step 1,
+// same arithmetic in the same order as pool_kernel) instead of reading pooled queries.  Streaming
+// 16 blocks (512 KB) per workgroup with three blocks per 256 threads in flight keeps the HBM busy
+// while the other workgroup of the CU scores and selects: the Q stream, four fifths of the bytes
+// of the select stage, hides the rest of the stage.
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV, bool QPOOL>
 __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
     constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
     constexpr int DS = D / 16;
@@ -493,8 +513,73 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
     // LDS copy of the split queries: the 8 dims 16s + 8 * half .. +7 of row r, part p (0 = hi, 1 = lo)
     // at bf16 offset ((((s * 2 + p) * R + r) * 2 + half) * 8
     __bf16* const qlds = reinterpret_cast<__bf16*>(S + R * LD);
-    {
-        static_assert(R * D * 4 <= NWV * 256 * 4, "staged queries must fit the counters' space");
+    static_assert(R * D * 4 <= NWV * 256 * 4, "staged queries must fit the counters' space");
+    if constexpr (QPOOL) {
+        constexpr int TPR = D / 8, RPP = 256 / TPR;      // lanes per token row, token rows per pass
+        constexpr int NGRP = NWV / 4;                    // groups of 256 threads, one block at a time each
+        constexpr int ROWS = (R + NGRP - 1) / NGRP;      // query blocks per group
+        constexpr int DEPTH = 3;                         // blocks in flight per group
+        // the partial sums live in the score rows' space, or (short rows) behind the counters
+        constexpr bool PART_IN_S = 2 * NGRP * RPP * D <= R * LD;
+        const int t = threadIdx.x, grp = t >> 8, t256 = t & 255;
+        const int prow = t256 / TPR, chunk = t256 % TPR;
+        const int Bs = a.Bs, passes = Bs / RPP;          // at most 8
+        const int Sq_b = entry_len(a.seq_lens, b, a.S);
+        typedef float (*Part)[D];
+        Part const part = reinterpret_cast<Part>(PART_IN_S ? S : S + R * LD + NWV * 256) + grp * 2 * RPP;   // two buffers of RPP rows per group
+        const uint16_t* const qhead = a.q + b * a.qs.b + h * a.qs.h;
+        const int64_t tstride = a.qs.t;
+        // tokens of this group's rr-th block that exist (0: block past the call, the entry or the tile)
+        auto valid_tokens = [&](int rr) {
+            const int r = grp + rr * NGRP, iq = i0 + r;
+            if (r >= R || iq >= NB) return 0;
+            const int n = Sq_b - iq * Bs;
+            return n < 0 ? 0 : (n > Bs ? Bs : n);
+        };
+        uint4 raw[DEPTH][8];
+        auto load = [&](auto slot_tag, int rr) {
+            constexpr int SLOT = decltype(slot_tag)::value;
+            const int nv = valid_tokens(rr);
+            const uint16_t* src = qhead + (int64_t)(i0 + grp + rr * NGRP) * Bs * tstride + chunk * 8;
+#pragma unroll
+            for (int p2 = 0; p2 < 8; ++p2) {
+                raw[SLOT][p2] = make_uint4(0u, 0u, 0u, 0u);
+                if (p2 < passes && p2 * RPP + prow < nv) raw[SLOT][p2] = stream_load16(src + (int64_t)(p2 * RPP + prow) * tstride);
+            }
+        };
+        static_for_sel<(DEPTH < ROWS ? DEPTH : ROWS)>([&](auto rr_tag) { load(rr_tag, decltype(rr_tag)::value); });
+        static_for_sel<ROWS>([&](auto rr_tag) {
+            constexpr int RR = decltype(rr_tag)::value;
+            constexpr int SLOT = RR % DEPTH;
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int p2 = 0; p2 < 8; ++p2) {             // passes beyond the block add exact zeros
+                acc[0] += bf16_lo(raw[SLOT][p2].x); acc[1] += bf16_hi(raw[SLOT][p2].x);
+                acc[2] += bf16_lo(raw[SLOT][p2].y); acc[3] += bf16_hi(raw[SLOT][p2].y);
+                acc[4] += bf16_lo(raw[SLOT][p2].z); acc[5] += bf16_hi(raw[SLOT][p2].z);
+                acc[6] += bf16_lo(raw[SLOT][p2].w); acc[7] += bf16_hi(raw[SLOT][p2].w);
+            }
+            Part const buf = part + (RR & 1) * RPP;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) buf[prow][chunk * 8 + e] = acc[e];
+            if constexpr (RR + DEPTH < ROWS) load(IC_sel<SLOT>{}, RR + DEPTH);
+            __syncthreads();
+            const int r = grp + RR * NGRP;
+            if (t256 < D && r < R) {
+                float sum = 0.f;
+#pragma unroll
+                for (int rr2 = 0; rr2 < RPP; ++rr2) sum += buf[rr2][t256];
+                const int nv = valid_tokens(RR);
+                const float mean = nv == Bs ? sum * (1.0f / (float)Bs) : (nv > 0 ? sum / (float)nv : 0.f);
+                const __bf16 hi = (__bf16)mean;                   // round to nearest even, twice
+                const __bf16 lo = (__bf16)(mean - (float)hi);
+                const int at = ((((t256 >> 4) * 2 + 0) * R + r) * 2 + ((t256 >> 3) & 1)) * 8 + (t256 & 7);
+                qlds[at] = hi;
+                qlds[at + R * 2 * 8] = lo;
+            }
+        });
+        __syncthreads();
+    } else {
         const int t = threadIdx.x;
         if (t < R * DS * 2) {
             const int r = t % R, s2 = (t / R) >> 1, hf = (t / R) & 1;
@@ -658,7 +743,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
 
 // Two workgroups per CU (4 wavefronts per SIMD): at most 128 registers, which is why the query
 // operands are staged in LDS.
-template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV>
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV, bool QPOOL>
 __global__ __launch_bounds__(NWV * 64, 4) void score_topk_mfma_kernel(ScoreArgs a, int n_tiles) {
     extern __shared__ __attribute__((aligned(128))) float S[];   // [R][LD] scores of this workgroup's rows, then 256 counters per wave
     // Workgroup ids go round robin over the 8 XCDs; give each XCD a contiguous slice of the
@@ -667,7 +752,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void score_topk_mfma_kernel(ScoreArgs 
     int wg = blockIdx.x;
     if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
     const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
-    score_topk_rows<D, R, MAXC, EXT, MASS, NWV>(a, wg / n_tiles, tile * R, S);
+    score_topk_rows<D, R, MAXC, EXT, MASS, NWV, QPOOL>(a, wg / n_tiles, tile * R, S);
 }
 
 // Dynamic LDS above the default cap has to be requested per kernel.
@@ -677,9 +762,9 @@ hipError_t allow_lds(const void* kernel, size_t bytes) {
 }
 
 ScoreArgs score_args(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern,
-                     const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null) {
+                     const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null, const void* q, Strides qs) {
     return ScoreArgs{qp, kp, d.Hq, d.G, d.NB, d.NBk, d.off, pattern_of(d), d.k, k_rows, head_pattern, lvn, d.T, d.scale,
-                     idx, cnt, scores_or_null, d.gamma_q16 >= 0 ? (uint32_t)d.gamma_q16 : 0u, d.seq_lens, d.S, d.Bs};
+                     idx, cnt, scores_or_null, d.gamma_q16 >= 0 ? (uint32_t)d.gamma_q16 : 0u, d.seq_lens, d.S, d.Bs, (const uint16_t*)q, qs};
 }
 
 size_t keys_lds_bytes(int NB) { return (size_t)kWaves * (((NB + 63) >> 6) << 6) * sizeof(uint32_t); }
@@ -703,51 +788,60 @@ hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int
     return hipGetLastError();
 }
 
-template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV = (R * (MAXC * 64 + 8) * 4 > 80 * 1024 ? 16 : 8)>
-hipError_t launch_mfma_e(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
-                       int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    constexpr size_t lds = (size_t)R * (MAXC * 64 + 8) * sizeof(float) + NWV * 256 * sizeof(uint32_t);
-    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV>, lds);
+// one call of the score / top-k kernel
+struct ScoreCall {
+    const Dims& d;
+    ScoreArgs a;
+    hipStream_t st;
+};
+
+template <int D, int R, int MAXC, bool EXT, bool MASS, bool QPOOL, int NWV = (R * (MAXC * 64 + 8) * 4 > 80 * 1024 ? 16 : 8)>
+hipError_t launch_mfma_e(const ScoreCall& c) {
+    constexpr size_t part_words = 2 * (NWV / 4) * (256 / (D / 8)) * D;    // partial sums of the in-kernel pooling
+    constexpr size_t lds = ((size_t)R * (MAXC * 64 + 8) + NWV * 256 +
+                            (QPOOL && part_words > (size_t)R * (MAXC * 64 + 8) ? part_words : 0)) * sizeof(float);
+    hipError_t e = allow_lds((const void*)score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV, QPOOL>, lds);
     if (e != hipSuccess) return e;
-    const int n_tiles = (d.NB + R - 1) / R;
-    dim3 grid((unsigned)(n_tiles * d.B * d.Hq));
-    const ScoreArgs a = score_args(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null);
-    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV>), grid, dim3(NWV * 64), lds, st, a, n_tiles);
+    const int n_tiles = (c.d.NB + R - 1) / R;
+    dim3 grid((unsigned)(n_tiles * c.d.B * c.d.Hq));
+    hipLaunchKernelGGL((score_topk_mfma_kernel<D, R, MAXC, EXT, MASS, NWV, QPOOL>), grid, dim3(NWV * 64), lds, c.st, c.a, n_tiles);
     return hipGetLastError();
 }
 
+template <int D, int R, int MAXC, bool EXT, bool MASS>
+hipError_t launch_mfma_q(const ScoreCall& c) {
+    if (c.a.q != nullptr) return launch_mfma_e<D, R, MAXC, EXT, MASS, true>(c);
+    return launch_mfma_e<D, R, MAXC, EXT, MASS, false>(c);
+}
+
 template <int D, int R, int MAXC>
-hipError_t launch_mfma(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
-                       int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
-    const bool mass = d.gamma_q16 >= 0;
-    if (extended(d)) {
-        if (mass) return launch_mfma_e<D, R, MAXC, true, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-        return launch_mfma_e<D, R, MAXC, true, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    }
-    if (mass) return launch_mfma_e<D, R, MAXC, false, true>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma_e<D, R, MAXC, false, false>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+hipError_t launch_mfma(const ScoreCall& c) {
+    const bool mass = c.d.gamma_q16 >= 0;
+    if (extended(c.d)) return mass ? launch_mfma_q<D, R, MAXC, true, true>(c) : launch_mfma_q<D, R, MAXC, true, false>(c);
+    return mass ? launch_mfma_q<D, R, MAXC, false, true>(c) : launch_mfma_q<D, R, MAXC, false, false>(c);
 }
 
 template <int D>
-hipError_t launch_mfma_d(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern, const float* lvn,
-                         int32_t* idx, int32_t* cnt, float* scores_or_null, hipStream_t st) {
+hipError_t launch_mfma_d(const ScoreCall& c) {
     // rows per workgroup shrink as rows get longer: up to 1024 blocks R * (NB padded) fp32 scores stay
     // within 66 KB of LDS, so that two 8-wave workgroups share a CU (measured at 131072 tokens:
     // 125 -> 106 us against 32 rows with one 8-wave workgroup per CU)
-    if (d.NBk <= 256) return launch_mfma<D, 16, 4>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 512) return launch_mfma<D, 16, 8>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.NBk <= 1024) return launch_mfma<D, 16, 16>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    const int NBk = c.d.NBk;
+    if (NBk <= 256) return launch_mfma<D, 16, 4>(c);
+    if (NBk <= 512) return launch_mfma<D, 16, 8>(c);
+    if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
     // 1025 .. 2048 blocks: 16 rows (131 KB) by one 16-wave workgroup per CU, same occupancy and half the
     // re-reads of the pooled K against 8 rows by two 8-wave workgroups (0.99 -> 0.95 ms at 262144 tokens)
-    if (d.NBk <= 2048) return launch_mfma<D, 16, 32>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    return launch_mfma<D, 4, 64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+    if (NBk <= 2048) return launch_mfma<D, 16, 32>(c);
+    return launch_mfma<D, 4, 64>(c);
 }
 
 hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows,
                              const int32_t* head_pattern, const float* lvn, int32_t* idx, int32_t* cnt, float* scores_or_null,
-                             hipStream_t st) {
-    if (d.D == 128) return launch_mfma_d<128>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
-    if (d.D == 64) return launch_mfma_d<64>(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, st);
+                             const void* q, Strides qs, hipStream_t st) {
+    const ScoreCall c{d, score_args(d, qp, kp, k_rows, head_pattern, lvn, idx, cnt, scores_or_null, q, qs), st};
+    if (d.D == 128) return launch_mfma_d<128>(c);
+    if (d.D == 64) return launch_mfma_d<64>(c);
     return hipErrorInvalidValue;
 }
 
