@@ -518,7 +518,7 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         constexpr int TPR = D / 8, RPP = 256 / TPR;      // lanes per token row, token rows per pass
         constexpr int NGRP = NWV / 4;                    // groups of 256 threads, one block at a time each
         constexpr int ROWS = (R + NGRP - 1) / NGRP;      // query blocks per group
-        constexpr int DEPTH = 3;                         // blocks in flight per group
+        constexpr int DEPTH = 2;                         // blocks in flight per group
         // the partial sums live in the score rows' space, or (short rows) behind the counters
         constexpr bool PART_IN_S = 2 * NGRP * RPP * D <= R * LD;
         const int t = threadIdx.x, grp = t >> 8, t256 = t & 255;
@@ -536,48 +536,76 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
             const int n = Sq_b - iq * Bs;
             return n < 0 ? 0 : (n > Bs ? Bs : n);
         };
-        uint4 raw[DEPTH][8];
-        auto load = [&](auto slot_tag, int rr) {
-            constexpr int SLOT = decltype(slot_tag)::value;
-            const int nv = valid_tokens(rr);
-            const uint16_t* src = qhead + (int64_t)(i0 + grp + rr * NGRP) * Bs * tstride + chunk * 8;
+        // One instantiation per number of passes (block size / token rows per pass) and per kind of
+        // tile.  FULL: every block of the tile exists and is whole, so all loads are unconditional: the
+        // compiler can then wait for exactly the block it is about to reduce while the next two stay in
+        // flight (with a conditional load anywhere in the loop it waits for all of them, and a
+        // workgroup streams at a third of the rate).  Otherwise (last tile of a sequence) rows are
+        // predicated; that path is rare and not tuned.
+        auto pool_rows = [&](auto passes_tag, auto full_tag) {
+            constexpr int PASSES = decltype(passes_tag)::value;
+            constexpr bool FULL = decltype(full_tag)::value != 0;
+            uint4 raw[DEPTH][PASSES];
+            // per-lane byte offsets inside a block (fixed for the kernel; token stride <= 2^22 elements,
+            // so they fit 32 bits) on top of a wave-uniform block base
+            uint32_t voff[PASSES];
 #pragma unroll
-            for (int p2 = 0; p2 < 8; ++p2) {
-                raw[SLOT][p2] = make_uint4(0u, 0u, 0u, 0u);
-                if (p2 < passes && p2 * RPP + prow < nv) raw[SLOT][p2] = stream_load16(src + (int64_t)(p2 * RPP + prow) * tstride);
-            }
+            for (int p2 = 0; p2 < PASSES; ++p2) voff[p2] = 2u * ((uint32_t)(p2 * RPP + prow) * (uint32_t)tstride + (uint32_t)chunk * 8u);
+            const int grp_u = __builtin_amdgcn_readfirstlane(grp);
+            auto load = [&](auto slot_tag, int rr) {
+                constexpr int SLOT = decltype(slot_tag)::value;
+                const char* const base = reinterpret_cast<const char*>(qhead + (int64_t)(i0 + grp_u + rr * NGRP) * Bs * tstride);
+                const int nv = FULL ? Bs : valid_tokens(rr);
+#pragma unroll
+                for (int p2 = 0; p2 < PASSES; ++p2) {
+                    if constexpr (FULL) {
+                        raw[SLOT][p2] = stream_load16(reinterpret_cast<const uint16_t*>(base + voff[p2]));
+                    } else {
+                        raw[SLOT][p2] = make_uint4(0u, 0u, 0u, 0u);
+                        if (p2 * RPP + prow < nv) raw[SLOT][p2] = stream_load16(reinterpret_cast<const uint16_t*>(base + voff[p2]));
+                    }
+                }
+            };
+            static_for_sel<(DEPTH < ROWS ? DEPTH : ROWS)>([&](auto rr_tag) { load(rr_tag, decltype(rr_tag)::value); });
+            static_for_sel<ROWS>([&](auto rr_tag) {
+                constexpr int RR = decltype(rr_tag)::value;
+                constexpr int SLOT = RR % DEPTH;
+                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int p2 = 0; p2 < PASSES; ++p2) {
+                    acc[0] += bf16_lo(raw[SLOT][p2].x); acc[1] += bf16_hi(raw[SLOT][p2].x);
+                    acc[2] += bf16_lo(raw[SLOT][p2].y); acc[3] += bf16_hi(raw[SLOT][p2].y);
+                    acc[4] += bf16_lo(raw[SLOT][p2].z); acc[5] += bf16_hi(raw[SLOT][p2].z);
+                    acc[6] += bf16_lo(raw[SLOT][p2].w); acc[7] += bf16_hi(raw[SLOT][p2].w);
+                }
+                Part const buf = part + (RR & 1) * RPP;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) buf[prow][chunk * 8 + e] = acc[e];
+                if constexpr (RR + DEPTH < ROWS) load(IC_sel<SLOT>{}, RR + DEPTH);
+                __syncthreads();
+                const int r = grp + RR * NGRP;
+                if (t256 < D && r < R) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int rr2 = 0; rr2 < RPP; ++rr2) sum += buf[rr2][t256];
+                    const int nv = FULL ? Bs : valid_tokens(RR);
+                    const float mean = nv == Bs ? sum * (1.0f / (float)Bs) : (nv > 0 ? sum / (float)nv : 0.f);
+                    const __bf16 hi = (__bf16)mean;                   // round to nearest even, twice
+                    const __bf16 lo = (__bf16)(mean - (float)hi);
+                    const int at = ((((t256 >> 4) * 2 + 0) * R + r) * 2 + ((t256 >> 3) & 1)) * 8 + (t256 & 7);
+                    qlds[at] = hi;
+                    qlds[at + R * 2 * 8] = lo;
+                }
+            });
         };
-        static_for_sel<(DEPTH < ROWS ? DEPTH : ROWS)>([&](auto rr_tag) { load(rr_tag, decltype(rr_tag)::value); });
-        static_for_sel<ROWS>([&](auto rr_tag) {
-            constexpr int RR = decltype(rr_tag)::value;
-            constexpr int SLOT = RR % DEPTH;
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int p2 = 0; p2 < 8; ++p2) {             // passes beyond the block add exact zeros
-                acc[0] += bf16_lo(raw[SLOT][p2].x); acc[1] += bf16_hi(raw[SLOT][p2].x);
-                acc[2] += bf16_lo(raw[SLOT][p2].y); acc[3] += bf16_hi(raw[SLOT][p2].y);
-                acc[4] += bf16_lo(raw[SLOT][p2].z); acc[5] += bf16_hi(raw[SLOT][p2].z);
-                acc[6] += bf16_lo(raw[SLOT][p2].w); acc[7] += bf16_hi(raw[SLOT][p2].w);
-            }
-            Part const buf = part + (RR & 1) * RPP;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) buf[prow][chunk * 8 + e] = acc[e];
-            if constexpr (RR + DEPTH < ROWS) load(IC_sel<SLOT>{}, RR + DEPTH);
-            __syncthreads();
-            const int r = grp + RR * NGRP;
-            if (t256 < D && r < R) {
-                float sum = 0.f;
-#pragma unroll
-                for (int rr2 = 0; rr2 < RPP; ++rr2) sum += buf[rr2][t256];
-                const int nv = valid_tokens(RR);
-                const float mean = nv == Bs ? sum * (1.0f / (float)Bs) : (nv > 0 ? sum / (float)nv : 0.f);
-                const __bf16 hi = (__bf16)mean;                   // round to nearest even, twice
-                const __bf16 lo = (__bf16)(mean - (float)hi);
-                const int at = ((((t256 >> 4) * 2 + 0) * R + r) * 2 + ((t256 >> 3) & 1)) * 8 + (t256 & 7);
-                qlds[at] = hi;
-                qlds[at + R * 2 * 8] = lo;
-            }
-        });
+        // whole tile inside the call, the entry and (rows per group) the tile: every block is full
+        const bool full = R % NGRP == 0 && (int64_t)(i0 + R) * Bs <= (int64_t)Sq_b;
+        constexpr int P128 = 128 / RPP, P64 = 64 / RPP;  // passes for blocks of 128 / 64 tokens
+        if (passes == P128) {
+            if (full) pool_rows(IC_sel<P128>{}, IC_sel<1>{}); else pool_rows(IC_sel<P128>{}, IC_sel<0>{});
+        } else {
+            if (full) pool_rows(IC_sel<P64>{}, IC_sel<1>{}); else pool_rows(IC_sel<P64>{}, IC_sel<0>{});
+        }
         __syncthreads();
     } else {
         const int t = threadIdx.x;
