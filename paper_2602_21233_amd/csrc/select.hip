@@ -449,6 +449,78 @@ __device__ int mass_budget_row(ScoreFn score, int i, const Pattern& pt, uint32_t
     return n_above + (int)((need + w_tau - 1u) / w_tau);
 }
 
+// The same budget for a row whose keys already sit in registers (the select kernel): the weights are
+// computed once per block, the weighted radix passes run over registers.  key[m] / is_static_bits
+// as in the select kernel (block 64 m + lane; 0 = not a candidate); score(j) returns the ranking
+// score of block j; chunks = chunks of 64 blocks the row reaches.  Integer arithmetic: the result is
+// the one mass_budget_row gives, whatever the order of the sums.
+template <int MAXC, typename ScoreFn>
+__device__ __forceinline__ int mass_budget_regs(const uint32_t (&key)[MAXC], uint64_t is_static_bits, ScoreFn score, int i,
+                                                int chunks, uint32_t gamma_q16, uint32_t* hist, int lane) {
+    float x[MAXC];
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int m = 0; m < MAXC; ++m) {
+        x[m] = -INFINITY;
+        if (m < chunks) {
+            const int j = (m << 6) + lane;
+            x[m] = j <= i ? score(j) : __builtin_nanf("");   // NaN: weighs nothing, never the maximum
+            if (x[m] == x[m] && x[m] > mloc) mloc = x[m];
+        }
+    }
+    const uint32_t mk = wave_max_u32(rank_key(mloc));
+    const float mx = mk >= 2u ? score_of_key(mk) : -INFINITY;
+    uint32_t w[MAXC];
+    int z_l = 0, ms_l = 0;
+#pragma unroll
+    for (int m = 0; m < MAXC; ++m) {
+        w[m] = 0u;
+        if (m < chunks) {
+            w[m] = mass_weight(x[m], mx);
+            z_l += (int)w[m];
+            if ((is_static_bits >> m) & 1ull) ms_l += (int)w[m];
+        }
+    }
+    const uint32_t Z = (uint32_t)wave_sum(z_l), Ms = (uint32_t)wave_sum(ms_l);
+    const uint32_t target = (uint32_t)(((uint64_t)gamma_q16 * Z + 65535ull) >> 16);
+    if (Ms >= target) return 0;
+    uint32_t need = target - Ms;
+    uint32_t prefix = 0u;
+#pragma nounroll
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        *reinterpret_cast<uint4*>(hist + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+        for (int m = 0; m < MAXC; ++m) {
+            const uint32_t kv = key[m];
+            if (m < chunks && kv != 0u && w[m] != 0u && (((kv ^ prefix) >> shift) >> 8) == 0u)
+                atomicAdd(&hist[(kv >> shift) & 255u], w[m]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint4 h = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // .w = bin 255-4l ... .x = bin 252-4l
+        const int own = (int)(h.x + h.y + h.z + h.w);
+        const int incl = wave_inclusive_scan(own);
+        const int Ln = __ffsll((unsigned long long)__ballot((uint32_t)incl >= need)) - 1;
+        const uint32_t before = (uint32_t)__builtin_amdgcn_readlane(incl - own, Ln);
+        const uint32_t b3 = (uint32_t)__builtin_amdgcn_readlane((int)h.w, Ln), b2 = (uint32_t)__builtin_amdgcn_readlane((int)h.z, Ln);
+        const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane((int)h.y, Ln);
+        const uint32_t rem = need - before;
+        uint32_t digit, above;
+        if (rem <= b3) { digit = 255 - 4 * Ln; above = 0; }
+        else if (rem <= b3 + b2) { digit = 254 - 4 * Ln; above = b3; }
+        else if (rem <= b3 + b2 + b1) { digit = 253 - 4 * Ln; above = b3 + b2; }
+        else { digit = 252 - 4 * Ln; above = b3 + b2 + b1; }
+        need = rem - above;
+        prefix |= digit << shift;
+    }
+    int n_above_l = 0;
+#pragma unroll
+    for (int m = 0; m < MAXC; ++m) n_above_l += (m < chunks && key[m] > prefix) ? 1 : 0;
+    const int n_above = wave_sum(n_above_l);
+    const uint32_t w_tau = mass_weight(score_of_key(prefix), mx);
+    return n_above + (int)((need + w_tau - 1u) / w_tau);
+}
+
 // Everything the score + top-k step of one workgroup needs besides its rows.
 struct ScoreArgs {
     const float* qp;              // pooled Q [B*Hq, NB, D] fp32
@@ -734,7 +806,11 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         int k_i = row_budget(k_rows, iq, k);
         uint32_t* hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
         if constexpr (MASS) {                             // the mass budget on top of the count budgets
-            const int k_m = mass_budget_row<EXT>([&](int j) { return srow[j]; }, i, pt, a.gamma_q16, hist, lane);
+            int k_m;                                      // rows of up to 2048 blocks: weights kept in registers
+            if constexpr (MAXC <= 32)
+                k_m = mass_budget_regs<MAXC>(key, is_static_bits, [&](int j) { return srow[j]; }, i, chunks, a.gamma_q16, hist, lane);
+            else
+                k_m = mass_budget_row<EXT>([&](int j) { return srow[j]; }, i, pt, a.gamma_q16, hist, lane);
             k_i = k_m < k_i ? k_m : k_i;
         }
         const int kk = k_i < n_cand ? k_i : n_cand;
