@@ -934,9 +934,9 @@ hipError_t launch_mfma_d(const ScoreCall& c) {
     if (NBk <= 256) return launch_mfma<D, 16, 4>(c);
     if (NBk <= 512) return launch_mfma<D, 16, 8>(c);
     if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
-    // 1025 .. 2048 blocks: 16 rows (131 KB) by one 16-wave workgroup per CU, same occupancy and half the
-    // re-reads of the pooled K against 8 rows by two 8-wave workgroups (0.99 -> 0.95 ms at 262144 tokens)
-    if (NBk <= 2048) return launch_mfma<D, 16, 32>(c);
+    // 1025 .. 2048 blocks: 8 rows, still two workgroups per CU, so that one can stream its queries while the
+    // other scores (0.84 -> 0.81 ms at 262144 tokens against 16 rows by one 16-wave workgroup per CU)
+    if (NBk <= 2048) return launch_mfma<D, 8, 32>(c);
     return launch_mfma<D, 4, 64>(c);
 }
 
