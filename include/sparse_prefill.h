@@ -127,8 +127,8 @@ int spa_row_capacity(const spa_params *p, int32_t *row_capacity);
 
 /* Bytes of device scratch that the select, attn and fused calls (all variants)
  * need in `ws` (pooled Q and K; the block lists of a fused call whose caller
- * does not ask for them; the value norms of the output-aware calls; for
- * head_dim 128 a per-block transposed copy of V).  One size serves every call.
+ * does not ask for them; the value norms of the output-aware calls; a per-block
+ * transposed copy of V).  One size serves every call.
  * Host only. */
 int spa_workspace_bytes(const spa_params *p, size_t *bytes);
 

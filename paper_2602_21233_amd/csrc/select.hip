@@ -3,26 +3,34 @@
 // budget of Sec. 4.1.2 Fig. "Stem" (a) or the per-query-block budget schedule of
 // Token Position-Decay, Fig. "Stem" (b); optional value-magnitude term of the
 // Output-Aware Metric, Fig. "Stem" (c); static patterns of Sec. 4.1.1: A-shape,
-// Strided, Dilated, Tri-shape; optional per-head settings and a KV prefix).
+// Strided, Dilated, Tri-shape; optional per-head settings, a KV prefix, ragged
+// batches and a cumulative-mass budget).
 //
-// score_topk_mfma_kernel: one 512-thread workgroup owns R consecutive query
-// blocks of one query head.
+// score_topk_mfma_kernel: one workgroup (512 threads; two per CU) owns R consecutive
+// query blocks of one query head.
+//   Phase 0 - query pooling (step 1 for Q, in the kernel).  The workgroup streams its R
+//   query blocks from Q and pools them itself, so that the Q stream of the select stage
+//   (four fifths of its bytes) runs while other workgroups score and select; the split
+//   pooled queries go straight to LDS.  (Group-shared lists read pooled queries from
+//   memory instead.)
 //   Phase 1 - scores on the matrix cores.  The fp32 pooled vectors are split
 //   into a bf16 head and a bf16 tail (x = hi + lo, |x - hi - lo| <= 2^-18 |x|)
 //   and each 32x32 tile of Qp Kp^T is accumulated in fp32 from three
 //   v_mfma_f32_32x32x16_bf16 products (hi.hi + hi.lo + lo.hi); the dropped
-//   lo.lo term is below 2^-17 of a product.  The 8 wavefronts take the key-block
+//   lo.lo term is below 2^-17 of a product.  The wavefronts take the key-block
 //   tiles round robin, reading Kp straight from L2 in operand layout.  The scores
 //   of the R rows stay in LDS; the NB x NB matrix never exists in memory unless
 //   the caller asks for it.
 //   Phase 2 - exact selection.  A wavefront owns a row: lane l holds the keys of
-//   blocks l, l+64, ... in registers as order-preserving uint32, finds the k-th
-//   largest by radix selection, 8 bits per pass (the wavefront histograms the
-//   current digit into 256 LDS counters, a prefix sum over the lanes finds the
-//   bin of the wanted rank; only the chunks a causal row can fill are visited,
-//   a pass that takes its whole bin ends early), resolves ties at the threshold by block index
-//   with a running prefix count, and, because the last pass walks the blocks in
-//   ascending order, emits static U top-k already sorted.
+//   blocks l, l+64, ... in registers as order-preserving uint32 and finds the k-th
+//   largest in two steps: a bound from the lanes (the smallest of the 64 lanes' largest
+//   keys is reached by at least 64 keys), below which keys drop out, then radix
+//   selection among the rest, 8 bits per pass (the wavefront histograms the current
+//   digit into 256 LDS counters, a prefix sum over the lanes finds the bin of the wanted
+//   rank; a pass that takes its whole bin ends early).  Ties at the threshold are
+//   resolved by block index with a running prefix count, and static U top-k is written
+//   in ascending order from the keys in registers.  With a cumulative-mass budget a
+//   weighted variant of the same search first finds how many blocks the row may take.
 // topk_from_scores_kernel applies the same rule to caller-supplied scores (one
 // wavefront per row, keys in LDS).
 #include <type_traits>
