@@ -510,6 +510,27 @@ def test_attn_strided_views(spa, oracle):
     _assert_attn_close(out, want)
     sidx, scnt = spa.select(dq[:, :, :4].permute(0, 2, 1, 3), dq[:, :, 4:6].permute(0, 2, 1, 3), Bs, 1, 2, 1)
     assert torch.equal(scnt.cpu(), cnt)
+    cidx, ccnt = spa.select(q.contiguous().cuda(), k.contiguous().cuda(), Bs, 1, 2, 1)
+    assert torch.equal(sidx, cidx) and torch.equal(scnt, ccnt)           # strides do not change the selection
+
+
+@pytest.mark.parametrize("NB,D,Bs", [(40, 128, 128), (37, 64, 64)])
+def test_select_strided_views_long(spa, oracle, NB, D, Bs):
+    """Token-major packed QKV (token stride = heads * head_dim): whole tiles of 16 query blocks
+    take the unconditional-load path of the in-kernel pooling; the lists equal those of contiguous copies."""
+    g = torch.Generator().manual_seed(NB)
+    qkv = torch.randn((2, NB * Bs + 17, 4 + 2, D), generator=g).to(torch.bfloat16).cuda()
+    q = qkv[:, :, :4].permute(0, 2, 1, 3)
+    k = qkv[:, :, 4:].permute(0, 2, 1, 3)
+    sidx, scnt, ssp = spa.select(q, k, Bs, 1, 2, 5, return_scores=True)
+    cidx, ccnt, csp = spa.select(q.contiguous(), k.contiguous(), Bs, 1, 2, 5, return_scores=True)
+    assert torch.equal(sidx, cidx) and torch.equal(scnt, ccnt) and torch.equal(ssp, csp)
+    g_idx, g_cnt = oracle.topk(ssp.cpu(), 1, 2, 5)
+    assert torch.equal(sidx.cpu(), g_idx) and torch.equal(scnt.cpu(), g_cnt)
+    o_sp = oracle.select(q.contiguous().cpu(), k.contiguous().cpu(), Bs, 1, 2, 5)[2]
+    n = ssp.shape[-1]
+    tri = torch.tril(torch.ones(n, n, dtype=torch.bool))
+    torch.testing.assert_close(ssp.cpu()[..., tri], o_sp[..., tri], rtol=1e-4, atol=1e-5)
 
 
 # ---------------------------------------------------------------- fused
