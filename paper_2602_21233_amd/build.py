@@ -7,8 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparse_prefill.so")
-SOURCES = ("api.hip", "pool.hip", "select.hip", "attn.hip")
-HEADERS = ("common.hpp", os.path.join("..", "..", "include", "sparse_prefill.h"))
+SOURCES = ("api.hip", "pool.hip", "select.hip", "select_d128.hip", "select_d64.hip", "attn.hip")
+HEADERS = ("common.hpp", "select_impl.hpp", os.path.join("..", "..", "include", "sparse_prefill.h"))
 
 # The attention kernel never produces NaN from finite inputs; telling the compiler so
 # removes the NaN-quieting v_max x,x pairs it otherwise puts around every fmaxf.
