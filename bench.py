@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1200)
+    ap.add_argument("--cold", action="store_true",
+                    help="overwrite a 1-GiB scratch buffer before every step (cold caches; for the small "
+                         "workloads); ms_per_step then comes from the events, not the wall clock")
     ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared", "mass"),
                     default="uniform")
     args = ap.parse_args()
@@ -123,9 +126,13 @@ def main():
 
     pattern = (ns, nl, tk, pat_kw.get("stride_blocks", 0), pat_kw.get("n_dense_q_blocks", 0))
 
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda") if args.cold else None
+
     def step(events=None):
         # the same three launches sparse_prefill_fused makes, split so that the
         # attention kernel can be bracketed by events on its own stream
+        if flush is not None:
+            flush.fill_(1)
         if events:
             events[0].record()
         idx, cnt = spa.select(dq, dk, Bs, ns, nl, tk, workspace=ws, **sel_kw, **pat_kw)
@@ -146,9 +153,25 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
+    if args.cold:
+        ms_step = sum(e[0].elapsed_time(e[2]) for e in evs) / args.steps
     sel_ms = sorted(e[0].elapsed_time(e[1]) for e in evs)
     att_ms = sorted(e[1].elapsed_time(e[2]) for e in evs)
     sel_avg, att_avg = sum(sel_ms) / len(sel_ms), sum(att_ms) / len(att_ms)
+
+    # the one-call entry point (select + attention in one C call), timed the same way
+    fused_ms = None
+    if args.variant == "uniform":
+        fev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        for a, b in fev:
+            if flush is not None:
+                flush.fill_(1)
+            a.record()
+            spa.fused(dq, dk, dv, Bs, ns, nl, tk, workspace=ws, out=out)
+            b.record()
+        torch.cuda.synchronize()
+        f = sorted(a.elapsed_time(b) for a, b in fev)
+        fused_ms = {"avg": sum(f) / len(f), "p10": f[len(f) // 10], "p50": f[len(f) // 2], "p90": f[(len(f) * 9) // 10]}
 
     # the output-aware score reads V once more (2 bytes per element)
     select_bytes = w.select_bytes + (2 * w.batch * w.n_kv_heads * w.seq_len * w.head_dim if args.variant == "stem" else 0)
@@ -170,10 +193,11 @@ def main():
                       "p90": sel_ms[(len(sel_ms) * 9) // 10]},
         "attn_ms": {"avg": att_avg, "p10": att_ms[len(att_ms) // 10], "p50": att_ms[len(att_ms) // 2],
                     "p90": att_ms[(len(att_ms) * 9) // 10]},
+        "fused_ms": fused_ms, "caches": "cold" if args.cold else "warm",
         "select_hbm": {"achieved": select_bytes / (sel_avg * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                        "frac": select_bytes / (sel_avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "bytes": select_bytes},
-        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128,128>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": f"attn_kernel<{Bs},{w.head_dim}>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": read_traffic_note("attn_kernel"), "traffic_unit": "bytes/launch",
                      "timed": "events around sparse_prefill_attn on its stream: the attention kernel plus the "
