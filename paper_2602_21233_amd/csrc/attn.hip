@@ -19,10 +19,10 @@
 //   * K rows are assigned to MFMA rows with bits 2 and 3 of the row index
 //     swapped; the logits a lane ends up holding are then 8 consecutive keys per
 //     16-key slice, which is exactly the B-operand order of the second product.
-//   * no running maximum: weights are 2^(x*c - m*c - 7) against a reference m that is only
-//     raised when some weight reaches 2 (the logit outgrew m by 2^8), which shows as the top
-//     exponent bit of the bf16 weight; the final normalisation makes the result independent
-//     of m.
+//   * no running maximum: weights are 2^(x*c - m*c) against a reference m that is only moved
+//     when a query's running denominator passes 2^40 (one compare per step); the final
+//     normalisation makes the result independent of m, and floating point keeps the relative
+//     precision of weights and sums at any magnitude in between.
 //   * a step (32 keys) overlaps three chains: logits of chunk n+2 (MFMA), weights of chunk
 //     n+1 (VALU), O^T += V^T P^T of chunk n (MFMA); its instruction order is fixed by hand.
 #include <type_traits>
@@ -314,15 +314,18 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     for (int dc = 0; dc < DT; ++dc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
-    // Weights are w = 2^(x*c - mcb) with mcb = m_run*c + 7: m_run is the reference maximum (raw
-    // logit) and the 2^-7 bias puts "w >= 2", i.e. "the logit outgrew the reference by 2^8", on
-    // the top exponent bit of the bf16 weight, where one OR over the packed weights finds it.
+    // Weights are w = 2^(x*c - mcb) with mcb = m_run*c, m_run a reference logit (raw).  The reference
+    // need not be the running maximum: a common factor 2^-mcb cancels between numerator and
+    // denominator, and bf16 weights and fp32 sums keep their relative precision at any magnitude.
+    // All it has to do is keep the numbers inside the fp32 range, so it is only moved when the
+    // running denominator (which bounds every weight so far) passes kRescaleAt.
     float m_run = -INFINITY;
     float mcb = 0.f;
     float l_run = 0.f;           // this lane's half of the running denominator (sum of bf16 weights)
     const float c = scale * 1.44269504088896340736f;
     const int q_in_blk = 32 * wave + l32;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
 
     // causal mask inside the diagonal block: register r of a chunk holds key
     // 64*sub + 32*kc + 16*(r>>3) + 8*half + (r&7) of the block
@@ -351,18 +354,20 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
             lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
         }
     };
-    // Slow path: raise the reference maximum to cover the chunk `s`, rescale what has been
-    // accumulated and recompute the chunk's weights.  Rare after the first chunk; wave-uniform.
-    // A lane whose chunk is fully masked keeps its reference (alpha = 1).
+    // Slow path: move the reference so that the chunk `s` has weights <= 1 and the denominator so
+    // far is about 1 or less, rescale what has been accumulated and recompute the chunk's weights.
+    // Always taken on the first chunk, almost never after; wave-uniform.
     auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
         float mx = fmaxf(s[0], s[1]);
 #pragma unroll
         for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
         mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m_run, mx);
+        const float lq = l_run + other_half(l_run);          // this query's denominator so far
+        const float lift = lq > 1.0f ? __log2f(lq) / c : 0.0f;
+        const float m_new = fmaxf(m_run + lift, mx);
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
         m_run = m_new;
-        mcb = m_new * c + 7.0f;
+        mcb = m_new * c;
         l_run *= alpha;
 #pragma unroll
         for (int dc = 0; dc < DT; ++dc)
@@ -399,11 +404,10 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
         for (int r = 0; r < 16; ++r) zero[r] = 0.f;
         f32x8 e;
         float l_new = l_run;
-        uint32_t ovf = 0u;
         // Group g holds MFMA g of the step, the LDS read of operand g + 3 and a share of the softmax
         // arithmetic of the chunk's logits: its 16 logits form two halves of 8 (keys 0-15 / 16-31),
         // each turned into weights over NG / 2 consecutive groups: scaled differences (8 fma), powers
-        // of two (8 exp2), conversion to bf16, denominator and overflow test.
+        // of two (8 exp2), conversion to bf16, denominator.
         auto group = [&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
             if constexpr (g % 2 == 0) {
@@ -433,11 +437,9 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
             };
             auto sum_and_test = [&]() {
                 const bf16x8 pw = first_half ? pn0 : pn1;
-                const u32x4 bits = __builtin_bit_cast(u32x4, pw);
 #pragma unroll
                 for (int x = 0; x < 4; ++x)
                     l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
-                ovf |= bits[0] | bits[1] | bits[2] | bits[3];
                 if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
             };
             if constexpr (HG == 8) {                 // head_dim 128: 8 groups per half
@@ -456,8 +458,11 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
         };
         SPA_FENCE();
         static_for<NG>([&](auto g_tag) { group(g_tag); });
-        // some weight >= 2 (or inf/NaN): the chunk outgrew the reference maximum
-        if (__any((ovf & 0x40004000u) != 0u)) {
+        // The weights are positive, so the running denominator bounds every one of them: while it
+        // stays below kRescaleAt no weight, and no sum of weights times values, can leave the fp32
+        // range, and bf16 / fp32 keep their relative precision at any magnitude.  Beyond it (or
+        // inf / NaN) the chunk has outgrown the reference maximum by far.
+        if (__any(!(l_new < kRescaleAt))) {
             float lsum;
             raise_reference(s_cur, pn0, pn1, lsum);
             l_new = l_run + lsum;

@@ -487,6 +487,32 @@ def test_attn_scale_and_large_logits(spa, oracle):
     assert (lse.cpu() - want_lse).abs().max().item() <= 2e-2
 
 
+@pytest.mark.parametrize("D,Bs", [(128, 128), (128, 64), (64, 128), (64, 64)])
+@pytest.mark.parametrize("direction", [1.0, -1.0])
+def test_attn_logits_drifting_far_from_the_first_keys(spa, oracle, D, Bs, direction):
+    """Logits that rise (or fall) by ~300 nats along the keys of a row: the kernel's softmax reference, set on
+    the first keys, has to be moved several times on the way (rising) or the later weights vanish
+    (falling).  Every causal block is selected; the softmax is peaked, hence the tolerance of
+    test_attn_scale_and_large_logits."""
+    NB = 6
+    S = NB * Bs
+    g = torch.Generator().manual_seed(59)
+    u = torch.randn(D, generator=g)
+    u = u / u.norm()
+    ramp = direction * torch.arange(S, dtype=torch.float32) / S
+    q = (3.0 * u + 0.1 * torch.randn(1, 2, S, D, generator=g)).to(torch.bfloat16)
+    kk = (ramp[None, None, :, None] * u * 100.0 * D ** 0.5
+          + 0.5 * torch.randn(1, 1, S, D, generator=g)).to(torch.bfloat16)
+    v = torch.randn(1, 1, S, D, generator=g).to(torch.bfloat16)
+    idx, cnt = _oracle_lists(oracle, q, kk, Bs, 1, 1, NB)
+    want, want_lse = oracle.attn(q, kk, v, idx, cnt, Bs)
+    out, lse = spa.attn(q.cuda(), kk.cuda(), v.cuda(), idx.cuda(), cnt.cuda(), Bs, return_lse=True)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    diff = (out.float().cpu() - want).abs()
+    assert diff.max().item() <= 2.6e-2 and diff.mean().item() <= MEAN_ABS
+    assert ((lse.cpu() - want_lse).abs() <= 2e-2 + 2e-3 * want_lse.abs()).all()
+
+
 def test_attn_unit_values(spa, oracle):
     q, kk, v = _qkv(1, 2, 2, 5 * 64, 64, 43)
     v = torch.ones_like(v)
