@@ -173,7 +173,10 @@ int sparse_prefill_topk_from_scores(const spa_params *p, const float *pooled_sco
  * natural-log sum of exponentials of the scaled logits of each row.
  * block_idx / block_cnt must satisfy the layout rules at the top of this file
  * (ascending, unique, 0 <= entry <= i, last valid entry == i, 1 <= cnt <= T);
- * lists produced by the select calls always do.  They are NOT validated.
+ * lists produced by the select calls always do.  They are not validated: a count outside
+ * [1, T] or a block outside [0, NBk) is clamped, so a malformed list cannot make the kernel read
+ * outside the tensors, but the output of such a row is unspecified
+ * (sparse_prefill_check_lists counts the rows that break the rules).
  * Of p this call uses the shape, strides and scale; the pattern fields fix T and
  * serve as a hint of how uneven the rows are (a dense strip or strided columns
  * make the library deal the query blocks to the chip's partitions one by one).
@@ -183,6 +186,17 @@ int sparse_prefill_attn(const spa_params *p, const void *q, const void *k, const
                         const int32_t *block_idx, const int32_t *block_cnt,
                         void *out, float *lse_or_null, void *ws, size_t ws_bytes,
                         void *hip_stream);
+
+/* Check of caller-made lists against the rules sparse_prefill_attn relies on (Sec. 4.1.1: the
+ * attention kernel consumes the block-level indices as they are).  For every list row of a query
+ * block that exists (ragged batches: inside its entry's length) it tests 1 <= cnt <= T, entries
+ * strictly ascending, first >= 0 and last == the row's diagonal block
+ * (kv_prefix_len / block_size + i), and stores the number of rows that fail in *n_bad_rows, a
+ * DEVICE int32 the call overwrites (0 = every row is well formed).  Lists are [batch, n_q_heads,
+ * NB, T], or [batch, n_kv_heads, NB, T] with lists_per_kv_head.  Uses of p: shape, pattern (T),
+ * kv_prefix_len, lists_per_kv_head, seq_lens.  Asynchronous like every other call. */
+int sparse_prefill_check_lists(const spa_params *p, const int32_t *block_idx,
+                               const int32_t *block_cnt, int32_t *n_bad_rows, void *hip_stream);
 
 /* select followed by attn on one stream.  block_idx_or_null / block_cnt_or_null:
  * pass both to receive the lists, or both NULL to keep them in the workspace. */

@@ -16,7 +16,7 @@ EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_pr
            "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
            "sparse_prefill_fused_tpd", "sparse_prefill_value_norms", "sparse_prefill_select_stem",
            "sparse_prefill_fused_stem", "sparse_prefill_select_ex", "sparse_prefill_topk_from_scores_ex",
-           "sparse_prefill_fused_ex")
+           "sparse_prefill_fused_ex", "sparse_prefill_check_lists")
 
 
 class SpaError(RuntimeError):
@@ -63,6 +63,7 @@ def load_library():
     lib.sparse_prefill_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
     lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_check_lists.argtypes = [pp, vp, vp, vp, vp]
     lib.sparse_prefill_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_select_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_topk_from_scores_tpd.argtypes = [pp, vp, vp, vp, vp, vp]
@@ -303,6 +304,26 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
                                               _ptr(block_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                               _stream(q)))
     return (out, lse) if return_lse else out
+
+
+def check_lists(q, k, block_idx, block_cnt, block_size, pattern=None, group_shared=False, seq_lens=None) -> int:
+    """sparse_prefill_check_lists: the number of list rows that break the attention kernel's layout
+    rules (0 = all well formed).  q, k only give the shape; pattern as in attn()."""
+    B, Hq, S, D = q.shape
+    T = block_idx.shape[-1]
+    if pattern is None:
+        p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), None, group_shared=group_shared, seq_lens=seq_lens)
+    else:
+        ns, nl, tk, stride, n_dense, *rest = pattern
+        p = _params_from(q, k, block_size, ns, nl, tk, None, stride_blocks=stride, n_dense_q_blocks=n_dense,
+                         stride_reach_blocks=rest[0] if rest else 0, group_shared=group_shared, seq_lens=seq_lens)
+    if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
+            or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
+        raise TypeError("block_idx must be contiguous int32 [B,H,NB,T] with the call's row capacity")
+    n_bad = torch.empty(1, dtype=torch.int32, device=block_idx.device)
+    _check(load_library().sparse_prefill_check_lists(ctypes.byref(p), _ptr(block_idx), _ptr(block_cnt), _ptr(n_bad),
+                                                     _stream(block_idx)))
+    return int(n_bad.item())
 
 
 def fused(q, k, v, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,

@@ -244,6 +244,15 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
                                    strides_of(p->o_stride), lse_or_null, (char*)ws + w.vt_off, st));
 }
 
+int sparse_prefill_check_lists(const spa_params* p, const int32_t* block_idx, const int32_t* block_cnt,
+                               int32_t* n_bad_rows, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt || !n_bad_rows) return SPA_ERR_NULLPTR;
+    const Dims d = resolved(p);
+    return launch_code(launch_check_lists(d, block_idx, block_cnt, n_bad_rows, (hipStream_t)hip_stream));
+}
+
 int sparse_prefill_fused(const spa_params* p, const void* q, const void* k, const void* v, void* out,
                          float* lse_or_null, int32_t* block_idx_or_null, int32_t* block_cnt_or_null,
                          void* ws, size_t ws_bytes, void* hip_stream) {

@@ -222,8 +222,16 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
-    const int n_sel = cnt[row_id];
+    // Lists are the caller's: a count outside [1, T] or a block outside [0, NBk) is clamped so that a
+    // malformed list can never make the kernel read outside the tensors (the row's output is then
+    // unspecified).  Scalar work, once per list entry.
+    int n_sel = cnt[row_id];
+    n_sel = n_sel < 1 ? 1 : (n_sel > T ? T : n_sel);
     const int n_st = n_sel * NSUB;
+    auto block_at = [&](int e) {
+        const int blk = sel[e];
+        return blk < 0 ? 0 : (blk >= NBk ? NBk - 1 : blk);
+    };
 
     // Direct global->LDS loads: instruction `inst` of a sub-tile fills 1 KB of LDS in lane order
     // (4 K rows of 256 B or 8 of 128 B, 8 V^T rows of 128 B); the lane picks the global 16-byte chunk whose
@@ -276,11 +284,11 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     };
     auto blk_of = [&](int st) {        // key block of sub-tile st (clamped: never read past the list)
         const int e = st / NSUB;
-        return sel[e < n_sel ? e : n_sel - 1];
+        return block_at(e < n_sel ? e : n_sel - 1);
     };
 
-    issue_k(IC<0>{}, 0, sel[0]);
-    issue_v(IC<0>{}, 0, sel[0]);
+    issue_k(IC<0>{}, 0, block_at(0));
+    issue_v(IC<0>{}, 0, block_at(0));
     if (n_st > 1) issue_k(IC<1>{}, 1, blk_of(1));
 
     // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
@@ -554,6 +562,34 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
         lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
 }
 
+// One wavefront per list row: counts the rows that break the rules the attention kernel relies on
+// (1 <= cnt <= T, entries strictly ascending, first >= 0, last == the row's diagonal block).
+__global__ __launch_bounds__(256) void check_lists_kernel(const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ cnt, int Hl, int NB, int T,
+                                                          int off, int Bs, int S, const int32_t* __restrict__ seq_lens,
+                                                          int64_t n_rows, int32_t* __restrict__ n_bad) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int lane = threadIdx.x & 63;
+    const int i = (int)(row % NB);
+    const int b = (int)(row / ((int64_t)NB * Hl));
+    const int Sb = entry_len(seq_lens, b, S);
+    if ((int64_t)i * Bs >= Sb) return;                     // past the entry's end: never read
+    const int c = cnt[row];
+    const int32_t* e = idx + row * T;
+    bool bad = c < 1 || c > T;
+    if (!bad) {
+        for (int j = lane; j < c; j += 64) {
+            const int v = e[j];
+            if (j == 0 ? v < 0 : v <= e[j - 1]) bad = true;
+            if (j == c - 1 && v != off + i) bad = true;
+        }
+    }
+    if (__any(bad) && lane == 0) atomicAdd(n_bad, 1);
+}
+
+__global__ void zero_i32_kernel(int32_t* p) { *p = 0; }
+
 template <int BS, int D>
 hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* v,
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
@@ -572,6 +608,19 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
 }
 
 }  // namespace
+
+hipError_t launch_check_lists(const Dims& d, const int32_t* idx, const int32_t* cnt, int32_t* n_bad, hipStream_t st) {
+    const int Hl = d.shared ? d.Hkv : d.Hq;
+    const int64_t n_rows = (int64_t)d.B * Hl * d.NB;
+    const int64_t nwg = (n_rows + 3) / 4;
+    if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(1), 0, st, n_bad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(check_lists_kernel, dim3((unsigned)nwg), dim3(256), 0, st, idx, cnt, Hl, d.NB, d.T, d.off, d.Bs,
+                       d.S, d.seq_lens, n_rows, n_bad);
+    return hipGetLastError();
+}
 
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                             const void* v, Strides vs, const int32_t* idx, const int32_t* cnt, void* out,

@@ -79,6 +79,8 @@ hipError_t launch_score_topk(const Dims& d, const float* qp, const float* kp, co
 hipError_t launch_topk_from_scores(const Dims& d, const float* scores, const int32_t* k_rows,
                                    const int32_t* head_pattern, int32_t* idx, int32_t* cnt, hipStream_t st);
 // vt is scratch for V transposed per block, B*Hkv*NBk*Bs*D bf16.
+// counts, into *n_bad (device), the list rows that break the attention kernel's layout rules
+hipError_t launch_check_lists(const Dims& d, const int32_t* idx, const int32_t* cnt, int32_t* n_bad, hipStream_t st);
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
                        void* out, Strides os, float* lse, void* vt, hipStream_t st);

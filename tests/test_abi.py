@@ -143,3 +143,12 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_check_lists_rejects_null_pointers_and_bad_shapes(lib):
+    p = _params()
+    fake = ctypes.c_void_p(256)
+    assert lib.sparse_prefill_check_lists(ctypes.byref(p), None, fake, fake, None) == -1
+    assert lib.sparse_prefill_check_lists(ctypes.byref(p), fake, None, fake, None) == -1
+    assert lib.sparse_prefill_check_lists(ctypes.byref(p), fake, fake, None, None) == -1
+    assert lib.sparse_prefill_check_lists(ctypes.byref(_params(head_dim=96)), fake, fake, fake, None) == -2

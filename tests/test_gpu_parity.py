@@ -764,6 +764,64 @@ def test_kv_prefix_equals_the_rows_of_the_full_run(spa, oracle, Sq, P, D, Bs):
     assert torch.equal(fused, out_c)
 
 
+# ------------------------------------------------------------- caller-made lists
+@pytest.mark.parametrize("D,Bs,P,shared", [(64, 64, 0, False), (128, 128, 0, True), (128, 64, 128, False)])
+def test_check_lists_counts_the_malformed_rows(spa, D, Bs, P, shared):
+    B, Hq, Hkv, NB, ns, nl, k = 2, 4, 2, 12, 1, 2, 3
+    Sq = NB * Bs - 5
+    S = P + Sq
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 401)
+    dq, dk = q.cuda()[:, :, P:], kk.cuda()
+    lens = torch.tensor([Sq, Sq - 3 * Bs], dtype=torch.int32).cuda()      # entry 1: its last 3 rows do not exist
+    idx, cnt = spa.select(dq, dk, Bs, ns, nl, k, group_shared=shared, seq_lens=lens)
+    T = idx.shape[-1]
+    pat = (ns, nl, k, 0, 0)
+    kw = dict(pattern=pat, group_shared=shared, seq_lens=lens)
+    assert spa.check_lists(dq, dk, idx, cnt, Bs, **kw) == 0
+    bad_i, bad_c = idx.clone(), cnt.clone()
+    h = 1
+    bad_c[0, h, 3] = 0                                   # empty row
+    bad_c[0, h, 4] = T + 1                               # longer than the row
+    bad_i[0, h, 9, 1], bad_i[0, h, 9, 2] = idx[0, h, 9, 2].item(), idx[0, h, 9, 1].item()   # not ascending
+    bad_i[0, h, 10, 2] = idx[0, h, 10, 1]                # duplicate
+    bad_i[0, h, 11, cnt[0, h, 11].item() - 1] += 1       # does not end on the diagonal block
+    bad_i[1, 0, 5, 0] = -1                               # negative entry
+    bad_i[1, 0, 6, 0] = -7
+    bad_c[1, 0, 6] = -2                                  # one row, two faults: counted once
+    bad_i[1, 0, NB - 1, :] = 12345                       # rows past entry 1's end are never read: not counted
+    bad_c[1, 0, NB - 2] = 99
+    assert spa.check_lists(dq, dk, bad_i, bad_c, Bs, **kw) == 7
+    assert spa.check_lists(dq, dk, idx, cnt, Bs, **kw) == 0              # the counter is overwritten, not added to
+
+
+def test_attn_with_malformed_lists_stays_in_bounds_and_leaves_other_rows_alone(spa):
+    """Counts outside [1, T] and blocks outside [0, NBk) are clamped by the kernel: such rows produce
+    unspecified values, every other row is bit-identical to the run with the good lists."""
+    B, Hq, Hkv, NB, D, Bs, ns, nl, k = 1, 4, 2, 10, 128, 128, 1, 2, 3
+    q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 409)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    idx, cnt = spa.select(dq, dk, Bs, ns, nl, k)
+    T = idx.shape[-1]
+    good = spa.attn(dq, dk, dv, idx, cnt, Bs)
+    bad_i, bad_c = idx.clone(), cnt.clone()
+    rows = [(0, 2), (1, 5), (2, 7), (3, 9), (3, 0), (2, 4)]
+    bad_c[0, 0, 2] = 0
+    bad_c[0, 1, 5] = T + 40
+    bad_i[0, 2, 7, 0] = -5
+    bad_i[0, 2, 7, 1] = NB + 3
+    bad_i[0, 3, 9, 2] = 2 ** 30
+    bad_c[0, 3, 0] = -2 ** 31
+    bad_i[0, 2, 4, :] = torch.tensor([4, 3, 3, 0, -1, 7][:T] + [0] * max(0, T - 6), dtype=torch.int32)
+    assert spa.check_lists(dq, dk, bad_i, bad_c, Bs, pattern=(ns, nl, k, 0, 0)) == len(rows)
+    out = spa.attn(dq, dk, dv, bad_i, bad_c, Bs)
+    torch.cuda.synchronize()
+    keep = torch.ones((Hq, NB), dtype=torch.bool)
+    for hh, ii in rows:
+        keep[hh, ii] = False
+    keep = keep.cuda().repeat_interleave(Bs, dim=1)
+    assert torch.equal(out[0][keep], good[0][keep])
+
+
 # ------------------------------------------------------------- HIP graph replay
 # ------------------------------------------------------------ ragged batches
 @pytest.mark.parametrize("lens,P,Hq,Hkv,D,Bs,kw", [
