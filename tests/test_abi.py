@@ -152,3 +152,78 @@ def test_check_lists_rejects_null_pointers_and_bad_shapes(lib):
     assert lib.sparse_prefill_check_lists(ctypes.byref(p), fake, None, fake, None) == -1
     assert lib.sparse_prefill_check_lists(ctypes.byref(p), fake, fake, None, None) == -1
     assert lib.sparse_prefill_check_lists(ctypes.byref(_params(head_dim=96)), fake, fake, fake, None) == -2
+
+
+def _compile_and_run_c(tmp_path, body, std="-std=c99"):
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text(body)
+    exe = tmp_path / "t"
+    subprocess.run(["gcc", std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-ldl"], check=True, capture_output=True, text=True)
+    return subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_structs(tmp_path):
+    """The header compiles as strict C99 with no other include, and the ctypes structures have
+    the size and the field offsets a C compiler gives the header's structs."""
+    from paper_2602_21233_amd import binding
+    lines = ['#include "sparse_prefill.h"', "#include <stdio.h>", "int main(void) {",
+             '  printf("spa_params %zu\\n", sizeof(spa_params));',
+             '  printf("spa_select_opts %zu\\n", sizeof(spa_select_opts));']
+    for struct, cls in (("spa_params", binding.SpaParams), ("spa_select_opts", binding.SpaSelectOpts)):
+        for name, _ in cls._fields_:
+            lines.append(f'  printf("{struct}.{name} %zu\\n", offsetof({struct}, {name}));')
+    lines += ["  return SPA_OK;", "}"]
+    got = dict(l.split() for l in _compile_and_run_c(tmp_path, "\n".join(lines)).splitlines())
+    assert int(got["spa_params"]) == ctypes.sizeof(binding.SpaParams)
+    assert int(got["spa_select_opts"]) == ctypes.sizeof(binding.SpaSelectOpts)
+    for struct, cls in (("spa_params", binding.SpaParams), ("spa_select_opts", binding.SpaSelectOpts)):
+        for name, _ in cls._fields_:
+            assert int(got[f"{struct}.{name}"]) == getattr(cls, name).offset, (struct, name)
+
+
+def test_library_is_callable_from_plain_c(tmp_path, lib):
+    """A C program with no Python and no torch loads the library and gets the host-side answers."""
+    from paper_2602_21233_amd import binding
+    body = r'''
+#define _POSIX_C_SOURCE 200809L
+#include "sparse_prefill.h"
+#include <dlfcn.h>
+#include <stdio.h>
+#include <string.h>
+typedef int (*cap_fn)(const spa_params *, int32_t *);
+typedef int (*ws_fn)(const spa_params *, size_t *);
+typedef const char *(*err_fn)(int);
+typedef int (*attn_fn)(const spa_params *, const void *, const void *, const void *, const int32_t *, const int32_t *,
+                       void *, float *, void *, size_t, void *);
+int main(void) {
+    void *h = dlopen("%LIB%", RTLD_NOW);
+    if (!h) { printf("dlopen failed: %s\n", dlerror()); return 1; }
+    cap_fn cap; ws_fn ws; err_fn err; attn_fn attn;
+    *(void **)&cap = dlsym(h, "spa_row_capacity");
+    *(void **)&ws = dlsym(h, "spa_workspace_bytes");
+    *(void **)&err = dlsym(h, "spa_strerror");
+    *(void **)&attn = dlsym(h, "sparse_prefill_attn");
+    if (!cap || !ws || !err || !attn) { printf("missing symbol\n"); return 1; }
+    spa_params p;
+    memset(&p, 0, sizeof p);
+    p.batch = 1; p.n_q_heads = 32; p.n_kv_heads = 8; p.seq_len = 131072; p.head_dim = 128; p.block_size = 128;
+    p.n_sink_blocks = 1; p.n_local_blocks = 4; p.top_k_blocks = 64;
+    int32_t T = -1; size_t bytes = 0;
+    int rc1 = cap(&p, &T), rc2 = ws(&p, &bytes);
+    printf("cap %d %d\nws %d %zu\n", rc1, (int)T, rc2, bytes);
+    printf("attn_null %d\n", attn(&p, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL));
+    p.head_dim = 96;
+    printf("bad_shape %d %s\n", cap(&p, &T), err(cap(&p, &T)));
+    return 0;
+}
+'''.replace("%LIB%", binding.library_path())
+    out = _compile_and_run_c(tmp_path, body, std="-std=c99").splitlines()
+    assert out[0] == "cap 0 69"
+    rc, nbytes = out[1].split()[1:]
+    p = _params(n_q_heads=32, n_kv_heads=8, seq_len=131072, n_local_blocks=4, top_k_blocks=64)
+    import paper_2602_21233_amd as m
+    assert int(rc) == 0 and int(nbytes) == m.workspace_bytes(p)
+    assert out[2] == "attn_null -1"
+    assert out[3].startswith("bad_shape -2 ") and len(out[3]) > len("bad_shape -2 ")
