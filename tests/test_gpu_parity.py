@@ -764,6 +764,81 @@ def test_kv_prefix_equals_the_rows_of_the_full_run(spa, oracle, Sq, P, D, Bs):
     assert torch.equal(fused, out_c)
 
 
+# ------------------------------------------------------------- options in combination
+def _random_case(seed):
+    r = __import__("random").Random(seed)
+    Bs, D = r.choice([64, 128]), r.choice([64, 128])
+    Hkv, G, B = r.choice([1, 2]), r.choice([1, 2, 4]), r.choice([1, 2])
+    NB = r.randint(3, 40)
+    long_rows = seed >= 48                       # rows of several 64-block chunks: one KV head, bounded patterns
+    if long_rows:
+        Hkv, G, B, NB = 1, r.choice([1, 2]), 1, r.choice([300, 700, 1100, 2100])
+    S = NB * Bs - r.choice([0, 0, 1, Bs // 2, Bs - 1])
+    P = r.choice([0, 0, Bs, 3 * Bs])
+    ns, nl, k = r.choice([0, 1, 2]), r.choice([1, 2, 3]), r.choice([0, 1, 3, 6])
+    stride = r.choice([0, 0, 2, 3, 5])
+    reach = r.choice([4, 7] if long_rows else [0, 4, 7]) if stride else 0
+    n_dense = r.choice([0, 0, 2])
+    return dict(seed=seed, Bs=Bs, D=D, Hkv=Hkv, G=G, B=B, NB=NB, S=S, P=P, ns=ns, nl=nl, k=k, stride=stride, reach=reach,
+                n_dense=n_dense, schedule=r.choice([None, "decay", "wild"]), head_pattern=r.random() < 0.3,
+                gamma=r.choice([None, None, 0.5, 0.9]), output_aware=r.random() < 0.3, shared=r.random() < 0.3,
+                ragged=B == 2 and r.random() < 0.6)
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_options_in_random_combination(spa, oracle, seed):
+    """Seeded random combinations of every option of the select and attention calls (block and head
+    sizes, partial last block, KV prefix, static patterns, budget schedule, per-head metadata,
+    cumulative-mass budget, output-aware score, group-shared lists, ragged batch): the lists equal
+    the oracle's rule on the GPU's own scores bit for bit, the lists are well formed, and the fused
+    output is the oracle's attention on those lists within the tolerance."""
+    c = _random_case(seed)
+    Bs, D, B, Hkv, G, S, P = c["Bs"], c["D"], c["B"], c["Hkv"], c["G"], c["S"], c["P"]
+    Hq = Hkv * G
+    ns, nl, k = c["ns"], c["nl"], c["k"]
+    g = torch.Generator().manual_seed(1000 + seed)
+    q = torch.randn((B, Hq, S, D), generator=g).to(torch.bfloat16)
+    kk = torch.randn((B, Hkv, P + S, D), generator=g).to(torch.bfloat16)
+    v = (torch.randn((B, Hkv, P + S, D), generator=g) * (0.5 + torch.rand((B, Hkv, P + S, 1), generator=g))).to(torch.bfloat16)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    NBq, off = -(-S // Bs), P // Bs
+    Hl = Hkv if c["shared"] else Hq
+    lens = [S, max(1, S - torch.randint(1, S, (1,), generator=g).item())] if c["ragged"] else None
+    dl = None if lens is None else torch.tensor(lens, dtype=torch.int32).cuda()
+    kr = None if c["schedule"] is None else _schedules(NBq, max(k, 1))[c["schedule"]]
+    hp = None
+    if c["head_pattern"]:
+        hp = torch.stack([torch.randint(-1, ns + 2, (Hl,), generator=g), torch.randint(0, nl + 2, (Hl,), generator=g),
+                          torch.randint(-1, k + 2, (Hl,), generator=g)], dim=1).to(torch.int32)
+    sel_kw = dict(stride_blocks=c["stride"], n_dense_q_blocks=c["n_dense"], stride_reach_blocks=c["reach"],
+                  group_shared=c["shared"], mass_gamma=c["gamma"], seq_lens=dl,
+                  top_k_per_block=None if kr is None else kr.cuda(), head_pattern=None if hp is None else hp.cuda())
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, v=dv if c["output_aware"] else None, **sel_kw)
+    pattern = (ns, nl, k, c["stride"], c["n_dense"], c["reach"])
+    assert spa.check_lists(dq, dk, idx, cnt, Bs, pattern=pattern, group_shared=c["shared"], seq_lens=dl) == 0, c
+    fused, lse = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, output_aware=c["output_aware"], **sel_kw)
+    out2 = spa.attn(dq, dk, dv, idx, cnt, Bs, pattern=pattern, group_shared=c["shared"], seq_lens=dl)
+    for b in range(B):
+        n = S if lens is None else lens[b]
+        nb = -(-n // Bs)
+        # the rule, applied by the oracle to the scores the GPU ranked, on the entry's own rows
+        w_idx, w_cnt = oracle.topk(sp[b:b + 1, :, :nb, :off + nb].cpu().contiguous(), ns, nl, k,
+                                   None if kr is None else kr[:nb].contiguous(), stride=c["stride"], n_dense=c["n_dense"],
+                                   head_pattern=hp, reach=c["reach"], gamma=c["gamma"])
+        Tw = w_idx.shape[-1]
+        assert torch.equal(cnt[b, :, :nb].cpu(), w_cnt[0]), (c, b)
+        assert torch.equal(idx[b, :, :nb, :Tw].cpu(), w_idx[0]) and (idx[b, :, :nb, Tw:] == -1).all(), (c, b)
+        assert (cnt[b, :, nb:] == 0).all() and (idx[b, :, nb:] == -1).all(), (c, b)
+        assert torch.equal(out2[b, :, :n], fused[b, :, :n]), (c, b)
+        li = idx[b:b + 1, :, :nb].cpu()
+        lc = cnt[b:b + 1, :, :nb].cpu()
+        if c["shared"]:
+            li, lc = li.repeat_interleave(G, 1), lc.repeat_interleave(G, 1)
+        want, want_lse = oracle.attn(q[b:b + 1, :, :n], kk[b:b + 1, :, :P + n], v[b:b + 1, :, :P + n], li, lc, Bs)
+        _assert_attn_close(fused[b:b + 1, :, :n], want, (c, b))
+        assert (lse[b:b + 1, :, :n].cpu() - want_lse).abs().max().item() <= 2e-2, (c, b)
+
+
 # ------------------------------------------------------------- caller-made lists
 @pytest.mark.parametrize("D,Bs,P,shared", [(64, 64, 0, False), (128, 128, 0, True), (128, 64, 128, False)])
 def test_check_lists_counts_the_malformed_rows(spa, D, Bs, P, shared):
