@@ -932,7 +932,10 @@ hipError_t launch_mfma_d(const ScoreCall& c) {
     // within 66 KB of LDS, so that two 8-wave workgroups share a CU (measured at 131072 tokens:
     // 125 -> 106 us against 32 rows with one 8-wave workgroup per CU)
     const int NBk = c.d.NBk;
-    if (NBk <= 256) return launch_mfma<D, 16, 4>(c);
+    // short rows: 8 rows per workgroup give the chip two rounds of workgroups, so that the second round's
+    // streaming overlaps the first round's scoring (0.065 -> 0.062 ms at 32768 tokens; 16 rows at 1024
+    // blocks stay: 8 there re-read the pooled K twice as often, 0.29 against 0.26 ms)
+    if (NBk <= 256) return launch_mfma<D, 8, 4>(c);
     if (NBk <= 512) return launch_mfma<D, 16, 8>(c);
     if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
     // 1025 .. 2048 blocks: 8 rows, still two workgroups per CU, so that one can stream its queries while the
