@@ -932,11 +932,12 @@ hipError_t launch_mfma_d(const ScoreCall& c) {
     // within 66 KB of LDS, so that two 8-wave workgroups share a CU (measured at 131072 tokens:
     // 125 -> 106 us against 32 rows with one 8-wave workgroup per CU)
     const int NBk = c.d.NBk;
-    // short rows: 8 rows per workgroup give the chip two rounds of workgroups, so that the second round's
-    // streaming overlaps the first round's scoring (0.065 -> 0.062 ms at 32768 tokens; 16 rows at 1024
-    // blocks stay: 8 there re-read the pooled K twice as often, 0.29 against 0.26 ms)
+    // up to 512 blocks: 8 rows per workgroup give the chip more rounds of workgroups, so that one round's
+    // streaming overlaps another's scoring (0.065 -> 0.062 ms at 32768 tokens, 0.135 -> 0.124 ms at 65536);
+    // from 513 blocks 16 rows stay: 8 there re-read the pooled K twice as often (0.20 against 0.19 ms at 768
+    // blocks, 0.29 against 0.26 ms at 1024)
     if (NBk <= 256) return launch_mfma<D, 8, 4>(c);
-    if (NBk <= 512) return launch_mfma<D, 16, 8>(c);
+    if (NBk <= 512) return launch_mfma<D, 8, 8>(c);
     if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
     // 1025 .. 2048 blocks: 8 rows, still two workgroups per CU, so that one can stream its queries while the
     // other scores (0.84 -> 0.81 ms at 262144 tokens against 16 rows by one 16-wave workgroup per CU)
