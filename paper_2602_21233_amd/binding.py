@@ -211,6 +211,8 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
     without a schedule); sparse_prefill_select_ex with head_pattern or mass_gamma (cumulative-mass
     budget).  Returns (block_idx, block_cnt[, scores])."""
     _dev_bf16(q, k)
+    if v is not None:
+        _dev_bf16(v)
     p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale, v=v,
                      stride_blocks=stride_blocks, n_dense_q_blocks=n_dense_q_blocks,
                      stride_reach_blocks=stride_reach_blocks, group_shared=group_shared, seq_lens=seq_lens)
@@ -229,7 +231,6 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
         _check(load_library().sparse_prefill_select_ex(ctypes.byref(p), _ptr(q), _ptr(k), ctypes.byref(o), _ptr(idx),
                                                        _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
     elif v is not None:
-        _dev_bf16(v)
         kr = None if top_k_per_block is None else _schedule(top_k_per_block, NB, q.device)
         _check(load_library().sparse_prefill_select_stem(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kr),
                                                          _ptr(idx), _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(),

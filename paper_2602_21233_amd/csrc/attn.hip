@@ -222,15 +222,18 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
-    // Lists are the caller's: a count outside [1, T] or a block outside [0, NBk) is clamped so that a
-    // malformed list can never make the kernel read outside the tensors (the row's output is then
-    // unspecified).  Scalar work, once per list entry.
+    // Lists are the caller's: a count outside [1, T] or a block outside the entry's own key blocks
+    // [0, ceil(Skv / BS)) is clamped so that a malformed list can never make the kernel read outside
+    // the tensors (the row's output is then unspecified).  The bound is the entry's, not the padded
+    // NBk: in a ragged batch a block past the entry's last token would make the partial-block path
+    // below compute a negative last row.  Skv >= 1 here.  Scalar work, once per list entry.
     int n_sel = cnt[row_id];
     n_sel = n_sel < 1 ? 1 : (n_sel > T ? T : n_sel);
     const int n_st = n_sel * NSUB;
+    const int blk_last = (Skv - 1) / BS < NBk - 1 ? (Skv - 1) / BS : NBk - 1;
     auto block_at = [&](int e) {
         const int blk = sel[e];
-        return blk < 0 ? 0 : (blk >= NBk ? NBk - 1 : blk);
+        return blk < 0 ? 0 : (blk > blk_last ? blk_last : blk);
     };
 
     // Direct global->LDS loads: instruction `inst` of a sub-tile fills 1 KB of LDS in lane order

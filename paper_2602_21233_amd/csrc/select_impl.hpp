@@ -38,7 +38,9 @@
 // instantiations compile in parallel: select.hip (top-k on caller scores and the dispatcher) and
 // select_d128.hip / select_d64.hip (score/top-k kernels for one head_dim each, SPA_SELECT_D set).
 #pragma once
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "common.hpp"
 
@@ -872,10 +874,28 @@ __global__ __launch_bounds__(NWV * 64, 4) void score_topk_mfma_kernel(ScoreArgs 
     score_topk_rows<D, R, MAXC, EXT, MASS, NWV, QPOOL>(a, wg / n_tiles, tile * R, S);
 }
 
-// Dynamic LDS above the default cap has to be requested per kernel.
+// Dynamic LDS above the default cap has to be requested per kernel and device.  That is done on the
+// first launch of a (kernel, device) pair and remembered: later launches, also those recorded into a
+// stream capture, make no runtime call besides the launch itself.
 hipError_t allow_lds(const void* kernel, size_t bytes) {
     if (bytes <= 32768) return hipSuccess;
-    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    struct Granted { const void* kernel; int device; size_t bytes; };
+    static std::mutex mu;
+    static std::vector<Granted> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (Granted& g : granted)
+        if (g.kernel == kernel && g.device == dev) {
+            if (g.bytes >= bytes) return hipSuccess;
+            e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e == hipSuccess) g.bytes = bytes;
+            return e;
+        }
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) granted.push_back(Granted{kernel, dev, bytes});
+    return e;
 }
 
 ScoreArgs score_args(const Dims& d, const float* qp, const float* kp, const int32_t* k_rows, const int32_t* head_pattern,

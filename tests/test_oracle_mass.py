@@ -35,6 +35,49 @@ def test_weights_match_exp_in_fp64(oracle):
         assert (W[:, :, i, :i + 1].max(-1) == ONE).all()    # the maximum weighs exactly 2^19
 
 
+def test_weights_on_a_dense_grid_against_fp64_exp(oracle):
+    """Every weight on a dense grid of differences d = x - m in [-28.5, 0] (200 000 points, plus the
+    points around the cut-off and exact ties) against floor(2^19 e^d + 1/2) evaluated in fp64.
+    Stated bound: |W - 2^19 e^d| <= 0.5 (rounding to an integer) + 0.2 (fp32 evaluation: the
+    polynomial's truncation error of 1.3e-7 and about three fp32 roundings of 2^-24, relative to a
+    weight of at most 2^19), hence W differs from the fp64 rounding by at most 1 and only where
+    2^19 e^d lies within 0.2 of a half-integer.  A wrong coefficient, a dropped term or a wrong
+    exponent split breaks the bound; the cut-off is where (x - m) log2 e, rounded to fp32, falls
+    below -40; weights never increase as d falls."""
+    n_rows, n = 50, 4001
+    d = -np.linspace(0.0, 28.5, n_rows * (n - 1))
+    # keep the maximum (d = 0) in column 0 of every row; a row is causal in full (KV prefix)
+    rows = np.concatenate([np.zeros((n_rows, 1)), d.reshape(n_rows, n - 1)], axis=1).astype(np.float32)
+    # an arbitrary common offset must not matter beyond the fp32 subtraction, which is exact here:
+    # the grid itself is fp32 and m = 0
+    sp = torch.from_numpy(rows).reshape(1, n_rows, 1, n)
+    W = oracle.mass_weights(sp)[0, :, 0].numpy().astype(np.int64)
+    x = rows.astype(np.float64)
+    exact = np.exp(x) * ONE
+    t32 = (rows.astype(np.float32) * np.float32(1.44269504088896340736)).astype(np.float32)
+    cut = ~(t32 >= np.float32(-40.0))
+    assert cut.any() and (~cut).sum() > 190000
+    assert (W[cut] == 0).all()
+    live = ~cut
+    assert np.abs(W[live] - exact[live]).max() <= 0.7
+    ref = np.floor(exact + 0.5).astype(np.int64)
+    off = W[live] != ref[live]
+    assert np.abs(W[live] - ref[live]).max() <= 1
+    frac = exact[live] - np.floor(exact[live])
+    assert (np.abs(frac[off] - 0.5) <= 0.2).all()
+    assert off.mean() < 0.05
+    flat = W[:, 1:].reshape(-1)                            # d falls along the flattened grid
+    assert (np.diff(flat) <= 0).all()
+    assert (W[:, 0] == ONE).all()
+    # ties: equal scores weigh the same whatever their position, and a shifted row (same
+    # differences, representable exactly) gives the same weights
+    tied = torch.tensor([1.5, -0.25, 1.5, -0.25, -0.25, 1.5, -7.0, -7.0]).reshape(1, 1, 1, 8)
+    Wt = oracle.mass_weights(tied)[0, 0, 0].tolist()
+    assert Wt[0] == Wt[2] == Wt[5] == ONE and Wt[1] == Wt[3] == Wt[4] and Wt[6] == Wt[7]
+    assert oracle.mass_weights(tied + 64.0)[0, 0, 0].tolist() == Wt
+    assert Wt[1] == int(math.floor(math.exp(-1.75) * ONE + 0.5)) and Wt[6] == int(math.floor(math.exp(-8.5) * ONE + 0.5))
+
+
 def test_weights_of_special_values(oracle):
     nan, inf = float("nan"), float("inf")
     sp = torch.tensor([[0.0, -inf, nan, -100.0, -0.0, 1.0, -1.0, 0.5],
