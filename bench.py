@@ -7,7 +7,10 @@ heads, head_dim 128, block 128, sink 1 + local 4 + top-k 64).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N] [--no-cpu-baseline]
-                    [--variant uniform|tpd|stem|strided|trishape|shared|mass]
+                    [--variant uniform|tpd|stem|strided|trishape|shared|mass] [--sample-power]
+
+--sample-power adds the shader clock and socket power the driver reports (sysfs), sampled from a side
+thread every 20 ms while the timed steps run (use enough steps for a loop of two seconds or more).
 
 --variant (default uniform = the headline) times the same workload under the other selection
 rules the library has: a position-decaying budget (tpd), that plus the output-aware ranking
@@ -29,19 +32,75 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 
-def read_traffic_note(kernel: str):
-    """HBM bytes per launch of `kernel` from the committed counter summary, if any."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+def read_traffic_note(kernel: str, workload: str):
+    """(HBM bytes per launch of `kernel` at `workload`, where the figure comes from) out of the committed
+    counter summaries, or (None, None): it is a recorded measurement of an earlier run of the same
+    command under rocprofv3 --pmc, not a measurement of this run."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         parts = line.split()
         if len(parts) >= 2 and parts[0] == kernel:
             try:
-                return float(parts[1])
+                return float(parts[1]), "recorded: profiles/" + os.path.basename(path) + " (rocprofv3 --pmc runs of this command)"
             except ValueError:
-                return None
-    return None
+                return None, None
+    return None, None
+
+
+class PowerSampler:
+    """Shader clock (pp_dpm_sclk, the level marked current) and socket power (hwmon power1_input or
+    power1_average) of the first GPU that exposes them in sysfs, read every `period` seconds."""
+
+    def __init__(self, period=0.02):
+        import glob
+        self.period, self.clock, self.power, self._stop, self._thread = period, [], [], False, None
+        self.sclk = self.pwr = None
+        for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+            sclk = os.path.join(dev, "pp_dpm_sclk")
+            pw = [f for n in ("power1_input", "power1_average") for f in glob.glob(os.path.join(dev, "hwmon", "hwmon*", n))]
+            if os.access(sclk, os.R_OK) and pw:
+                self.sclk, self.pwr = sclk, pw[0]
+                break
+
+    def _read(self):
+        try:
+            for line in open(self.sclk):
+                if "*" in line:
+                    self.clock.append(float(line.split(":")[1].lower().split("mhz")[0]))
+                    break
+            self.power.append(float(open(self.pwr).read()) * 1e-6)
+        except (OSError, ValueError, IndexError):
+            pass
+
+    def _run(self):
+        while not self._stop:
+            self._read()
+            time.sleep(self.period)
+
+    def start(self):
+        import threading
+        if self.sclk is None:
+            return
+        self._thread = threading.Thread(target=self._run, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join()
+
+    @staticmethod
+    def _stats(xs):
+        if not xs:
+            return None
+        xs = sorted(xs)
+        return {"min": xs[0], "p10": xs[len(xs) // 10], "median": xs[len(xs) // 2], "max": xs[-1], "samples": len(xs)}
+
+    def summary(self):
+        return {"shader_clock_mhz": self._stats(self.clock), "socket_power_w": self._stats(self.power),
+                "source": f"{self.sclk} (current level), {self.pwr}", "period_s": self.period}
 
 
 def cpu_baseline(w, q, k, v, idx, cnt, n_rows):
@@ -78,6 +137,8 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="overwrite a 1-GiB scratch buffer before every step (cold caches; for the small "
                          "workloads); ms_per_step then comes from the events, not the wall clock")
+    ap.add_argument("--sample-power", action="store_true",
+                    help="sample the reported shader clock and socket power during the timed steps")
     ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared", "mass"),
                     default="uniform")
     args = ap.parse_args()
@@ -147,11 +208,16 @@ def main():
         step()
     torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    sampler = PowerSampler() if args.sample_power else None
+    if sampler:
+        sampler.start()
     t0 = time.perf_counter()
     for s in range(args.steps):
         idx, cnt = step(evs[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if sampler:
+        sampler.stop()
     ms_step = wall * 1e3 / args.steps
     if args.cold:
         ms_step = sum(e[0].elapsed_time(e[2]) for e in evs) / args.steps
@@ -175,11 +241,16 @@ def main():
 
     # the output-aware score reads V once more (2 bytes per element)
     select_bytes = w.select_bytes + (2 * w.batch * w.n_kv_heads * w.seq_len * w.head_dim if args.variant == "stem" else 0)
-    visited_pairs = w.visited_pairs if args.variant == "uniform" else int(cnt.sum().item()) * (w.group if shared else 1)
+    visited_pairs = int(cnt.sum().item()) * (w.group if shared else 1)        # what the GPU's own lists hold
+    if args.variant == "uniform" and visited_pairs != w.visited_pairs:
+        print(f"bench.py: the lists hold {visited_pairs} block pairs, the closed form says {w.visited_pairs}", file=sys.stderr)
+        sys.exit(1)
     flops = 4.0 * Bs * Bs * w.head_dim * visited_pairs
     achieved = flops / (att_avg * 1e-3) / 1e12
+    traffic, traffic_source = read_traffic_note("attn_kernel", w.name) if args.variant == "uniform" else (None, None)
     result = {
-        "metric": "sparse prefill attention effective TFLOP/s on visited blocks (select + attention), 128K tokens",
+        "metric": f"sparse prefill attention effective TFLOP/s on visited blocks (select + attention), "
+                  f"{w.seq_len // 1024}K tokens" + ("" if args.variant == "uniform" else f", variant {args.variant}"),
         "value": flops / (ms_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
@@ -199,10 +270,13 @@ def main():
                        "bytes": select_bytes},
         "roofline": {"bound": "mfma", "kernel": f"attn_kernel<{Bs},{w.head_dim}>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": read_traffic_note("attn_kernel"), "traffic_unit": "bytes/launch",
+                     "median_ms": att_ms[len(att_ms) // 2], "min_ms": att_ms[0],
+                     "traffic": traffic, "traffic_unit": "bytes/launch", "traffic_source": traffic_source,
                      "timed": "events around sparse_prefill_attn on its stream: the attention kernel plus the "
                               "V transpose that precedes it (~0.08 ms)"},
     }
+    if sampler:
+        result["power"] = sampler.summary()
     if not args.no_cpu_baseline and args.variant == "uniform":
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, idx.cpu(), cnt.cpu(), args.cpu_rows)
     print(json.dumps(result))

@@ -441,7 +441,9 @@ def test_select_special_values_through_the_score_kernel(spa, oracle, NB, D, Bs, 
     causal = sp_c[..., tri]
     # the premise: the kernel's own scores hold every kind of special value
     assert torch.isnan(causal).any() and torch.isposinf(causal).any() and torch.isneginf(causal).any()
-    assert (causal == 0).any() and (causal.abs() > 1e30).any()
+    assert (causal.abs() > 1e30).any()
+    if variant != "output_aware":                         # there ln of the value magnitude shifts the zeros
+        assert (causal == 0).any()
     o_kw = dict(gamma=0.9) if variant == "mass" else {}
     g_idx, g_cnt = oracle.topk(sp_c, ns, nl, k, **o_kw)
     assert torch.equal(cnt.cpu(), g_cnt) and torch.equal(idx.cpu(), g_idx)
