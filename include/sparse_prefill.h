@@ -64,7 +64,9 @@ enum {
                                          n_dense, lists_per_kv_head not 0 or 1               */
     SPA_ERR_BAD_STRIDE = -4,          /* stride not a multiple of 8 / pointer not 16-B aligned */
     SPA_ERR_WORKSPACE_TOO_SMALL = -5, /* ws_bytes < spa_workspace_bytes()                   */
-    SPA_ERR_LAUNCH = -6               /* the HIP runtime rejected a launch                  */
+    SPA_ERR_LAUNCH = -6,              /* the HIP runtime rejected a launch                  */
+    SPA_ERR_STATIC_SCRATCH_TOO_SMALL = -7 /* sparse_prefill_select_static: the call needs more than
+                                         SPA_STATIC_SCRATCH_BYTES of scratch                 */
 };
 
 typedef struct spa_params {
@@ -156,6 +158,30 @@ int sparse_prefill_select(const spa_params *p, const void *q, const void *k,
                           int32_t *block_idx, int32_t *block_cnt,
                           float *pooled_scores_or_null, void *ws, size_t ws_bytes,
                           void *hip_stream);
+
+/* sparse_prefill_select for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * computation, same outputs and same checks as sparse_prefill_select, bit for bit, but the scratch
+ * of the stage (the pooled K in the score kernel's layout; with lists_per_kv_head also the pooled
+ * queries and their group means) lives in a static device array inside the library instead of
+ * `ws`: SPA_STATIC_SCRATCH_BYTES per GPU the library is used on, held until the process ends.  The
+ * call allocates and frees nothing and enqueues only kernels on hip_stream.
+ *   - Limit: 256-byte-aligned regions of
+ *       batch * n_kv_heads * 32 * ceil(NBk / 32) * head_dim * 4 bytes,
+ *     plus, with lists_per_kv_head, batch * (n_q_heads + n_kv_heads) * NB * head_dim * 4 bytes,
+ *     must fit SPA_STATIC_SCRATCH_BYTES (8 MiB: e.g. 8 KV heads x 2048 key blocks x head_dim 128,
+ *     the 262144-token workload); beyond it the call returns SPA_ERR_STATIC_SCRATCH_TOO_SMALL and
+ *     enqueues nothing.
+ *   - Every call on a GPU shares that GPU's one array: calls that overlap in time on the same GPU
+ *     (different streams, or threads) race on it and give unspecified lists; serialise them.  The
+ *     array keeps the previous call's contents; nothing in it has to start at zero (the stage reads
+ *     only what it has written in the same call, stale parts feed columns that are never ranked).
+ *   - The array's address is looked up once per device, on the first call made with that device
+ *     current (a runtime query, no allocation); make that first call outside stream capture. */
+#define SPA_STATIC_SCRATCH_BYTES (8u << 20)
+int sparse_prefill_select_static(const spa_params *p, const void *q, const void *k,
+                                 int32_t *block_idx, int32_t *block_cnt,
+                                 float *pooled_scores_or_null, void *hip_stream);
 
 /* The top-k + static-merge step alone, on caller-supplied scores
  * [batch, n_q_heads, NB, NBk] fp32 (entries beyond the causal limit are ignored).  Given the

@@ -5,7 +5,7 @@ The binding only marshals arguments: every step of the path runs in the HIP
 kernels.  PyTorch supplies device memory and the current stream.
 """
 from .binding import (SpaError, attn, check_lists, fused, library_path, load_library, pool, row_capacity, select,
-                      topk_from_scores, value_norms, workspace_bytes)
+                      select_static, topk_from_scores, value_norms, workspace_bytes)
 
 __all__ = ["SpaError", "attn", "check_lists", "fused", "library_path", "load_library", "pool", "row_capacity",
-           "select", "topk_from_scores", "value_norms", "workspace_bytes"]
+           "select", "select_static", "topk_from_scores", "value_norms", "workspace_bytes"]

@@ -16,7 +16,7 @@ EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_pr
            "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
            "sparse_prefill_fused_tpd", "sparse_prefill_value_norms", "sparse_prefill_select_stem",
            "sparse_prefill_fused_stem", "sparse_prefill_select_ex", "sparse_prefill_topk_from_scores_ex",
-           "sparse_prefill_fused_ex", "sparse_prefill_check_lists")
+           "sparse_prefill_fused_ex", "sparse_prefill_check_lists", "sparse_prefill_select_static")
 
 
 class SpaError(RuntimeError):
@@ -61,6 +61,7 @@ def load_library():
     lib.spa_workspace_bytes.argtypes = [pp, ctypes.POINTER(ctypes.c_size_t)]
     lib.sparse_prefill_pool.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.sparse_prefill_select.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparse_prefill_select_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
     lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_check_lists.argtypes = [pp, vp, vp, vp, vp]
@@ -242,6 +243,33 @@ def select(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softma
         kr = _schedule(top_k_per_block, NB, q.device)
         _check(load_library().sparse_prefill_select_tpd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(kr), _ptr(idx),
                                                         _ptr(cnt), _ptr(sp), _ptr(ws), ws.numel(), _stream(q)))
+    return (idx, cnt, sp) if return_scores else (idx, cnt)
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def select_static(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale=None,
+                  return_scores=False, group_shared=False, seq_lens=None, block_idx=None, block_cnt=None):
+    """sparse_prefill_select_static: the plain select call on the library's own static scratch (no
+    workspace).  block_idx / block_cnt may be passed in (a caller that must not allocate); otherwise
+    they are made here.  Returns (block_idx, block_cnt[, scores])."""
+    _dev_bf16(q, k)
+    p = _params_from(q, k, block_size, n_sink_blocks, n_local_blocks, top_k_blocks, softmax_scale,
+                     group_shared=group_shared, seq_lens=seq_lens)
+    B, Hq, S, _ = q.shape
+    if group_shared:
+        Hq = k.shape[1]
+    NB, T = -(-S // block_size), row_capacity(p)
+    idx = torch.empty((B, Hq, NB, T), dtype=torch.int32, device=q.device) if block_idx is None else block_idx
+    cnt = torch.empty((B, Hq, NB), dtype=torch.int32, device=q.device) if block_cnt is None else block_cnt
+    if tuple(idx.shape) != (B, Hq, NB, T) or tuple(cnt.shape) != (B, Hq, NB) or idx.dtype != torch.int32 \
+            or cnt.dtype != torch.int32 or not idx.is_contiguous() or not cnt.is_contiguous():
+        raise TypeError("block_idx / block_cnt must be contiguous int32 [B,H,NB,T] / [B,H,NB]")
+    NBk = -(-k.shape[2] // block_size)
+    sp = torch.empty((B, Hq, NB, NBk), dtype=torch.float32, device=q.device) if return_scores else None
+    _check(load_library().sparse_prefill_select_static(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(idx), _ptr(cnt), _ptr(sp),
+                                                       _stream(q)))
     return (idx, cnt, sp) if return_scores else (idx, cnt)
 
 

@@ -2,6 +2,8 @@
 // Nothing here allocates, frees or synchronises; see include/sparse_prefill.h.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace spa;
@@ -75,24 +77,51 @@ int set_mass_budget(Dims& d, float mass_gamma) {
 }  // namespace
 
 namespace {
+// The scratch regions of the select stage: pooled Q and the group means (group-shared lists only),
+// pooled K in the score kernel's operand layout, ln of the value magnitudes (output-aware score only).
+struct SelectScratch {
+    float *qp, *kp, *qg, *lvn;
+};
+
+// Shape, pointer and budget checks of a select call; on success d holds the resolved sizes.
+int check_select(const spa_params* p, const void* q, const void* k, const void* v_or_null, float mass_gamma,
+                 const int32_t* block_idx, const int32_t* block_cnt, Dims& d) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if (v_or_null && (rc = check_tensor(v_or_null, p->v_stride, p->head_dim))) return rc;
+    d = resolved(p);
+    return set_mass_budget(d, mass_gamma);
+}
+
+int select_launches(Dims d, const spa_params* p, const void* q, const void* k, const void* v_or_null, const int32_t* k_rows,
+                    const int32_t* head_pattern, int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null,
+                    const SelectScratch& sc, hipStream_t st);
+
 // v_or_null: values for the output-aware ranking score, or nullptr for the plain pooled score
 int select_impl(const spa_params* p, const void* q, const void* k, const void* v_or_null, const int32_t* k_rows,
                 const int32_t* head_pattern, float mass_gamma, int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null, void* ws, size_t ws_bytes,
                 void* hip_stream) {
-    int rc = check_shape(p);
+    Dims d;
+    int rc = check_select(p, q, k, v_or_null, mass_gamma, block_idx, block_cnt, d);
     if (rc) return rc;
-    if (!block_idx || !block_cnt || !ws) return SPA_ERR_NULLPTR;
-    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
-    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
-    if (v_or_null && (rc = check_tensor(v_or_null, p->v_stride, p->head_dim))) return rc;
+    if (!ws) return SPA_ERR_NULLPTR;
     if (((uintptr_t)ws) & (kAlign - 1)) return SPA_ERR_BAD_STRIDE;
-    Dims d = resolved(p);
-    if ((rc = set_mass_budget(d, mass_gamma))) return rc;
     Workspace w = carve(d);
     if (ws_bytes < w.total) return SPA_ERR_WORKSPACE_TOO_SMALL;
-    float* qp = (float*)((char*)ws + w.qp_off);
-    float* kp = (float*)((char*)ws + w.kp_off);
-    hipStream_t st = (hipStream_t)hip_stream;
+    const SelectScratch sc{(float*)((char*)ws + w.qp_off), (float*)((char*)ws + w.kp_off), (float*)((char*)ws + w.qg_off),
+                           (float*)((char*)ws + w.lvn_off)};
+    return select_launches(d, p, q, k, v_or_null, k_rows, head_pattern, block_idx, block_cnt, pooled_scores_or_null, sc,
+                           (hipStream_t)hip_stream);
+}
+
+int select_launches(Dims d, const spa_params* p, const void* q, const void* k, const void* v_or_null, const int32_t* k_rows,
+                    const int32_t* head_pattern, int32_t* block_idx, int32_t* block_cnt, float* pooled_scores_or_null,
+                    const SelectScratch& sc, hipStream_t st) {
+    float* qp = sc.qp;
+    float* kp = sc.kp;
     // Group-shared lists rank the mean of the group's pooled queries, which needs them in memory; all other
     // calls pool K only and let the score kernel pool its own query blocks from Q (the Q stream then hides
     // the scoring and selection)
@@ -101,13 +130,13 @@ int select_impl(const spa_params* p, const void* q, const void* k, const void* v
     if (e != hipSuccess) return SPA_ERR_LAUNCH;
     float* lvn = nullptr;
     if (v_or_null) {
-        lvn = (float*)((char*)ws + w.lvn_off);
+        lvn = sc.lvn;
         if (launch_vnorm(d, v_or_null, strides_of(p->v_stride), lvn, st) != hipSuccess) return SPA_ERR_LAUNCH;
     }
     if (d.shared) {
         // one list per KV head: rank the group by its mean pooled query, then select as if the
         // KV heads were the query heads
-        float* qg = (float*)((char*)ws + w.qg_off);
+        float* qg = sc.qg;
         if (launch_group_mean(d, qp, qg, st) != hipSuccess) return SPA_ERR_LAUNCH;
         d.Hq = d.Hkv;
         d.G = 1;
@@ -151,6 +180,55 @@ int fused_impl(const spa_params* p, const void* q, const void* k, const void* v,
 }
 }  // namespace
 
+
+// ---- scratch that the library owns: for callers that cannot allocate ---------------------------
+// One array per GPU, in the device image of this library, held until the process ends.  In host
+// code the array's name is only a stand-in for the symbol, not a device address: its address on a
+// given device comes from hipGetSymbolAddress, asked once per device with that device current
+// and remembered; everything below uses that pointer, never the name.
+constexpr size_t kStaticScratchBytes = SPA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex scratch_mu;
+void* scratch_ptr[kMaxDevices];             // per device; nullptr = not asked yet
+
+// address of this device's copy of the array, or nullptr with *err set
+void* static_scratch(hipError_t* err) {
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || ptr == nullptr) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
+
+// bytes of scratch a plain select call needs: pooled K in tiles of 32 key blocks, plus, with
+// group-shared lists, the pooled queries and their group means
+struct StaticCarve {
+    size_t kp_off, qp_off, qg_off, total;
+};
+StaticCarve carve_static(const Dims& d) {
+    StaticCarve c;
+    size_t off = 0;
+    c.kp_off = off; off = align_up(off + (size_t)d.B * d.Hkv * ((d.NBk + 31) / 32 * 32) * d.D * sizeof(float));
+    c.qp_off = off; if (d.shared) off = align_up(off + (size_t)d.B * d.Hq * d.NB * d.D * sizeof(float));
+    c.qg_off = off; if (d.shared) off = align_up(off + (size_t)d.B * d.Hkv * d.NB * d.D * sizeof(float));
+    c.total = off;
+    return c;
+}
+}  // namespace
+
 #pragma GCC visibility push(default)
 extern "C" {
 
@@ -163,6 +241,7 @@ const char* spa_strerror(int code) {
         case SPA_ERR_BAD_STRIDE: return "strides must be non-negative multiples of 8 elements, token stride >= head_dim, pointers 16-byte aligned";
         case SPA_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than spa_workspace_bytes()";
         case SPA_ERR_LAUNCH: return "the HIP runtime rejected a kernel launch";
+        case SPA_ERR_STATIC_SCRATCH_TOO_SMALL: return "the call needs more scratch than the library's static device array holds (SPA_STATIC_SCRATCH_BYTES); use the call that takes a workspace";
         default: return "unknown error code";
     }
 }
@@ -202,6 +281,21 @@ int sparse_prefill_select(const spa_params* p, const void* q, const void* k, int
                           void* hip_stream) {
     return select_impl(p, q, k, nullptr, nullptr, nullptr, 0.0f, block_idx, block_cnt, pooled_scores_or_null, ws, ws_bytes,
                        hip_stream);
+}
+
+int sparse_prefill_select_static(const spa_params* p, const void* q, const void* k, int32_t* block_idx,
+                                 int32_t* block_cnt, float* pooled_scores_or_null, void* hip_stream) {
+    Dims d;
+    int rc = check_select(p, q, k, nullptr, 0.0f, block_idx, block_cnt, d);
+    if (rc) return rc;
+    const StaticCarve c = carve_static(d);
+    if (c.total > kStaticScratchBytes) return SPA_ERR_STATIC_SCRATCH_TOO_SMALL;
+    hipError_t e;
+    char* base = (char*)static_scratch(&e);
+    if (base == nullptr) return SPA_ERR_LAUNCH;
+    const SelectScratch sc{(float*)(base + c.qp_off), (float*)(base + c.kp_off), (float*)(base + c.qg_off), nullptr};
+    return select_launches(d, p, q, k, nullptr, nullptr, nullptr, block_idx, block_cnt, pooled_scores_or_null, sc,
+                           (hipStream_t)hip_stream);
 }
 
 int sparse_prefill_select_tpd(const spa_params* p, const void* q, const void* k, const int32_t* top_k_per_block,

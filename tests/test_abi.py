@@ -138,6 +138,29 @@ def test_null_and_misaligned_pointers_rejected_before_launch(lib):
     assert lib.spa_strerror(-99).decode() == "unknown error code"
 
 
+def test_static_scratch_select_rejects_what_does_not_fit(lib):
+    """The size check of the call that allocates nothing is made on the host, before the array's address
+    is even asked for: nothing is enqueued and no GPU is needed."""
+    from paper_2602_21233_amd import binding
+    fake = ctypes.c_void_p(0x10000)                       # never dereferenced: the size check comes first
+    # 16 KV heads x 2048 key blocks x head_dim 128 x 4 bytes = 16 MiB of pooled K: twice the array
+    p = binding.make_params(batch=1, n_q_heads=16, n_kv_heads=16, seq_len=2048 * 128, head_dim=128, block_size=128,
+                            n_sink_blocks=1, n_local_blocks=2, top_k_blocks=8)
+    for f in ("q_stride", "k_stride"):
+        setattr(p, f, (ctypes.c_int64 * 3)(0, 2048 * 128 * 128, 128))
+    assert lib.sparse_prefill_select_static(ctypes.byref(p), fake, fake, fake, fake, None, None) == -7
+    assert b"static" in lib.spa_strerror(-7)
+    # exactly at the limit (8 KV heads) the size check passes and the next check (here: a NULL output) answers
+    p.n_q_heads, p.n_kv_heads = 8, 8
+    assert lib.sparse_prefill_select_static(ctypes.byref(p), fake, fake, None, fake, None, None) == -1
+    # group-shared lists add the pooled queries: 32 + 8 heads x 1024 blocks x 128 x 4 = 20 MiB
+    p = binding.make_params(batch=1, n_q_heads=32, n_kv_heads=8, seq_len=1024 * 128, head_dim=128, block_size=128,
+                            n_sink_blocks=1, n_local_blocks=4, top_k_blocks=64, lists_per_kv_head=1)
+    for f in ("q_stride", "k_stride"):
+        setattr(p, f, (ctypes.c_int64 * 3)(0, 1024 * 128 * 128, 128))
+    assert lib.sparse_prefill_select_static(ctypes.byref(p), fake, fake, fake, fake, None, None) == -7
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
