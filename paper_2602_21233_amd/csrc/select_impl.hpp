@@ -558,48 +558,24 @@ struct ScoreArgs {
     Strides qs;
 };
 
-// Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
-// 512-thread workgroup.  S: R * (MAXC * 64 + 8) floats of LDS for the scores, then 256 counters per
-// wavefront.  Ends without a barrier; the caller must not reuse S before one.
-// The split pooled queries (MFMA A operands) are staged in LDS, in the space of the phase-2 counters,
-// instead of being held in 8 * D / 16 registers per lane: the kernel stays within 128 registers.
-// Needs R * D * 4 bytes <= the counters' 8 KB.
+// Phase 0 of the score kernels: the split pooled queries (MFMA A operands) of the query blocks
+// i0 .. i0 + R - 1 of head bh go to LDS behind the SW words of score space at S, in the space of the
+// phase-2 counters, instead of being held in 8 * D / 16 registers per lane: the kernels stay within
+// 128 registers.  Needs R * D * 4 bytes <= the counters' NWV KB.
 // QPOOL: the workgroup pools its R query blocks from Q itself (the block mean pooling of step 1,
 // same arithmetic in the same order as pool_kernel) instead of reading pooled queries.  Streaming
-// 16 blocks (512 KB) per workgroup with three blocks per 256 threads in flight keeps the HBM busy
+// 16 blocks (512 KB) per workgroup with two blocks per 256 threads in flight keeps the HBM busy
 // while the other workgroup of the CU scores and selects: the Q stream, four fifths of the bytes
-// of the select stage, hides the rest of the stage.
-template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV, bool QPOOL>
-__device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
-    constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
+// of the select stage, hides the rest of the stage.  Ends with a barrier.
+template <int D, int R, int SW, int NWV, bool QPOOL>
+__device__ __forceinline__ void stage_queries(const ScoreArgs& a, const int bh, const int i0, float* S) {
     constexpr int DS = D / 16;
-    const float* __restrict__ qp = a.qp;
-    const float* __restrict__ kp = a.kp;
-    const int Hq = a.Hq, G = a.G, NB = a.NB, NBk = a.NBk, off = a.off, T = a.T;
-    Pattern pt = a.pt;
-    int k = a.k;
-    const int32_t* __restrict__ k_rows = a.k_rows;
-    const int32_t* __restrict__ head_pattern = a.head_pattern;
-    const float* __restrict__ lvn = a.lvn;
-    const float scale = a.scale;
-    int32_t* __restrict__ idx = a.idx;
-    int32_t* __restrict__ cnt = a.cnt;
-    float* __restrict__ scores_out = a.scores_out;
-
-    const int b = bh / Hq, h = bh % Hq;
-    const int Hkv = Hq / G;
-    const float* qbase = qp + (int64_t)bh * NB * D;
-    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * ((NBk + 31) >> 5) * (32 * D);   // tiled, see fetch_tile
-    const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NBk : nullptr;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int half = lane >> 5, l32 = lane & 31;
-    const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
-    const int n_jt = ((i_last + off) >> 5) + 1;           // 32-wide key-block tiles with some causal j
-
-    // ---- phase 1 ---------------------------------------------------------------------
+    const int NB = a.NB;
+    const int b = bh / a.Hq, h = bh % a.Hq;
+    const float* qbase = a.qp + (int64_t)bh * NB * D;
     // LDS copy of the split queries: the 8 dims 16s + 8 * half .. +7 of row r, part p (0 = hi, 1 = lo)
     // at bf16 offset ((((s * 2 + p) * R + r) * 2 + half) * 8
-    __bf16* const qlds = reinterpret_cast<__bf16*>(S + R * LD);
+    __bf16* const qlds = reinterpret_cast<__bf16*>(S + SW);
     static_assert(R * D * 4 <= NWV * 256 * 4, "staged queries must fit the counters' space");
     if constexpr (QPOOL) {
         constexpr int TPR = D / 8, RPP = 256 / TPR;      // lanes per token row, token rows per pass
@@ -607,13 +583,13 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         constexpr int ROWS = (R + NGRP - 1) / NGRP;      // query blocks per group
         constexpr int DEPTH = 2;                         // blocks in flight per group
         // the partial sums live in the score rows' space, or (short rows) behind the counters
-        constexpr bool PART_IN_S = 2 * NGRP * RPP * D <= R * LD;
+        constexpr bool PART_IN_S = 2 * NGRP * RPP * D <= SW;
         const int t = threadIdx.x, grp = t >> 8, t256 = t & 255;
         const int prow = t256 / TPR, chunk = t256 % TPR;
         const int Bs = a.Bs, passes = Bs / RPP;          // at most 8
         const int Sq_b = entry_len(a.seq_lens, b, a.S);
         typedef float (*Part)[D];
-        Part const part = reinterpret_cast<Part>(PART_IN_S ? S : S + R * LD + NWV * 256) + grp * 2 * RPP;   // two buffers of RPP rows per group
+        Part const part = reinterpret_cast<Part>(PART_IN_S ? S : S + SW + NWV * 256) + grp * 2 * RPP;   // two buffers of RPP rows per group
         const uint16_t* const qhead = a.q + b * a.qs.b + h * a.qs.h;
         const int64_t tstride = a.qs.t;
         // tokens of this group's rr-th block that exist (0: block past the call, the entry or the tile)
@@ -708,6 +684,42 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
         }
         __syncthreads();
     }
+}
+
+// Scores, top-k and merged lists of the query blocks i0 .. i0 + R - 1 of head bh = b * Hq + h, by a
+// 512-thread workgroup.  S: R * (MAXC * 64 + 8) floats of LDS for the scores, then 256 counters per
+// wavefront.  Ends without a barrier; the caller must not reuse S before one.
+// The split pooled queries are staged in LDS by stage_queries (QPOOL: pooled from Q in the kernel).
+template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV, bool QPOOL>
+__device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh, const int i0, float* S) {
+    constexpr int LD = MAXC * 64 + 8;          // +8 words: the two lane halves of a store hit different banks
+    constexpr int DS = D / 16;
+    const float* __restrict__ kp = a.kp;
+    const int Hq = a.Hq, G = a.G, NB = a.NB, NBk = a.NBk, off = a.off, T = a.T;
+    Pattern pt = a.pt;
+    int k = a.k;
+    const int32_t* __restrict__ k_rows = a.k_rows;
+    const int32_t* __restrict__ head_pattern = a.head_pattern;
+    const float* __restrict__ lvn = a.lvn;
+    const float scale = a.scale;
+    int32_t* __restrict__ idx = a.idx;
+    int32_t* __restrict__ cnt = a.cnt;
+    float* __restrict__ scores_out = a.scores_out;
+
+    const int b = bh / Hq, h = bh % Hq;
+    const int Hkv = Hq / G;
+    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * ((NBk + 31) >> 5) * (32 * D);   // tiled, see fetch_tile
+    const float* lvbase = lvn != nullptr ? lvn + (int64_t)(b * Hkv + h / G) * NBk : nullptr;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
+    const int n_jt = ((i_last + off) >> 5) + 1;           // 32-wide key-block tiles with some causal j
+
+    // ---- phase 0 / phase 1 ------------------------------------------------------------
+    // LDS copy of the split queries: the 8 dims 16s + 8 * half .. +7 of row r, part p (0 = hi, 1 = lo)
+    // at bf16 offset ((((s * 2 + p) * R + r) * 2 + half) * 8
+    stage_queries<D, R, R * LD, NWV, QPOOL>(a, bh, i0, S);
+    const __bf16* const qlds = reinterpret_cast<const __bf16*>(S + R * LD);
     // The pooled K arrives tiled in operand layout and already split into bf16 head and tail:
     // tile jt of 32 key blocks is 32 * D * 4 bytes, and the 8 dims 16s + 8 * half .. +7 of block
     // l32 sit at bf16 offset (((2s + half) * 2 + part) * 32 + l32) * 8 (part 0 = hi, 1 = lo), so
@@ -860,6 +872,219 @@ __device__ __forceinline__ void score_topk_rows(const ScoreArgs& a, const int bh
     }
 }
 
+// Column-chunked variant for rows of 1025 .. 2048 key blocks: R = 16 query blocks per workgroup, as
+// for 1024-block rows, so that every pooled-K tile a workgroup reads from L2 serves 16 rows (8-row
+// workgroups re-read the pooled K twice as often: 5.2 GB against the 2.7 GB Q stream at 262144
+// tokens, and use a quarter of every MFMA), while the scores in LDS stay those of one chunk of
+// CW = 1024 key blocks: 66 KB, two workgroups per CU.  A wavefront owns two rows; the scores of the
+// first chunk wait in registers (16 per lane and row) while the second chunk is scored, then each
+// row is selected exactly as in the plain kernel, from 32 scores per lane.  (No cumulative-mass
+// variant: that budget keeps the 8-row kernel.)
+template <int D, int R, int MAXCH, bool EXT, int NWV, bool QPOOL>
+__device__ __forceinline__ void score_topk_rows_chunked(const ScoreArgs& a, const int bh, const int i0, float* S) {
+    constexpr int CC = 16;                     // 64-block register chunks per column chunk
+    constexpr int CW = CC * 64;                // key blocks per column chunk
+    constexpr int LD = CW + 8;
+    constexpr int DS = D / 16;
+    constexpr int RPW = R / NWV;               // rows per wavefront
+    constexpr int MAXC = MAXCH * CC;
+    static_assert(R % NWV == 0 && MAXCH == 2, "two column chunks");
+    const float* __restrict__ kp = a.kp;
+    const int Hq = a.Hq, G = a.G, NB = a.NB, NBk = a.NBk, off = a.off, T = a.T;
+    Pattern pt = a.pt;
+    int k = a.k;
+    const float scale = a.scale;
+    int32_t* __restrict__ idx = a.idx;
+    int32_t* __restrict__ cnt = a.cnt;
+    float* __restrict__ scores_out = a.scores_out;
+
+    const int b = bh / Hq, h = bh % Hq;
+    const int Hkv = Hq / G;
+    const float* kbase = kp + (int64_t)(b * Hkv + h / G) * ((NBk + 31) >> 5) * (32 * D);
+    const float* lvbase = a.lvn != nullptr ? a.lvn + (int64_t)(b * Hkv + h / G) * NBk : nullptr;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int i_last = (i0 + R - 1 < NB - 1) ? i0 + R - 1 : NB - 1;
+    const int n_jt = ((i_last + off) >> 5) + 1;           // 32-wide key-block tiles with some causal j
+    const int n_ch = (i_last + off) / CW + 1;             // column chunks with some causal j (workgroup-uniform)
+
+    stage_queries<D, R, R * LD, NWV, QPOOL>(a, bh, i0, S);
+    const __bf16* const qlds = reinterpret_cast<const __bf16*>(S + R * LD);
+
+    head_config(a.head_pattern, h, pt, k);
+    const int NB_b = (entry_len(a.seq_lens, b, a.S) + a.Bs - 1) / a.Bs;      // ragged batch
+    pt.NB = off + NB_b;
+
+    bf16x8 kraw[2 * DS];                                  // [2s] = hi, [2s + 1] = lo of slice s
+    auto tile_ptr = [&](int jt) {
+        return reinterpret_cast<const __bf16*>(kbase + (int64_t)jt * (32 * D)) + (half * 64 + l32) * 8;
+    };
+    // scores of column chunk c into S (phase 1 of the plain kernel, restricted to the chunk's tiles)
+    auto score_chunk = [&](int c) {
+        const int jt_end = n_jt < (c + 1) * (CW / 32) ? n_jt : (c + 1) * (CW / 32);
+        const int jt_first = c * (CW / 32) + wave;
+        if (jt_first < jt_end) {
+            const __bf16* src = tile_ptr(jt_first);
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                kraw[2 * s] = *reinterpret_cast<const bf16x8*>(src + s * 1024);
+                kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
+            }
+        }
+        for (int jt = jt_first; jt < jt_end; jt += NWV) {
+            const int j = 32 * jt + l32;
+            const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
+            const __bf16* next = tile_ptr(jt + NWV < jt_end ? jt + NWV : jt);
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                const bf16x8 k_hi = kraw[2 * s], k_lo = kraw[2 * s + 1];
+                const bf16x8 qh = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 0) * R + l32 % R) * 2 + half) * 8);
+                const bf16x8 ql = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 1) * R + l32 % R) * 2 + half) * 8);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ql, k_hi, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_lo, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_hi, acc, 0, 0, 0);
+                kraw[2 * s] = *reinterpret_cast<const bf16x8*>(next + s * 1024);
+                kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(next + s * 1024 + 256);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int mrow = 8 * (r >> 2) + 4 * half + (r & 3);
+                if (mrow < R) {
+                    const float sc = lvbase != nullptr ? scale * acc[r] + lv : scale * acc[r];
+                    S[mrow * LD + j - c * CW] = sc;
+                    const int i = i0 + mrow;
+                    if (scores_out != nullptr && i < NB && j < NBk)
+                        scores_out[((int64_t)bh * NB + i) * NBk + j] = j <= i + off ? sc : -INFINITY;
+                }
+            }
+        }
+    };
+    // scores of the blocks c * CW + 64 m + lane of row r from the chunk's scores in S (columns past the
+    // computed tiles hold junk; they lie beyond the causal limit and are never candidates)
+    auto load_scores = [&](int r, float* x) {
+        const float* srow = S + r * LD;
+#pragma unroll
+        for (int m = 0; m < CC; ++m) x[m] = srow[(m << 6) + lane];
+    };
+
+    float x0[RPW][CC];                                    // first-chunk scores of this wavefront's rows
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+        for (int m = 0; m < CC; ++m) x0[rr][m] = -INFINITY;
+    score_chunk(0);
+    __syncthreads();
+    if (n_ch > 1) {                                       // workgroup-uniform
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr) {
+            const int iq = i0 + wave + rr * NWV;
+            if (iq < NB && iq < NB_b) load_scores(wave + rr * NWV, x0[rr]);
+        }
+        __syncthreads();                                  // every row's first-chunk scores are in registers
+        score_chunk(1);
+        __syncthreads();
+    }
+    if (scores_out != nullptr) {                          // key blocks past the last computed tile
+        const int j_first = 32 * n_jt;
+        for (int r = 0; r < R && i0 + r < NB; ++r)
+            for (int j = j_first + (int)threadIdx.x; j < NBk; j += NWV * 64)
+                scores_out[((int64_t)bh * NB + i0 + r) * NBk + j] = -INFINITY;
+    }
+
+    // ---- selection, row by row, as in the plain kernel; the staged queries are not needed any more,
+    // their space holds the counters of the search ----
+    uint32_t* const hist = reinterpret_cast<uint32_t*>(S + R * LD) + 256 * wave;
+    static_for_sel<RPW>([&](auto rr_tag) {
+        constexpr int rr = decltype(rr_tag)::value;
+        const int r = wave + rr * NWV;
+        const int iq = i0 + r;
+        if (iq >= NB) return;                             // wave-uniform
+        const int64_t row = (int64_t)bh * NB + iq;
+        int32_t* idx_row = idx + row * T;
+        if (iq >= NB_b) {                                 // past the entry's end: empty list
+            for (int t = lane; t < T; t += 64) idx_row[t] = -1;
+            if (lane == 0) cnt[row] = 0;
+            return;
+        }
+        const int i = iq + off;
+        const int n = i + 1;
+        const int chunks = (n + 63) >> 6;
+        float x[MAXC];
+        if (n_ch > 1) {
+#pragma unroll
+            for (int m = 0; m < CC; ++m) x[m] = x0[rr][m];
+            load_scores(r, x + CC);
+        } else {
+            load_scores(r, x);
+#pragma unroll
+            for (int m = CC; m < MAXC; ++m) x[m] = -INFINITY;
+        }
+        const int k_i = row_budget(a.k_rows, iq, k);
+        {
+            uint32_t key[MAXC];
+            uint64_t is_static_bits = 0ull;
+            int ncl = 0;
+#pragma unroll
+            for (int m = 0; m < MAXC; ++m) {
+                key[m] = 0u;
+                if (m < chunks) {
+                    const int j = (m << 6) + lane;
+                    const bool st = j <= i && static_block<EXT>(pt, i, j);
+                    key[m] = (j <= i && !st) ? rank_key(x[m]) : 0u;
+                    is_static_bits |= st ? (1ull << m) : 0ull;
+                    if constexpr (EXT) ncl += key[m] != 0u ? 1 : 0;
+                }
+            }
+            int n_cand;
+            if constexpr (EXT) {
+                n_cand = wave_sum(ncl);
+            } else {                                      // sinks 0 .. ns-1, window i-nl+1 .. i, the rest are candidates
+                const int n_sink = pt.ns < n ? pt.ns : n;
+                const int first_local = i - pt.nl + 1 > n_sink ? i - pt.nl + 1 : n_sink;
+                n_cand = first_local - n_sink;
+            }
+            const int kk = k_i < n_cand ? k_i : n_cand;
+            uint32_t thr;
+            int need_eq;
+            const int nc4 = 4 * chunks;
+            if (nc4 <= MAXC) find_threshold_hist<MAXC, (MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
+            else if (nc4 <= 2 * MAXC) find_threshold_hist<MAXC, (MAXC + 1) / 2>(key, kk, n_cand, hist, lane, thr, need_eq);
+            else if (nc4 <= 3 * MAXC) find_threshold_hist<MAXC, (3 * MAXC + 3) / 4>(key, kk, n_cand, hist, lane, thr, need_eq);
+            else find_threshold_hist<MAXC, MAXC>(key, kk, n_cand, hist, lane, thr, need_eq);
+            int eq_seen = 0, out_pos = 0;
+#pragma unroll
+            for (int m = 0; m < MAXC; ++m) {
+                if (m < chunks) {
+                    const uint32_t kv = key[m];
+                    const bool is_eq = need_eq > 0 && kv == thr && kv != 0u;
+                    const uint64_t eq_mask = __ballot(is_eq);
+                    const bool take = ((is_static_bits >> m) & 1ull) != 0ull || (kv != 0u && kv > thr) ||
+                                      (is_eq && eq_seen + lanes_below(eq_mask, lane) < need_eq);
+                    const uint64_t take_mask = __ballot(take);
+                    if (take) idx_row[out_pos + lanes_below(take_mask, lane)] = (m << 6) + lane;
+                    eq_seen += __popcll(eq_mask);
+                    out_pos += __popcll(take_mask);
+                }
+            }
+            for (int t = out_pos + lane; t < T; t += 64) idx_row[t] = -1;
+            if (lane == 0) cnt[row] = out_pos;
+        }
+    });
+}
+
+template <int D, int R, int MAXCH, bool EXT, int NWV, bool QPOOL>
+__global__ __launch_bounds__(NWV * 64, 4) void score_topk_chunked_kernel(ScoreArgs a, int n_tiles) {
+    extern __shared__ __attribute__((aligned(128))) float S[];   // [R][1024 + 8] scores of one column chunk, then the staged queries
+    const int nwg = gridDim.x;
+    int wg = blockIdx.x;
+    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);   // each XCD a contiguous slice, as in the plain kernel
+    const int tile = n_tiles - 1 - wg % n_tiles;          // long rows first
+    score_topk_rows_chunked<D, R, MAXCH, EXT, NWV, QPOOL>(a, wg / n_tiles, tile * R, S);
+}
+
 // Two workgroups per CU (4 wavefronts per SIMD): at most 128 registers, which is why the query
 // operands are staged in LDS.
 template <int D, int R, int MAXC, bool EXT, bool MASS, int NWV, bool QPOOL>
@@ -939,6 +1164,26 @@ hipError_t launch_mfma_q(const ScoreCall& c) {
     return launch_mfma_e<D, R, MAXC, EXT, MASS, false>(c);
 }
 
+template <int D, int MAXCH, bool EXT, bool QPOOL>
+hipError_t launch_chunked_e(const ScoreCall& c) {
+    constexpr int R = 16, NWV = 8;
+    constexpr size_t lds = ((size_t)R * (1024 + 8) + NWV * 256) * sizeof(float);
+    static_assert(2 * (NWV / 4) * (256 / (D / 8)) * D <= R * (1024 + 8), "the pooling partial sums fit the score space");
+    hipError_t e = allow_lds((const void*)score_topk_chunked_kernel<D, R, MAXCH, EXT, NWV, QPOOL>, lds);
+    if (e != hipSuccess) return e;
+    const int n_tiles = (c.d.NB + R - 1) / R;
+    dim3 grid((unsigned)(n_tiles * c.d.B * c.d.Hq));
+    hipLaunchKernelGGL((score_topk_chunked_kernel<D, R, MAXCH, EXT, NWV, QPOOL>), grid, dim3(NWV * 64), lds, c.st, c.a, n_tiles);
+    return hipGetLastError();
+}
+
+template <int D, int MAXCH>
+hipError_t launch_chunked(const ScoreCall& c) {
+    const bool qpool = c.a.q != nullptr;
+    if (extended(c.d)) return qpool ? launch_chunked_e<D, MAXCH, true, true>(c) : launch_chunked_e<D, MAXCH, true, false>(c);
+    return qpool ? launch_chunked_e<D, MAXCH, false, true>(c) : launch_chunked_e<D, MAXCH, false, false>(c);
+}
+
 template <int D, int R, int MAXC>
 hipError_t launch_mfma(const ScoreCall& c) {
     const bool mass = c.d.gamma_q16 >= 0;
@@ -961,7 +1206,10 @@ hipError_t launch_mfma_d(const ScoreCall& c) {
     if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
     // 1025 .. 2048 blocks: 8 rows, still two workgroups per CU, so that one can stream its queries while the
     // other scores (0.84 -> 0.81 ms at 262144 tokens against 16 rows by one 16-wave workgroup per CU)
-    if (NBk <= 2048) return launch_mfma<D, 8, 32>(c);
+    // 1025 .. 2048 blocks: 16 rows per workgroup with the columns scored in two chunks of 1024 (not with a
+    // mass budget)
+    const bool chunked = c.d.gamma_q16 < 0;
+    if (NBk <= 2048) return chunked ? launch_chunked<D, 2>(c) : launch_mfma<D, 8, 32>(c);
     return launch_mfma<D, 4, 64>(c);
 }
 
