@@ -455,6 +455,74 @@ def test_select_special_values_through_the_score_kernel(spa, oracle, NB, D, Bs, 
     assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
 
 
+@pytest.mark.parametrize("NB,P_blocks,D,k,kw", [
+    (1025, 0, 128, 96, {}),                                        # one block into the second column chunk
+    (1040, 0, 64, 64, dict(group_shared=True)),                    # a row tile that straddles the chunk border
+    (2048, 0, 128, 200, {}),                                       # both chunks full, a budget of several blocks per lane
+    (1500, 7, 128, 96, dict(schedule=True)),                       # KV prefix: rows shifted against the chunk grid
+    (1300, 0, 128, 40, dict(ragged=[1300, 900])),                  # second entry stays inside the first chunk
+    (1700, 3, 64, 33, dict(stride_blocks=5, n_dense_q_blocks=3)),  # extended static patterns
+    (1200, 0, 128, 50, dict(head_pattern=True, output_aware=True)),
+])
+def test_select_rows_of_1025_to_2048_blocks(spa, oracle, NB, P_blocks, D, k, kw):
+    """Rows of 1025 .. 2048 key blocks take the column-chunked score kernel (16 rows per workgroup, the
+    columns scored in two chunks of 1024, first-chunk scores held in registers meanwhile).  Its
+    scores against the oracle's, its lists against the rule on its own scores (from the oracle and
+    from the caller-score kernel), with every option that changes its control flow."""
+    Bs, ns, nl = 64, 2, 3
+    kw = dict(kw)
+    lens = kw.pop("ragged", None)
+    B = 1 if lens is None else len(lens)
+    Hq, Hkv = 2, 1
+    S, P = NB * Bs - 17, P_blocks * Bs                             # a partial last block as well
+    g = torch.Generator().manual_seed(NB + k)
+    q = torch.randn((B, Hq, S, D), generator=g).to(torch.bfloat16)
+    kk = torch.randn((B, Hkv, P + S, D), generator=g).to(torch.bfloat16)
+    v = (torch.randn((B, Hkv, P + S, D), generator=g) * (0.25 + torch.rand((B, Hkv, P + S, 1), generator=g))).to(torch.bfloat16)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    NBq, off = -(-S // Bs), P_blocks
+    shared = kw.get("group_shared", False)
+    Hl = Hkv if shared else Hq
+    kr = _schedules(NBq, k)["decay"] if kw.pop("schedule", False) else None
+    hp = None
+    if kw.pop("head_pattern", False):
+        hp = torch.tensor([[1, 2, k // 2], [2, 3, k]][:Hl], dtype=torch.int32)
+    output_aware = kw.pop("output_aware", False)
+    if lens is not None:
+        lens = [n * Bs - 17 for n in lens]
+    dl = None if lens is None else torch.tensor(lens, dtype=torch.int32).cuda()
+    sel_kw = dict(kw, seq_lens=dl, top_k_per_block=None if kr is None else kr.cuda(),
+                  head_pattern=None if hp is None else hp.cuda(), v=dv if output_aware else None)
+    idx, cnt, sp = spa.select(dq, dk, Bs, ns, nl, k, return_scores=True, **sel_kw)
+    idx2, cnt2 = spa.select(dq, dk, Bs, ns, nl, k, **sel_kw)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)            # the score output does not change the lists
+    o_kw = dict(stride=kw.get("stride_blocks", 0), n_dense=kw.get("n_dense_q_blocks", 0), head_pattern=hp)
+    t_kw = dict(stride_blocks=kw.get("stride_blocks", 0), n_dense_q_blocks=kw.get("n_dense_q_blocks", 0),
+                head_pattern=None if hp is None else hp.cuda())
+    for b in range(B):
+        n = S if lens is None else lens[b]
+        nb = -(-n // Bs)
+        sp_b = sp[b:b + 1, :, :nb, :off + nb].contiguous()
+        w_idx, w_cnt = oracle.topk(sp_b.cpu(), ns, nl, k, None if kr is None else kr[:nb].contiguous(), **o_kw)
+        Tw = w_idx.shape[-1]
+        assert torch.equal(cnt[b, :, :nb].cpu(), w_cnt[0]), b
+        assert torch.equal(idx[b, :, :nb, :Tw].cpu(), w_idx[0]) and (idx[b, :, :nb, Tw:] == -1).all(), b
+        assert (cnt[b, :, nb:] == 0).all() and (idx[b, :, nb:] == -1).all(), b
+        t_idx, t_cnt = spa.topk_from_scores(sp_b, ns, nl, k, top_k_per_block=None if kr is None else kr[:nb].contiguous().cuda(),
+                                            **t_kw)
+        assert torch.equal(t_idx[0], idx[b, :, :nb, :Tw]) and torch.equal(t_cnt[0], cnt[b, :, :nb]), b
+    # the scores themselves, on rows on both sides of the chunk border and at the ends
+    if lens is None and not output_aware:
+        o_qp, o_kp = oracle.pool(q, Bs), oracle.pool(kk, Bs)
+        if shared:
+            o_qp = o_qp.view(B, Hkv, Hq // Hkv, NBq, D).double().mean(2).float()
+        rows = sorted({0, 1, min(1023 - off, NBq - 1), min(1024 - off, NBq - 1), min(1025 - off, NBq - 1), NBq - 2, NBq - 1})
+        o_sp = oracle.scores(o_qp, o_kp, oracle.default_scale(D))
+        for i in rows:
+            torch.testing.assert_close(sp[:, :, i, : off + i + 1].cpu(), o_sp[:, :, i, : off + i + 1], rtol=1e-4, atol=1e-5)
+            assert torch.isneginf(sp[:, :, i, off + i + 1:]).all()
+
+
 # ------------------------------------------------ cumulative-mass budget
 @pytest.mark.parametrize("NB", [1, 19, 65, 300, 1100])
 @pytest.mark.parametrize("ns,nl,k,gamma", [(1, 2, 40, 0.9), (0, 1, 400, 0.5), (2, 3, 9, 0.99), (1, 4, 64, 0.75),
