@@ -7,10 +7,11 @@ heads, head_dim 128, block 128, sink 1 + local 4 + top-k 64).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N] [--no-cpu-baseline]
-                    [--variant uniform|tpd|stem|strided|trishape|shared|mass] [--sample-power]
+                    [--variant uniform|tpd|stem|strided|trishape|shared|mass] [--no-sample-power]
 
---sample-power adds the shader clock and socket power the driver reports (sysfs), sampled from a side
-thread every 20 ms while the timed steps run (use enough steps for a loop of two seconds or more).
+The line carries, under "power", the shader clock and socket power the driver reports in sysfs, sampled
+from a side thread every 20 ms while the timed steps run (--no-sample-power leaves it out; a loop of two
+seconds or more, e.g. --steps 150, gives the settled values).
 
 --variant (default uniform = the headline) times the same workload under the other selection
 rules the library has: a position-decaying budget (tpd), that plus the output-aware ranking
@@ -137,8 +138,8 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="overwrite a 1-GiB scratch buffer before every step (cold caches; for the small "
                          "workloads); ms_per_step then comes from the events, not the wall clock")
-    ap.add_argument("--sample-power", action="store_true",
-                    help="sample the reported shader clock and socket power during the timed steps")
+    ap.add_argument("--no-sample-power", action="store_true",
+                    help="do not sample the reported shader clock and socket power during the timed steps")
     ap.add_argument("--variant", choices=("uniform", "tpd", "stem", "strided", "trishape", "shared", "mass"),
                     default="uniform")
     args = ap.parse_args()
@@ -208,7 +209,7 @@ def main():
         step()
     torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    sampler = PowerSampler() if args.sample_power else None
+    sampler = None if args.no_sample_power else PowerSampler()
     if sampler:
         sampler.start()
     t0 = time.perf_counter()

@@ -55,3 +55,32 @@ def test_static_scratch_select_group_shared_and_ragged(spa):
         want_idx, want_cnt = spa.select(q, k, 64, 1, 4, 6, **kw)
         got_idx, got_cnt = spa.select_static(q, k, 64, 1, 4, 6, **kw)
         assert torch.equal(got_cnt, want_cnt) and torch.equal(got_idx, want_idx), kw
+
+
+def test_static_scratch_select_replays_from_a_hip_graph(spa):
+    """What the call is for: recorded into a HIP graph (its first call on the device, which looks the
+    array's address up, was made before the capture), then replayed with eager work and
+    synchronisations in between; every replay reproduces the eager lists."""
+    q, k = _qk(1, 4, 2, 40 * 128, 40 * 128, 128, 504)
+    Bs, ns, nl, tk = 128, 1, 2, 6
+    want_idx, want_cnt = spa.select(q, k, Bs, ns, nl, tk)
+    idx, cnt = torch.empty_like(want_idx), torch.empty_like(want_cnt)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        spa.select_static(q, k, Bs, ns, nl, tk, block_idx=idx, block_cnt=cnt)       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        spa.select_static(q, k, Bs, ns, nl, tk, block_idx=idx, block_cnt=cnt)
+    for rep in range(3):
+        idx.fill_(-5)
+        cnt.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, want_idx) and torch.equal(cnt, want_cnt), rep
+        q2, k2 = _qk(1, 2, 1, 9 * 64, 9 * 64, 64, 505 + rep)                    # eager work on the same array in between
+        spa.select_static(q2, k2, 64, 1, 1, 2)
+        torch.cuda.synchronize()
