@@ -2,7 +2,8 @@
 // Sec. 4.1.1 of the AngelSlim report), head_dim 128 or 64, blocks of 128 or 64 tokens.
 //
 // Transposed formulation: S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_32x32x16_bf16, one
-// workgroup per (batch, head, query block), one wavefront per 32 query rows.  A lane then
+// workgroup per (batch, head, query block) (two heads of a KV group per workgroup when the group
+// shares its block list), one wavefront per 32 query rows.  A lane then
 // owns the logits of one query: the rescale factor is a per-lane scalar and exp(S^T) is
 // already the B operand of the second product.  Built around what the LDS can deliver:
 //   * V is transposed once per call into a workspace ([.., block, d, token]) by
@@ -139,12 +140,13 @@ struct RowDeal {
     int n_dense, run, seq_len;
 };
 
-RowDeal deal_rows(const Dims& d) {
+// nh: query heads served by one workgroup (their workgroups per row position number G / nh)
+RowDeal deal_rows(const Dims& d, int nh) {
     RowDeal r;
     r.n_dense = d.n_dense < d.NB ? d.n_dense : d.NB;
     r.run = (d.stride > 0 || d.n_dense > 0) ? 1 : 8;
     const int runs = (d.NB - r.n_dense + r.run - 1) / r.run;
-    r.seq_len = (((r.n_dense + 7) >> 3) + ((runs + 7) >> 3) * r.run) * d.G;
+    r.seq_len = (((r.n_dense + 7) >> 3) + ((runs + 7) >> 3) * r.run) * (d.G / nh);
     return r;
 }
 
@@ -159,13 +161,18 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-template <int BS, int D>
-__global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
+// NH: query heads of one KV group served by one workgroup (BS / 32 wavefronts each).  NH = 2 is for
+// lists shared by the group (one list per KV head): the heads then walk the same key blocks, and
+// two of them take every K and V^T sub-tile from one staged copy, which halves the tile traffic
+// (L2 -> LDS) per FLOP; with blocks of 64 tokens it also puts two wavefronts on every SIMD.
+template <int BS, int D, int NH>
+__global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)) void attn_kernel(
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
     float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens) {
-    constexpr int NW = BS / 32;         // wavefronts
+    constexpr int NWH = BS / 32;        // wavefronts per head
+    constexpr int NW = NWH * NH;        // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
     constexpr int DS = D / 16;          // 16-dim slices of a key row = MFMAs of one logits tile
     constexpr int DT = D / 32;          // 32-row tiles of O^T = MFMAs per 16 keys of the second product
@@ -188,7 +195,8 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     const int slot = blockIdx.x >> 3;
     const int head_slot = slot / deal.seq_len;            // b * Hkv + kv head
     const int within = slot % deal.seq_len;
-    const int pos = within / G;                           // position in this XCD's row sequence
+    const int GH = G / NH;                                // workgroups per row position
+    const int pos = within / GH;                          // position in this XCD's row sequence
     const int n_single = (deal.n_dense + 7) >> 3;
     int i;
     if (pos < n_single) {
@@ -201,11 +209,9 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
         if (ridx >= NB - deal.n_dense) return;
         i = NB - deal.n_dense - 1 - ridx;
     }
-    const int g = within % G;
     const int Hkv = Hq / G;
     const int kvh = head_slot % Hkv;
     const int b = head_slot / Hkv;
-    const int h = kvh * G + g;
     // ragged batch: this entry's own length; query blocks past it leave (the whole workgroup, before any barrier)
     const int Sb = entry_len(seq_lens, b, S);
     if (i * BS >= Sb) return;
@@ -215,6 +221,8 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
+    const int wq = wave % NWH;                            // which 32 queries of the block
+    const int h = kvh * G + (within % GH) * NH + wave / NWH;   // this wavefront's query head
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
@@ -294,11 +302,11 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     issue_v(IC<0>{}, 0, block_at(0));
     if (n_st > 1) issue_k(IC<1>{}, 1, blk_of(1));
 
-    // Q^T fragments (B operand): query row 32*wave + l32, dims 16s + 8*half .. +7
+    // Q^T fragments (B operand): query row 32*wq + l32, dims 16s + 8*half .. +7
     bf16x8 qf[DS];
     {
         // rows past the end of a partial last block read the last token (their results are never stored)
-        int qr = 32 * wave + l32;
+        int qr = 32 * wq + l32;
         if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
         const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
 #pragma unroll
@@ -334,14 +342,14 @@ __global__ __launch_bounds__(BS * 2, BS / 64) void attn_kernel(
     float mcb = 0.f;
     float l_run = 0.f;           // this lane's half of the running denominator (sum of bf16 weights)
     const float c = scale * 1.44269504088896340736f;
-    const int q_in_blk = 32 * wave + l32;
+    const int q_in_blk = 32 * wq + l32;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
 
     // causal mask inside the diagonal block: register r of a chunk holds key
     // 64*sub + 32*kc + 16*(r>>3) + 8*half + (r&7) of the block
     auto mask_diag = [&](f32x16& s, int sub, int kc) {
-        if (KT * sub + 32 * kc + 31 > 32 * wave) {
+        if (KT * sub + 32 * kc + 31 > 32 * wq) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kpos = KT * sub + 32 * kc + 16 * (r >> 3) + 8 * half + (r & 7);
@@ -593,6 +601,18 @@ __global__ __launch_bounds__(256) void check_lists_kernel(const int32_t* __restr
 
 __global__ void zero_i32_kernel(int32_t* p) { *p = 0; }
 
+template <int BS, int D, int NH>
+hipError_t launch_nh(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                     const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse, void* vt, hipStream_t st) {
+    const RowDeal deal = deal_rows(d, NH);
+    const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
+    if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((attn_kernel<BS, D, NH>), dim3((unsigned)nwg), dim3(BS * 2 * NH), 0, st, (const uint16_t*)q, qs,
+                       (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens);
+    return hipGetLastError();
+}
+
 template <int BS, int D>
 hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* v,
                   Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
@@ -601,13 +621,9 @@ hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strid
                        (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt, d.seq_lens, d.S);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const RowDeal deal = deal_rows(d);
-    const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
-    if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_kernel<BS, D>), dim3((unsigned)nwg), dim3(BS * 2), 0, st, (const uint16_t*)q, qs,
-                       (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens);
-    return hipGetLastError();
+    // lists shared by the heads of a group: two heads per workgroup take every tile from one staged copy
+    if (d.shared && d.G % 2 == 0) return launch_nh<BS, D, 2>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, st);
+    return launch_nh<BS, D, 1>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, st);
 }
 
 }  // namespace
