@@ -915,18 +915,24 @@ __device__ __forceinline__ void score_topk_rows_chunked(const ScoreArgs& a, cons
     const int NB_b = (entry_len(a.seq_lens, b, a.S) + a.Bs - 1) / a.Bs;      // ragged batch
     pt.NB = off + NB_b;
 
-    bf16x8 kraw[2 * DS];                                  // [2s] = hi, [2s + 1] = lo of slice s
     auto tile_ptr = [&](int jt) {
         return reinterpret_cast<const __bf16*>(kbase + (int64_t)jt * (32 * D)) + (half * 64 + l32) * 8;
     };
-    // scores of column chunk c into S (phase 1 of the plain kernel, restricted to the chunk's tiles)
-    auto score_chunk = [&](int c) {
+    // Scores of column chunk c into S (phase 1 of the plain kernel, restricted to the chunk's tiles).
+    // NBUF = DS: the whole-tile register pipeline of the plain kernel (a slice's registers are refilled
+    // with the same slice of the wave's next tile as soon as its three products are issued).
+    // NBUF = DS / 2, for the second chunk, when 32 registers per lane hold the first chunk's scores: a
+    // rolling buffer of half a tile; slot s % NBUF holds slice s and is refilled with slice s + NBUF,
+    // of this tile or the next, so a load still has half a tile of MFMA work to arrive.
+    auto score_chunk = [&](int c, auto nbuf_tag) {
+        constexpr int NBUF = decltype(nbuf_tag)::value;
+        bf16x8 kraw[2 * NBUF];                            // [2b] = hi, [2b + 1] = lo of the slice in slot b
         const int jt_end = n_jt < (c + 1) * (CW / 32) ? n_jt : (c + 1) * (CW / 32);
         const int jt_first = c * (CW / 32) + wave;
         if (jt_first < jt_end) {
             const __bf16* src = tile_ptr(jt_first);
 #pragma unroll
-            for (int s = 0; s < DS; ++s) {
+            for (int s = 0; s < NBUF; ++s) {
                 kraw[2 * s] = *reinterpret_cast<const bf16x8*>(src + s * 1024);
                 kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(src + s * 1024 + 256);
             }
@@ -934,20 +940,24 @@ __device__ __forceinline__ void score_topk_rows_chunked(const ScoreArgs& a, cons
         for (int jt = jt_first; jt < jt_end; jt += NWV) {
             const int j = 32 * jt + l32;
             const float lv = lvbase != nullptr ? lvbase[j < NBk ? j : NBk - 1] : 0.f;
-            const __bf16* next = tile_ptr(jt + NWV < jt_end ? jt + NWV : jt);
+            const __bf16* cur = tile_ptr(jt);
+            const __bf16* next = tile_ptr(jt + NWV < jt_end ? jt + NWV : jt);      // the last tile refills from itself: in bounds, never used
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
-                const bf16x8 k_hi = kraw[2 * s], k_lo = kraw[2 * s + 1];
+                const int slot = s % NBUF;
+                const bf16x8 k_hi = kraw[2 * slot], k_lo = kraw[2 * slot + 1];
                 const bf16x8 qh = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 0) * R + l32 % R) * 2 + half) * 8);
                 const bf16x8 ql = *reinterpret_cast<const bf16x8*>(qlds + (((s * 2 + 1) * R + l32 % R) * 2 + half) * 8);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ql, k_hi, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_lo, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh, k_hi, acc, 0, 0, 0);
-                kraw[2 * s] = *reinterpret_cast<const bf16x8*>(next + s * 1024);
-                kraw[2 * s + 1] = *reinterpret_cast<const bf16x8*>(next + s * 1024 + 256);
+                const int s_fill = (s + NBUF) % DS;                               // the slice this slot holds next
+                const __bf16* from = s + NBUF < DS ? cur : next;
+                kraw[2 * slot] = *reinterpret_cast<const bf16x8*>(from + s_fill * 1024);
+                kraw[2 * slot + 1] = *reinterpret_cast<const bf16x8*>(from + s_fill * 1024 + 256);
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -975,7 +985,7 @@ __device__ __forceinline__ void score_topk_rows_chunked(const ScoreArgs& a, cons
     for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int m = 0; m < CC; ++m) x0[rr][m] = -INFINITY;
-    score_chunk(0);
+    score_chunk(0, IC_sel<DS>{});
     __syncthreads();
     if (n_ch > 1) {                                       // workgroup-uniform
 #pragma unroll
@@ -984,7 +994,7 @@ __device__ __forceinline__ void score_topk_rows_chunked(const ScoreArgs& a, cons
             if (iq < NB && iq < NB_b) load_scores(wave + rr * NWV, x0[rr]);
         }
         __syncthreads();                                  // every row's first-chunk scores are in registers
-        score_chunk(1);
+        score_chunk(1, IC_sel<DS / 2>{});
         __syncthreads();
     }
     if (scores_out != nullptr) {                          // key blocks past the last computed tile
