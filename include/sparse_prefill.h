@@ -213,6 +213,30 @@ int sparse_prefill_attn(const spa_params *p, const void *q, const void *k, const
                         void *out, float *lse_or_null, void *ws, size_t ws_bytes,
                         void *hip_stream);
 
+/* The attention kernel reads V transposed per key block (both of its matrix-core operands are then
+ * plain 16-byte reads of the staged tile): sparse_prefill_attn makes that copy in `ws` on every
+ * call.  A caller that keeps the copy itself, e.g. beside V in its KV cache, so that a chunked
+ * prefill (Sec. 4.1: the KV cache generation stage; kv_prefix_len > 0) does not transpose the
+ * whole prefix again for every chunk, uses these two calls instead; sparse_prefill_attn is exactly
+ * transpose_v of all key blocks into `ws` followed by attn_vt.
+ *   vt: [batch, n_kv_heads, vt_blocks_per_head, head_dim, block_size] bf16, contiguous, 16-byte
+ *       aligned; vt_blocks_per_head >= NBk (the key blocks of this call; room to grow).  Block j of
+ *       (b, kv head) holds V[b, kv head, j*Bs + t, d] at [d, t]; tokens past the end of a partial
+ *       last block are zeros.
+ * sparse_prefill_transpose_v fills the blocks first_block .. first_block + n_blocks - 1 (0 <=
+ *   first_block, first_block + n_blocks <= NBk, else SPA_ERR_BAD_SHAPE; n_blocks = 0 is a no-op)
+ *   from V in the layout of p->v_stride; a block that was partial when it was last written has to
+ *   be written again once it has more tokens.  Uses of p: shape, kv_prefix_len, seq_lens, v_stride.
+ * sparse_prefill_attn_vt is sparse_prefill_attn with that vt in place of v and no workspace. */
+int sparse_prefill_transpose_v(const spa_params *p, const void *v, void *vt,
+                               int64_t vt_blocks_per_head, int32_t first_block, int32_t n_blocks,
+                               void *hip_stream);
+
+int sparse_prefill_attn_vt(const spa_params *p, const void *q, const void *k, const void *vt,
+                           int64_t vt_blocks_per_head, const int32_t *block_idx,
+                           const int32_t *block_cnt, void *out, float *lse_or_null,
+                           void *hip_stream);
+
 /* Check of caller-made lists against the rules sparse_prefill_attn relies on (Sec. 4.1.1: the
  * attention kernel consumes the block-level indices as they are).  For every list row of a query
  * block that exists (ragged batches: inside its entry's length) it tests 1 <= cnt <= T, entries

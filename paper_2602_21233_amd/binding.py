@@ -16,7 +16,8 @@ EXPORTS = ("spa_strerror", "spa_row_capacity", "spa_workspace_bytes", "sparse_pr
            "sparse_prefill_fused", "sparse_prefill_select_tpd", "sparse_prefill_topk_from_scores_tpd",
            "sparse_prefill_fused_tpd", "sparse_prefill_value_norms", "sparse_prefill_select_stem",
            "sparse_prefill_fused_stem", "sparse_prefill_select_ex", "sparse_prefill_topk_from_scores_ex",
-           "sparse_prefill_fused_ex", "sparse_prefill_check_lists", "sparse_prefill_select_static")
+           "sparse_prefill_fused_ex", "sparse_prefill_check_lists", "sparse_prefill_select_static",
+           "sparse_prefill_transpose_v", "sparse_prefill_attn_vt")
 
 
 class SpaError(RuntimeError):
@@ -65,6 +66,8 @@ def load_library():
     lib.sparse_prefill_topk_from_scores.argtypes = [pp, vp, vp, vp, vp]
     lib.sparse_prefill_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_check_lists.argtypes = [pp, vp, vp, vp, vp]
+    lib.sparse_prefill_transpose_v.argtypes = [pp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp]
+    lib.sparse_prefill_attn_vt.argtypes = [pp, vp, vp, vp, ctypes.c_int64, vp, vp, vp, vp, vp]
     lib.sparse_prefill_fused.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_select_tpd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparse_prefill_topk_from_scores_tpd.argtypes = [pp, vp, vp, vp, vp, vp]
@@ -332,6 +335,54 @@ def attn(q, k, v, block_idx, block_cnt, block_size, softmax_scale=None, return_l
     _check(load_library().sparse_prefill_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(block_idx),
                                               _ptr(block_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                               _stream(q)))
+    return (out, lse) if return_lse else out
+
+
+def transpose_v(v, block_size, vt=None, blocks_per_head=None, first_block=0, n_blocks=None, kv_prefix_len=0,
+                seq_lens=None):
+    """sparse_prefill_transpose_v: V [B,Hkv,Skv,D] -> vt [B,Hkv,blocks_per_head,D,Bs] bf16 (made here unless
+    given), blocks first_block .. first_block + n_blocks - 1 (default: all).  With seq_lens (ragged batch),
+    kv_prefix_len says how many of the Skv tokens are the prefix that every entry has in full."""
+    _dev_bf16(v)
+    B, Hkv, Skv, D = v.shape
+    p = make_params(batch=B, n_q_heads=Hkv, n_kv_heads=Hkv, seq_len=Skv - kv_prefix_len, head_dim=D,
+                    block_size=block_size, n_sink_blocks=0, n_local_blocks=1, top_k_blocks=0, v=v,
+                    kv_prefix_len=kv_prefix_len, seq_lens=seq_lens)
+    NBk = -(-Skv // block_size)
+    bph = NBk if blocks_per_head is None else int(blocks_per_head)
+    if vt is None:
+        vt = torch.zeros((B, Hkv, bph, D, block_size), dtype=torch.bfloat16, device=v.device)
+    if vt.dtype != torch.bfloat16 or not vt.is_cuda or not vt.is_contiguous() or tuple(vt.shape) != (B, Hkv, bph, D, block_size):
+        raise TypeError("vt must be a contiguous bf16 device tensor [B,Hkv,blocks_per_head,D,Bs]")
+    n = NBk - first_block if n_blocks is None else n_blocks
+    _check(load_library().sparse_prefill_transpose_v(ctypes.byref(p), _ptr(v), _ptr(vt), bph, first_block, n, _stream(v)))
+    return vt
+
+
+def attn_vt(q, k, vt, block_idx, block_cnt, block_size, softmax_scale=None, return_lse=False, out=None,
+            pattern=None, group_shared=False, seq_lens=None):
+    """sparse_prefill_attn_vt: sparse_prefill_attn on a V^T the caller keeps (transpose_v); no workspace."""
+    _dev_bf16(q, k, vt)
+    B, Hq, S, D = q.shape
+    out = torch.empty((B, Hq, S, D), dtype=torch.bfloat16, device=q.device) if out is None else out
+    T = block_idx.shape[-1]
+    if pattern is None:
+        p = _params_from(q, k, block_size, 0, 1, max(T - 1, 0), softmax_scale, out=out, group_shared=group_shared,
+                         seq_lens=seq_lens)
+    else:
+        ns, nl, tk, stride, n_dense, *rest = pattern
+        p = _params_from(q, k, block_size, ns, nl, tk, softmax_scale, out=out, stride_blocks=stride,
+                         n_dense_q_blocks=n_dense, stride_reach_blocks=rest[0] if rest else 0,
+                         group_shared=group_shared, seq_lens=seq_lens)
+    if vt.dim() != 5 or not vt.is_contiguous() or vt.shape[0] != B or vt.shape[1] != k.shape[1] \
+            or tuple(vt.shape[3:]) != (D, block_size):
+        raise TypeError("vt must be contiguous [B,Hkv,blocks_per_head,D,Bs]")
+    if row_capacity(p) != T or block_idx.dtype != torch.int32 or block_cnt.dtype != torch.int32 \
+            or not block_idx.is_contiguous() or not block_cnt.is_contiguous():
+        raise TypeError("block_idx must be contiguous int32 [B,Hq,NB,T] with T <= NB")
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device=q.device) if return_lse else None
+    _check(load_library().sparse_prefill_attn_vt(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(vt), vt.shape[2], _ptr(block_idx),
+                                                 _ptr(block_cnt), _ptr(out), _ptr(lse), _stream(q)))
     return (out, lse) if return_lse else out
 
 

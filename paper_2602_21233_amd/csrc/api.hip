@@ -338,6 +338,37 @@ int sparse_prefill_attn(const spa_params* p, const void* q, const void* k, const
                                    strides_of(p->o_stride), lse_or_null, (char*)ws + w.vt_off, st));
 }
 
+int sparse_prefill_transpose_v(const spa_params* p, const void* v, void* vt, int64_t vt_blocks_per_head,
+                               int32_t first_block, int32_t n_blocks, void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!vt) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(v, p->v_stride, p->head_dim))) return rc;
+    if (((uintptr_t)vt) & 15u) return SPA_ERR_BAD_STRIDE;
+    const Dims d = resolved(p);
+    if (vt_blocks_per_head < d.NBk || first_block < 0 || n_blocks < 0 || (int64_t)first_block + n_blocks > d.NBk)
+        return SPA_ERR_BAD_SHAPE;
+    return launch_code(launch_transpose_v(d, v, strides_of(p->v_stride), vt, vt_blocks_per_head, first_block, n_blocks,
+                                          (hipStream_t)hip_stream));
+}
+
+int sparse_prefill_attn_vt(const spa_params* p, const void* q, const void* k, const void* vt, int64_t vt_blocks_per_head,
+                           const int32_t* block_idx, const int32_t* block_cnt, void* out, float* lse_or_null,
+                           void* hip_stream) {
+    int rc = check_shape(p);
+    if (rc) return rc;
+    if (!block_idx || !block_cnt || !vt) return SPA_ERR_NULLPTR;
+    if ((rc = check_tensor(q, p->q_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(k, p->k_stride, p->head_dim))) return rc;
+    if ((rc = check_tensor(out, p->o_stride, p->head_dim))) return rc;
+    if (((uintptr_t)vt) & 15u) return SPA_ERR_BAD_STRIDE;
+    const Dims d = resolved(p);
+    if (vt_blocks_per_head < d.NBk) return SPA_ERR_BAD_SHAPE;
+    return launch_code(launch_attn_vt(d, q, strides_of(p->q_stride), k, strides_of(p->k_stride), vt, vt_blocks_per_head,
+                                      block_idx, block_cnt, out, strides_of(p->o_stride), lse_or_null,
+                                      (hipStream_t)hip_stream));
+}
+
 int sparse_prefill_check_lists(const spa_params* p, const int32_t* block_idx, const int32_t* block_cnt,
                                int32_t* n_bad_rows, void* hip_stream) {
     int rc = check_shape(p);

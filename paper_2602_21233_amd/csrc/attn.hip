@@ -77,14 +77,15 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_
 __device__ __forceinline__ int swap_bits23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
 // ---------------------------------------------------------------------------
-// V [B,Hkv,S,D] (strided) -> Vt [B,Hkv,NB,D,BS] contiguous.
+// V [B,Hkv,S,D] (strided) -> Vt [B,Hkv,vt_bph,D,BS] contiguous, blocks first .. first + gridDim.x - 1.
+// vt_bph: blocks per head in the V^T allocation (>= the key blocks of the call); first: first block to do
 template <int BS, int D>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, Strides vs, int Hkv,
-                                                          int NB, int S, uint16_t* __restrict__ vt,
-                                                          const int32_t* __restrict__ seq_lens, int Sq) {
+                                                          int64_t vt_bph, int S, uint16_t* __restrict__ vt,
+                                                          const int32_t* __restrict__ seq_lens, int Sq, int first) {
     constexpr int PITCH = D + 2;
     __shared__ uint16_t tile[BS * PITCH];
-    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int blk = first + blockIdx.x, bh = blockIdx.y;
     const int b = bh / Hkv, h = bh % Hkv;
     const uint16_t* src = v + b * vs.b + h * vs.h + (int64_t)blk * BS * vs.t;
     const int tid = threadIdx.x;
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
         dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
     }
     __syncthreads();
-    uint16_t* dstb = vt + (((int64_t)bh * NB + blk) * D) * BS;
+    uint16_t* dstb = vt + (((int64_t)bh * vt_bph + blk) * D) * BS;
     constexpr int CPR = BS / 8;         // 16-byte chunks per output row
 #pragma unroll
     for (int p = 0; p < BS * D / 8 / 256; ++p) {
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
     const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
     uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
-    float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens) {
+    float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens, int64_t vt_bph) {
     constexpr int NWH = BS / 32;        // wavefronts per head
     constexpr int NW = NWH * NH;        // wavefronts
     constexpr int NSUB = BS / KT;       // sub-tiles per key block
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
-    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * NBk) * D * BS;      // K, V, V^T may carry a prefix
+    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * vt_bph) * D * BS;   // K, V, V^T may carry a prefix
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
     const int32_t* sel = idx + row_id * T;
@@ -603,27 +604,32 @@ __global__ void zero_i32_kernel(int32_t* p) { *p = 0; }
 
 template <int BS, int D, int NH>
 hipError_t launch_nh(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                     const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse, void* vt, hipStream_t st) {
+                     const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse, const void* vt, int64_t vt_bph,
+                     hipStream_t st) {
     const RowDeal deal = deal_rows(d, NH);
     const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_kernel<BS, D, NH>), dim3((unsigned)nwg), dim3(BS * 2 * NH), 0, st, (const uint16_t*)q, qs,
                        (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens);
+                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens, vt_bph);
     return hipGetLastError();
 }
 
 template <int BS, int D>
-hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* v,
-                  Strides vs, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
-                  void* vt, hipStream_t st) {
-    hipLaunchKernelGGL((transpose_v_kernel<BS, D>), dim3(d.NBk, d.B * d.Hkv), dim3(256), 0, st,
-                       (const uint16_t*)v, vs, d.Hkv, d.NBk, d.Skv, (uint16_t*)vt, d.seq_lens, d.S);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+hipError_t launch_tv(const Dims& d, const void* v, Strides vs, void* vt, int64_t vt_bph, int first, int n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL((transpose_v_kernel<BS, D>), dim3(n, d.B * d.Hkv), dim3(256), 0, st,
+                       (const uint16_t*)v, vs, d.Hkv, vt_bph, d.Skv, (uint16_t*)vt, d.seq_lens, d.S, first);
+    return hipGetLastError();
+}
+
+template <int BS, int D>
+hipError_t launch(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                  const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
+                  const void* vt, int64_t vt_bph, hipStream_t st) {
     // lists shared by the heads of a group: two heads per workgroup take every tile from one staged copy
-    if (d.shared && d.G % 2 == 0) return launch_nh<BS, D, 2>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, st);
-    return launch_nh<BS, D, 1>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, st);
+    if (d.shared && d.G % 2 == 0) return launch_nh<BS, D, 2>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
+    return launch_nh<BS, D, 1>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
 }
 
 }  // namespace
@@ -641,15 +647,33 @@ hipError_t launch_check_lists(const Dims& d, const int32_t* idx, const int32_t* 
     return hipGetLastError();
 }
 
-hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
-                            const void* v, Strides vs, const int32_t* idx, const int32_t* cnt, void* out,
-                            Strides os, float* lse, void* vt, hipStream_t st) {
-    if (vt == nullptr) return hipErrorInvalidValue;
-    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
-    if (d.D == 128 && d.Bs == 64) return launch<64, 128>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
-    if (d.D == 64 && d.Bs == 128) return launch<128, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
-    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, v, vs, idx, cnt, out, os, lse, vt, st);
+hipError_t launch_transpose_v(const Dims& d, const void* v, Strides vs, void* vt, int64_t vt_bph, int first, int n,
+                              hipStream_t st) {
+    if (vt == nullptr || vt_bph < d.NBk || first < 0 || n < 0 || first + n > d.NBk) return hipErrorInvalidValue;
+    if (d.D == 128 && d.Bs == 128) return launch_tv<128, 128>(d, v, vs, vt, vt_bph, first, n, st);
+    if (d.D == 128 && d.Bs == 64) return launch_tv<64, 128>(d, v, vs, vt, vt_bph, first, n, st);
+    if (d.D == 64 && d.Bs == 128) return launch_tv<128, 64>(d, v, vs, vt, vt_bph, first, n, st);
+    if (d.D == 64 && d.Bs == 64) return launch_tv<64, 64>(d, v, vs, vt, vt_bph, first, n, st);
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_vt(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* vt,
+                          int64_t vt_bph, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
+                          hipStream_t st) {
+    if (vt == nullptr || vt_bph < d.NBk) return hipErrorInvalidValue;
+    if (d.D == 128 && d.Bs == 128) return launch<128, 128>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
+    if (d.D == 128 && d.Bs == 64) return launch<64, 128>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
+    if (d.D == 64 && d.Bs == 128) return launch<128, 64>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
+    if (d.D == 64 && d.Bs == 64) return launch<64, 64>(d, q, qs, k, ks, idx, cnt, out, os, lse, vt, vt_bph, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
+                       const void* v, Strides vs, const int32_t* idx, const int32_t* cnt, void* out,
+                       Strides os, float* lse, void* vt, hipStream_t st) {
+    hipError_t e = launch_transpose_v(d, v, vs, vt, d.NBk, 0, d.NBk, st);
+    if (e != hipSuccess) return e;
+    return launch_attn_vt(d, q, qs, k, ks, vt, d.NBk, idx, cnt, out, os, lse, st);
 }
 
 }  // namespace spa

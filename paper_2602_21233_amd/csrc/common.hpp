@@ -84,5 +84,12 @@ hipError_t launch_check_lists(const Dims& d, const int32_t* idx, const int32_t* 
 hipError_t launch_attn(const Dims& d, const void* q, Strides qs, const void* k, Strides ks,
                        const void* v, Strides vs, const int32_t* idx, const int32_t* cnt,
                        void* out, Strides os, float* lse, void* vt, hipStream_t st);
+// The two halves of launch_attn: V -> V^T for the key blocks first .. first + n - 1 into an allocation of
+// vt_bph blocks per head ([B, Hkv, vt_bph, D, Bs] bf16), and the attention on such a V^T.
+hipError_t launch_transpose_v(const Dims& d, const void* v, Strides vs, void* vt, int64_t vt_bph, int first, int n,
+                              hipStream_t st);
+hipError_t launch_attn_vt(const Dims& d, const void* q, Strides qs, const void* k, Strides ks, const void* vt,
+                          int64_t vt_bph, const int32_t* idx, const int32_t* cnt, void* out, Strides os, float* lse,
+                          hipStream_t st);
 
 }  // namespace spa

@@ -161,6 +161,25 @@ def test_static_scratch_select_rejects_what_does_not_fit(lib):
     assert lib.sparse_prefill_select_static(ctypes.byref(p), fake, fake, fake, fake, None, None) == -7
 
 
+def test_kept_vt_calls_reject_bad_arguments_on_the_host(lib):
+    p = _params()                                          # 8 key blocks of 128 tokens
+    fake = ctypes.c_void_p(0x10000)
+    i64, i32 = ctypes.c_int64, ctypes.c_int32
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, None, i64(8), i32(0), i32(8), None) == -1
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), None, fake, i64(8), i32(0), i32(8), None) == -1
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, ctypes.c_void_p(0x10008), i64(8), i32(0), i32(8), None) == -4
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, fake, i64(7), i32(0), i32(7), None) == -2      # allocation too short
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, fake, i64(8), i32(3), i32(6), None) == -2      # past the last block
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, fake, i64(8), i32(-1), i32(2), None) == -2
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(p), fake, fake, i64(8), i32(2), i32(-1), None) == -2
+    assert lib.sparse_prefill_transpose_v(ctypes.byref(_params(head_dim=96)), fake, fake, i64(8), i32(0), i32(8), None) == -2
+    assert lib.sparse_prefill_attn_vt(ctypes.byref(p), fake, fake, None, i64(8), fake, fake, fake, None, None) == -1
+    assert lib.sparse_prefill_attn_vt(ctypes.byref(p), fake, fake, fake, i64(8), None, fake, fake, None, None) == -1
+    assert lib.sparse_prefill_attn_vt(ctypes.byref(p), fake, fake, fake, i64(7), fake, fake, fake, None, None) == -2
+    assert lib.sparse_prefill_attn_vt(ctypes.byref(p), fake, fake, ctypes.c_void_p(0x10004), i64(8), fake, fake, fake, None, None) == -4
+    assert lib.sparse_prefill_attn_vt(ctypes.byref(p), None, fake, fake, i64(8), fake, fake, fake, None, None) == -1
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

@@ -1077,6 +1077,61 @@ def test_attn_with_malformed_lists_in_a_ragged_batch(spa, D, Bs, P):
         assert (out[b, :, n:].float() == sentinel).all(), b      # tokens past an entry's end are not written
 
 
+# ------------------------------------------------------- a V^T that the caller keeps
+@pytest.mark.parametrize("D,Bs,Hq,Hkv,S,kw", [
+    (128, 128, 4, 2, 7 * 128, {}), (128, 64, 4, 1, 9 * 64 + 30, {}), (64, 128, 2, 2, 5 * 128 - 1, {}),
+    (64, 64, 4, 2, 12 * 64, dict(group_shared=True)), (128, 64, 4, 2, 20 * 64, dict(ragged=[20 * 64, 11 * 64 + 9])),
+])
+def test_attn_on_a_kept_vt_equals_attn(spa, D, Bs, Hq, Hkv, S, kw):
+    """sparse_prefill_attn is transpose_v of every key block into the workspace followed by attn_vt: the two
+    calls made by hand, on a V^T allocation with room to spare, give the same bits."""
+    kw = dict(kw)
+    lens = kw.pop("ragged", None)
+    B = 1 if lens is None else len(lens)
+    q, kk, v = _qkv(B, Hq, Hkv, S, D, 431)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    dl = None if lens is None else torch.tensor(lens, dtype=torch.int32).cuda()
+    ns, nl, k = 1, 2, 3
+    idx, cnt = spa.select(dq, dk, Bs, ns, nl, k, seq_lens=dl, **kw)
+    pat = (ns, nl, k, 0, 0)
+    sentinel = 12352.0
+    want, want_lse = spa.attn(dq, dk, dv, idx, cnt, Bs, return_lse=True, pattern=pat, seq_lens=dl,
+                              out=torch.full_like(dq, sentinel), **kw)
+    NBk = -(-S // Bs)
+    vt = spa.transpose_v(dv, Bs, blocks_per_head=NBk + 5, seq_lens=dl)
+    got, got_lse = spa.attn_vt(dq, dk, vt, idx, cnt, Bs, return_lse=True, pattern=pat, seq_lens=dl,
+                               out=torch.full_like(dq, sentinel), **kw)
+    assert torch.equal(got, want)
+    for b in range(B):
+        n = S if lens is None else lens[b]
+        assert torch.equal(got_lse[b, :, :n], want_lse[b, :, :n]), b
+
+
+def test_chunked_prefill_with_a_kept_vt(spa, oracle):
+    """Chunked prefill the way the kept V^T is meant to be used: one allocation for the whole sequence, every
+    chunk transposes only its own key blocks (the prefix is there already) and attends with attn_vt.  Each
+    chunk equals the workspace call on the same chunk bit for bit, and the oracle within the tolerance."""
+    D, Bs, Hq, Hkv, ns, nl, k = 128, 64, 4, 2, 1, 2, 4
+    S_total = 13 * Bs + 21                                  # the last chunk ends in a partial block
+    q, kk, v = _qkv(1, Hq, Hkv, S_total, D, 433)
+    dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
+    bph = 16
+    vt = torch.full((1, Hkv, bph, D, Bs), float("nan"), dtype=torch.bfloat16, device="cuda")   # stale contents must not matter
+    edges = [0, 4 * Bs, 9 * Bs, S_total]
+    for c in range(3):
+        P, E = edges[c], edges[c + 1]
+        qc, kc, vc = dq[:, :, P:E].contiguous(), dk[:, :, :E].contiguous(), dv[:, :, :E].contiguous()
+        spa.transpose_v(vc, Bs, vt=vt, blocks_per_head=bph, first_block=P // Bs, n_blocks=-(-E // Bs) - P // Bs)
+        idx, cnt = spa.select(qc, kc, Bs, ns, nl, k)
+        want, want_lse = spa.attn(qc, kc, vc, idx, cnt, Bs, return_lse=True)
+        got, got_lse = spa.attn_vt(qc, kc, vt, idx, cnt, Bs, return_lse=True)
+        assert torch.equal(got, want) and torch.equal(got_lse, want_lse), c
+        ref, ref_lse = oracle.attn(q[:, :, P:E].contiguous(), kk[:, :, :E].contiguous(), v[:, :, :E].contiguous(),
+                                   idx.cpu(), cnt.cpu(), Bs)
+        _assert_attn_close(got, ref, f"chunk {c}")
+        assert (got_lse.cpu() - ref_lse).abs().max().item() <= 2e-2
+
+
 # ------------------------------------------------------------- HIP graph replay
 # ------------------------------------------------------------ ragged batches
 @pytest.mark.parametrize("lens,P,Hq,Hkv,D,Bs,kw", [
