@@ -54,11 +54,11 @@ class PowerSampler:
     """Shader clock (pp_dpm_sclk, the level marked current) and socket power (hwmon power1_input or
     power1_average) of the first GPU that exposes them in sysfs, read every `period` seconds."""
 
-    def __init__(self, period=0.02):
+    def __init__(self, period=0.02, root="/sys/class/drm"):
         import glob
         self.period, self.clock, self.power, self._stop, self._thread = period, [], [], False, None
         self.sclk = self.pwr = None
-        for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+        for dev in sorted(glob.glob(os.path.join(root, "card*", "device"))):
             sclk = os.path.join(dev, "pp_dpm_sclk")
             pw = [f for n in ("power1_input", "power1_average") for f in glob.glob(os.path.join(dev, "hwmon", "hwmon*", n))]
             if os.access(sclk, os.R_OK) and pw:

@@ -92,3 +92,30 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_power_sampler_reads_the_current_clock_level_and_the_socket_power(tmp_path):
+    """bench.py's side-thread sampler on a stand-in for the driver's sysfs files: the clock is the level marked
+    current in pp_dpm_sclk, the power is hwmon's power1_input in microwatts; a GPU without the files gives None."""
+    import importlib.util
+    import time
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    dev = tmp_path / "card0" / "device"
+    (dev / "hwmon" / "hwmon3").mkdir(parents=True)
+    (dev / "pp_dpm_sclk").write_text("0: 500Mhz\n1: 1496Mhz *\n2: 2400Mhz\n")
+    (dev / "hwmon" / "hwmon3" / "power1_input").write_text("1340000000\n")
+    s = bench.PowerSampler(period=0.005, root=str(tmp_path))
+    s.start()
+    time.sleep(0.05)
+    (dev / "pp_dpm_sclk").write_text("0: 500Mhz *\n1: 1496Mhz\n2: 2400Mhz\n")
+    time.sleep(0.05)
+    s.stop()
+    out = s.summary()
+    assert out["shader_clock_mhz"]["max"] == 1496.0 and out["shader_clock_mhz"]["min"] == 500.0
+    assert out["socket_power_w"]["median"] == 1340.0 and out["socket_power_w"]["samples"] >= 4
+    empty = bench.PowerSampler(root=str(tmp_path / "nothing"))
+    empty.start()
+    empty.stop()
+    assert empty.summary()["shader_clock_mhz"] is None and empty.summary()["socket_power_w"] is None
