@@ -26,6 +26,8 @@
 //     precision of weights and sums at any magnitude in between.
 //   * a step (32 keys) overlaps three chains: logits of chunk n+2 (MFMA), weights of chunk
 //     n+1 (VALU), O^T += V^T P^T of chunk n (MFMA); its instruction order is fixed by hand.
+// Blocks of 64 tokens with one head per workgroup run attn_chunked_kernel: the same step, staged in
+// 32-key chunks through half the LDS, so that two wavefronts share a SIMD.
 #include <type_traits>
 
 #include "common.hpp"
@@ -574,6 +576,366 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
         lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
 }
 
+// ---------------------------------------------------------------------------
+// Variant for blocks of 64 tokens.  A 64-key tile serves only 64 queries there, so a workgroup is two
+// wavefronts and the 64 KB of tile buffers of the kernel above leave one wavefront per SIMD, with
+// nothing to fill the time its tiles take to arrive.  This one stages K and V^T in 32-key chunks, two
+// stages per operand (32 KB with head_dim 128): four workgroups per CU, two wavefronts per SIMD, one
+// barrier per step (= chunk); the loads of a chunk are requested one step before it is read.  Same
+// arithmetic in the same order: the two kernels give the same bits.
+__device__ __forceinline__ int swz_c(int row) { return (row >> 2) & 3; }     // V^T stage rows are 64 B
+
+template <int BS, int D, int NH>
+__global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
+    const uint16_t* __restrict__ q, Strides qs, const uint16_t* __restrict__ k, Strides ks,
+    const uint16_t* __restrict__ vt, const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+    uint16_t* __restrict__ out, Strides os, float* __restrict__ lse, int Hq, int G, int NB, int T, int S,
+    float scale, RowDeal deal, int shared, int NBk, int Skv_max, const int32_t* __restrict__ seq_lens, int64_t vt_bph) {
+    constexpr int NWH = BS / 32;        // wavefronts per head
+    constexpr int NW = NWH * NH;        // wavefronts
+    constexpr int CPB = BS / 32;        // 32-key chunks per key block
+    constexpr int DS = D / 16;          // MFMAs of one logits tile
+    constexpr int DT = D / 32;          // 32-row tiles of O^T
+    constexpr int NG = 2 * DS;          // MFMAs (= instruction groups) of a step
+    constexpr int STG = 32 * D;         // elements of a stage: one 32-key chunk of K or of V^T (8 KB / 4 KB)
+    constexpr int STG_B = STG * 2;
+    constexpr int CPR = D / 8;          // 16-byte pieces of a K row
+    constexpr int RPI = 64 / CPR;       // K rows filled by one 1-KB load instruction
+    constexpr int LPW = STG / 512 / NW; // 1-KB load instructions per wave per operand per chunk
+    constexpr int DTILE_B = 32 * 32 * 2;  // bytes of 32 d rows of a V^T stage
+    static_assert(LPW >= 1 && CPB >= 2, "blocks of 64 tokens");
+    __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][STG];   // K chunk n in stage n % 2
+    __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][STG];   // V^T chunk n likewise
+
+    // workgroup -> (b, kv head, query block, head in group): as in the kernel above
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int head_slot = slot / deal.seq_len;
+    const int within = slot % deal.seq_len;
+    const int GH = G / NH;
+    const int pos = within / GH;
+    const int n_single = (deal.n_dense + 7) >> 3;
+    int i;
+    if (pos < n_single) {
+        const int hidx = pos * 8 + xcd;
+        if (hidx >= deal.n_dense) return;                 // the whole workgroup leaves, before any barrier
+        i = NB - 1 - hidx;
+    } else {
+        const int rr = pos - n_single;
+        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
+        if (ridx >= NB - deal.n_dense) return;
+        i = NB - deal.n_dense - 1 - ridx;
+    }
+    const int Hkv = Hq / G;
+    const int kvh = head_slot % Hkv;
+    const int b = head_slot / Hkv;
+    const int Sb = entry_len(seq_lens, b, S);
+    if (i * BS >= Sb) return;
+    const int Skv = Skv_max - S + Sb;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int wq = wave % NWH;
+    const int h = kvh * G + (within % GH) * NH + wave / NWH;
+
+    const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
+    const uint16_t* kb = k + b * ks.b + kvh * ks.h;
+    const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * vt_bph) * D * BS;
+    const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
+    const int32_t* sel = idx + row_id * T;
+    // count and entries are clamped as in the kernel above: a malformed list cannot leave the tensors
+    int n_sel = cnt[row_id];
+    n_sel = n_sel < 1 ? 1 : (n_sel > T ? T : n_sel);
+    const int n_ch = n_sel * CPB;                         // chunks (= steps) of the row
+    const int blk_last = (Skv - 1) / BS < NBk - 1 ? (Skv - 1) / BS : NBk - 1;
+    auto blk_of = [&](int n) {                            // key block of chunk n; past the list: its last entry
+        const int e = n / CPB;
+        const int blk = sel[e < n_sel ? e : n_sel - 1];
+        return blk < 0 ? 0 : (blk > blk_last ? blk_last : blk);
+    };
+
+    // direct global->LDS loads, 1 KB per instruction in lane order: 4 K rows of 256 B (8 of 128 B), or
+    // 16 rows of 64 B of a V^T chunk; the XOR swizzle is applied on the global side
+    uint32_t k_offb[LPW], v_offb[LPW];
+#pragma unroll
+    for (int x = 0; x < LPW; ++x) {
+        const int inst = wave * LPW + x;
+        const int krow = RPI * inst + lane / CPR;
+        const int vrow = 16 * inst + (lane >> 2);
+        k_offb[x] = 2u * ((uint32_t)krow * (uint32_t)ks.t + (uint32_t)(((lane % CPR) ^ swz_k<D>(krow)) << 3));
+        v_offb[x] = 2u * (uint32_t)(vrow * BS + (((lane & 3) ^ swz_c(vrow)) << 3));
+    }
+    const uint32_t k_dst = lds_address(&smemK[0][0]) + wave * LPW * 1024;
+    const uint32_t v_dst = lds_address(&smemV[0][0]) + wave * LPW * 1024;
+    auto issue_k = [&](auto stg_tag, int n, int blk) {
+        constexpr int ST = decltype(stg_tag)::value;
+        const int cib = n % CPB;                          // chunk in block
+        if ((blk + 1) * BS <= Skv) {
+            const char* kt = reinterpret_cast<const char*>(kb + ((int64_t)blk * BS + cib * 32) * ks.t);
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                lds_dma16<ST * STG_B + X * 1024>(k_dst, k_offb[X], kt);
+            });
+        } else {
+            // partial last block: key rows past the end re-read the last token (masked for every query that exists)
+            const char* kt = reinterpret_cast<const char*>(kb + (int64_t)blk * BS * ks.t);
+            const int last_row = Skv - 1 - blk * BS;
+            static_for<LPW>([&](auto x_tag) {
+                constexpr int X = decltype(x_tag)::value;
+                const int krow = RPI * (wave * LPW + X) + lane / CPR;
+                int row = cib * 32 + krow;
+                if (row > last_row) row = last_row;
+                const uint32_t off = 2u * ((uint32_t)row * (uint32_t)ks.t + (uint32_t)(((lane % CPR) ^ swz_k<D>(krow)) << 3));
+                lds_dma16<ST * STG_B + X * 1024>(k_dst, off, kt);
+            });
+        }
+    };
+    auto issue_v = [&](auto stg_tag, int n, int blk) {
+        constexpr int ST = decltype(stg_tag)::value;
+        const char* vtt = reinterpret_cast<const char*>(vtb + (int64_t)blk * D * BS + (n % CPB) * 32);
+        static_for<LPW>([&](auto x_tag) {
+            constexpr int X = decltype(x_tag)::value;
+            lds_dma16<ST * STG_B + X * 1024>(v_dst, v_offb[X], vtt);
+        });
+    };
+
+    issue_k(IC<0>{}, 0, blk_of(0));
+    issue_k(IC<1>{}, 1, blk_of(1));
+    issue_v(IC<0>{}, 0, blk_of(0));
+
+    bf16x8 qf[DS];
+    {
+        int qr = 32 * wq + l32;
+        if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;  // rows past the end read the last token; never stored
+        const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
+    }
+    int kofs[DS], vofs[2];
+    {
+        const int row = swap_bits23(l32);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) kofs[s] = 2 * (row * D + (((2 * s + half) ^ swz_k<D>(row)) << 3));
+#pragma unroll
+        for (int x = 0; x < 2; ++x) vofs[x] = 2 * (l32 * 32 + (((2 * x + half) ^ swz_c(l32)) << 3));
+    }
+    const char* const ldsK = reinterpret_cast<const char*>(&smemK[0][0]);
+    const char* const ldsV = reinterpret_cast<const char*>(&smemV[0][0]);
+    auto lds16 = [](const char* p) { return *reinterpret_cast<const bf16x8*>(p); };
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
+    float m_run = -INFINITY;
+    float mcb = 0.f;
+    float l_run = 0.f;
+    const float c = scale * 1.44269504088896340736f;
+    const int q_in_blk = 32 * wq + l32;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
+
+    // causal mask inside the diagonal block: register r of chunk cib holds key 32*cib + 16*(r>>3) + 8*half + (r&7)
+    auto mask_diag = [&](f32x16& s, int cib) {
+        if (32 * cib + 31 > 32 * wq) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kpos = 32 * cib + 16 * (r >> 3) + 8 * half + (r & 7);
+                if (kpos > q_in_blk) s[r] = -INFINITY;
+            }
+        }
+    };
+    auto weights = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        f32x8 e0, e1;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
+            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
+        }
+        p0 = __builtin_convertvector(e0, bf16x8);
+        p1 = __builtin_convertvector(e1, bf16x8);
+        lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
+        }
+    };
+    // moves the reference logit (see the kernel above); always on the first chunk, almost never after
+    auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+        mx = fmaxf(mx, other_half(mx));
+        const float lq = l_run + other_half(l_run);
+        const float lift = lq > 1.0f ? __log2f(lq) / c : 0.0f;
+        const float m_new = fmaxf(m_run + lift, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        m_run = m_new;
+        mcb = m_new * c;
+        l_run *= alpha;
+#pragma unroll
+        for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
+        weights(s, p0, p1, lsum);
+    };
+
+    int blk_v = blk_of(1), blk_k = blk_of(3);             // key blocks of the next V^T and K chunk to request
+
+    // Step n, P = n % 2: logits of chunk n + 2 (K stage P), weights of chunk n + 1, O^T += V^T(chunk n,
+    // stage P) pc^T; the instruction groups of the kernel above.  K chunk n + 2 and V^T chunk n were
+    // requested by step n - 1; after the barrier the stages read by step n - 1 take K chunk n + 3 and
+    // V^T chunk n + 1.
+    auto step = [&](auto p_tag, auto plain_tag, int n, const f32x16& s_cur, f32x16& s_nxt, const bf16x8& pc0,
+                    const bf16x8& pc1, bf16x8& pn0, bf16x8& pn1) {
+        constexpr int P = decltype(p_tag)::value;
+        constexpr bool PLAIN = decltype(plain_tag)::value != 0;
+        auto operand = [&](auto j_tag) {
+            constexpr int j = decltype(j_tag)::value;
+            if constexpr (j % 2 == 0) return lds16(ldsK + P * STG_B + kofs[j / 2]);
+            else return lds16(ldsV + P * STG_B + vofs[(j / 2) / DT] + ((j / 2) % DT) * DTILE_B);
+        };
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's loads have landed
+        __syncthreads();
+        bf16x8 f[4];
+        f[0] = operand(IC<0>{});
+        f[1] = operand(IC<1>{});
+        f[2] = operand(IC<2>{});
+        if (PLAIN || n + 1 < n_ch) issue_v(IC<1 - P>{}, n + 1, blk_v);
+        if (PLAIN || n + 3 < n_ch) issue_k(IC<1 - P>{}, n + 3, blk_k);
+        blk_v = blk_of(n + 2);
+        blk_k = blk_of(n + 4);
+        f32x16 zero;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+        f32x8 e;
+        float l_new = l_run;
+        auto group = [&](auto g_tag) {
+            constexpr int g = decltype(g_tag)::value;
+            if constexpr (g % 2 == 0) {
+                if constexpr (g == 0) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], zero, 0, 0, 0);
+                else s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], s_nxt, 0, 0, 0);
+            } else {
+                constexpr int dc = (g / 2) % DT;
+                if constexpr (g < NG / 2) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc0, oacc[dc], 0, 0, 0);
+                else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc1, oacc[dc], 0, 0, 0);
+            }
+            if constexpr (g + 3 < NG) f[(g + 3) % 4] = operand(IC<g + 3>{});
+            constexpr int HG = NG / 2;               // groups per half of the chunk's 16 logits
+            constexpr int hb = (g / HG) * 8;
+            constexpr int gg = g % HG;
+            constexpr bool first_half = g < HG;
+            auto scale_sub = [&](int x0, int cnt_x) {
+#pragma unroll
+                for (int x = x0; x < x0 + cnt_x; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
+            };
+            auto exps = [&](int x0, int cnt_x) {
+#pragma unroll
+                for (int x = x0; x < x0 + cnt_x; ++x) e[x] = __builtin_amdgcn_exp2f(e[x]);
+            };
+            auto convert = [&]() {
+                if constexpr (first_half) pn0 = __builtin_convertvector(e, bf16x8);
+                else pn1 = __builtin_convertvector(e, bf16x8);
+            };
+            auto sum_and_test = [&]() {
+                const bf16x8 pw = first_half ? pn0 : pn1;
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
+                if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
+            };
+            if constexpr (HG == 8) {                 // head_dim 128
+                if constexpr (gg < 2) scale_sub(4 * gg, 4);
+                else if constexpr (gg < 6) exps(2 * (gg - 2), 2);
+                else if constexpr (gg == 6) convert();
+                else sum_and_test();
+            } else {                                 // head_dim 64
+                static_assert(HG == 4 || HG == 8, "head_dim 64 or 128");
+                if constexpr (gg == 0) scale_sub(0, 8);
+                else if constexpr (gg == 1) exps(0, 4);
+                else if constexpr (gg == 2) exps(4, 4);
+                else { convert(); sum_and_test(); }
+            }
+            SPA_FENCE();
+        };
+        SPA_FENCE();
+        static_for<NG>([&](auto g_tag) { group(g_tag); });
+        if (__any(!(l_new < kRescaleAt))) {
+            float lsum;
+            raise_reference(s_cur, pn0, pn1, lsum);
+            l_new = l_run + lsum;
+        }
+        l_run = l_new;
+        if constexpr (!PLAIN) {                      // the logits just produced: chunk n + 2
+            if (n + 2 >= n_ch) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_nxt[r] = -INFINITY;           // past the end: a stale stage
+            } else if (n + 2 >= n_ch - CPB) {
+                mask_diag(s_nxt, (n + 2) % CPB);                             // the diagonal block ends the list
+            }
+        }
+    };
+
+    // ---- prologue: logits of chunks 0 and 1, weights of chunk 0, then K chunk 2 -----------
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+    __syncthreads();
+    f32x16 sA, sB;                                 // logits of even / odd chunks
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sA[r] = 0.f; sB[r] = 0.f; }
+#pragma unroll
+    for (int sidx = 0; sidx < DS; ++sidx) {
+        sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + kofs[sidx]), qf[sidx], sA, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds16(ldsK + STG_B + kofs[sidx]), qf[sidx], sB, 0, 0, 0);
+    }
+    if (n_ch <= CPB) {                             // the only block is the diagonal one
+        mask_diag(sA, 0);
+        mask_diag(sB, 1);
+    }
+    bf16x8 pA0, pA1, pB0, pB1;                     // weights of even / odd chunks
+    {
+        float lsum;
+        raise_reference(sA, pA0, pA1, lsum);
+        l_run = lsum;
+    }
+    __syncthreads();                               // K chunks 0 and 1 have been read by every wave
+    if (n_ch > 2) issue_k(IC<0>{}, 2, blk_of(2));
+
+    // steps far from the end of the list run without the mask and end-of-list tests
+    int n = 0;
+    const int n_plain = n_ch > CPB + 2 ? (n_ch - CPB - 2) & ~1 : 0;      // n + 3 < n_ch and n + 2 < n_ch - CPB
+    for (; n < n_plain; n += 2) {
+        step(IC<0>{}, IC<1>{}, n, sB, sA, pA0, pA1, pB0, pB1);
+        step(IC<1>{}, IC<1>{}, n + 1, sA, sB, pB0, pB1, pA0, pA1);
+    }
+    for (;;) {
+        step(IC<0>{}, IC<0>{}, n, sB, sA, pA0, pA1, pB0, pB1);
+        if (++n == n_ch) break;
+        step(IC<1>{}, IC<0>{}, n, sA, sB, pB0, pB1, pA0, pA1);
+        if (++n == n_ch) break;
+    }
+
+    // ---- epilogue ----------------------------------------------------------------
+    const float l_tot = l_run + other_half(l_run);
+    const float inv = 1.0f / l_tot;
+    if (i * BS + q_in_blk >= Sb) return;                  // token past the end of a partial last block
+    uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
+#pragma unroll
+    for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            f32x4 o4;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) o4[x] = oacc[dc][4 * rq + x] * inv;
+            *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
+        }
+    if (lse != nullptr && half == 0)
+        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
+}
+
 // One wavefront per list row: counts the rows that break the rules the attention kernel relies on
 // (1 <= cnt <= T, entries strictly ascending, first >= 0, last == the row's diagonal block).
 __global__ __launch_bounds__(256) void check_lists_kernel(const int32_t* __restrict__ idx,
@@ -609,9 +971,16 @@ hipError_t launch_nh(const Dims& d, const void* q, Strides qs, const void* k, St
     const RowDeal deal = deal_rows(d, NH);
     const int64_t nwg = 8ll * deal.seq_len * d.B * d.Hkv;
     if (nwg > 0x7fffffffll) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_kernel<BS, D, NH>), dim3((unsigned)nwg), dim3(BS * 2 * NH), 0, st, (const uint16_t*)q, qs,
-                       (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
-                       d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens, vt_bph);
+    // blocks of 64 tokens, one head per workgroup: the chunked kernel (two wavefronts per SIMD instead of one);
+    // with two heads per workgroup the sub-tile kernel already has them and is the faster one
+    if constexpr (BS == 64 && NH == 1)
+        hipLaunchKernelGGL((attn_chunked_kernel<BS, D, NH>), dim3((unsigned)nwg), dim3(BS * 2 * NH), 0, st, (const uint16_t*)q,
+                           qs, (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq, d.G,
+                           d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens, vt_bph);
+    else
+        hipLaunchKernelGGL((attn_kernel<BS, D, NH>), dim3((unsigned)nwg), dim3(BS * 2 * NH), 0, st, (const uint16_t*)q, qs,
+                           (const uint16_t*)k, ks, (const uint16_t*)vt, idx, cnt, (uint16_t*)out, os, lse, d.Hq,
+                           d.G, d.NB, d.T, d.S, d.scale, deal, d.shared, d.NBk, d.Skv, d.seq_lens, vt_bph);
     return hipGetLastError();
 }
 

@@ -765,6 +765,15 @@ def _sampled_workload_check(spa, oracle, cfg, n_random):
         if flipped:
             vals = [float(s[x]) for x in flipped]
             assert max(vals) - min(vals) < 1e-5, (b, h, i, sorted(flipped))
+    # the three calls a benchmark step makes (select, V transpose into a kept V^T, attention on it) run the
+    # same kernels on the same grids as the one-call entry checked above: same lists, same bits
+    del qp, kp
+    vt = torch.empty((w.batch, w.n_kv_heads, NB, w.head_dim, Bs), dtype=torch.bfloat16, device="cuda")
+    idx2, cnt2 = spa.select(dq, dk, Bs, w.n_sink_blocks, w.n_local_blocks, w.top_k_blocks)
+    spa.transpose_v(dv, Bs, vt=vt)
+    out2, lse2 = spa.attn_vt(dq, dk, vt, idx2, cnt2, Bs, return_lse=True)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    assert torch.equal(out2, out) and torch.equal(lse2, lse)
 
 
 def test_fused_sampled_16k_workload(spa, oracle):
