@@ -1214,10 +1214,9 @@ hipError_t launch_mfma_d(const ScoreCall& c) {
     if (NBk <= 256) return launch_mfma<D, 8, 4>(c);
     if (NBk <= 512) return launch_mfma<D, 8, 8>(c);
     if (NBk <= 1024) return launch_mfma<D, 16, 16>(c);
-    // 1025 .. 2048 blocks: 8 rows, still two workgroups per CU, so that one can stream its queries while the
-    // other scores (0.84 -> 0.81 ms at 262144 tokens against 16 rows by one 16-wave workgroup per CU)
-    // 1025 .. 2048 blocks: 16 rows per workgroup with the columns scored in two chunks of 1024 (not with a
-    // mass budget)
+    // 1025 .. 2048 blocks: 16 rows per workgroup with the columns scored in two chunks of 1024, still two
+    // workgroups per CU (0.84 -> 0.78 ms at 262144 tokens against 8 rows scored in one pass, which is what a
+    // mass budget still takes there)
     const bool chunked = c.d.gamma_q16 < 0;
     if (NBk <= 2048) return chunked ? launch_chunked<D, 2>(c) : launch_mfma<D, 8, 32>(c);
     return launch_mfma<D, 4, 64>(c);
