@@ -164,6 +164,258 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// What the two attention kernels below share: the row a workgroup serves, its block list, the
+// softmax arithmetic of a wavefront, the instruction groups of a pipeline step, the final store.
+// They differ in how the K and V^T tiles are staged.
+
+// Workgroup -> (b, kv head, query block, head in group).  In time, the whole chip works
+// through one KV head after the other, so that the K and V^T of the current head (tens of MB)
+// stay in the memory-side cache; in space, see RowDeal.  All G heads of a group follow each
+// other, they share most of their key blocks.
+struct RowOfWorkgroup {
+    int i, b, kvh;      // query block, batch entry, KV head
+    int first_head;     // first of the workgroup's NH query heads within the group
+    int Sb, Skv;        // this entry's own query and key tokens (ragged batch)
+};
+// false: nothing to do (a surplus workgroup, or a query block past the entry's end); the whole
+// workgroup then leaves, before any barrier
+template <int BS, int NH>
+__device__ __forceinline__ bool row_of_workgroup(const RowDeal& deal, int Hq, int G, int NB, int S, int Skv_max,
+                                                 const int32_t* __restrict__ seq_lens, RowOfWorkgroup& r) {
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int head_slot = slot / deal.seq_len;            // b * Hkv + kv head
+    const int within = slot % deal.seq_len;
+    const int GH = G / NH;                                // workgroups per row position
+    const int pos = within / GH;                          // position in this XCD's row sequence
+    const int n_single = (deal.n_dense + 7) >> 3;
+    if (pos < n_single) {
+        const int hidx = pos * 8 + xcd;
+        if (hidx >= deal.n_dense) return false;
+        r.i = NB - 1 - hidx;
+    } else {
+        const int rr = pos - n_single;
+        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
+        if (ridx >= NB - deal.n_dense) return false;
+        r.i = NB - deal.n_dense - 1 - ridx;
+    }
+    const int Hkv = Hq / G;
+    r.kvh = head_slot % Hkv;
+    r.b = head_slot / Hkv;
+    r.first_head = (within % GH) * NH;
+    r.Sb = entry_len(seq_lens, r.b, S);
+    if (r.i * BS >= r.Sb) return false;
+    r.Skv = Skv_max - S + r.Sb;
+    return true;
+}
+
+// A row's block list.  Lists are the caller's: a count outside [1, T] or a block outside the entry's
+// own key blocks [0, ceil(Skv / BS)) is clamped so that a malformed list can never make the kernel
+// read outside the tensors (the row's output is then unspecified).  The bound is the entry's, not
+// the padded NBk: in a ragged batch a block past the entry's last token would make the
+// partial-block path of the tile loads compute a negative last row.  Skv >= 1.  Scalar work, once
+// per list entry.
+struct BlockList {
+    const int32_t* sel;
+    int n_sel, blk_last;
+    __device__ __forceinline__ BlockList(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, int64_t row_id,
+                                         int T, int Skv, int BS, int NBk)
+        : sel(idx + row_id * T) {
+        const int n = cnt[row_id];
+        n_sel = n < 1 ? 1 : (n > T ? T : n);
+        blk_last = (Skv - 1) / BS < NBk - 1 ? (Skv - 1) / BS : NBk - 1;
+    }
+    __device__ __forceinline__ int at(int e) const {
+        const int blk = sel[e];
+        return blk < 0 ? 0 : (blk > blk_last ? blk_last : blk);
+    }
+    // entry e, or the last one when e is past the end (look-ahead never reads past the list)
+    __device__ __forceinline__ int at_or_last(int e) const { return at(e < n_sel ? e : n_sel - 1); }
+};
+
+// Q^T fragments (B operand of S^T = K Q^T): query row 32*wq + l32 of the block, dims 16s + 8*half .. +7.
+// Rows past the end of a partial last block read the last token (their results are never stored).
+template <int BS, int D>
+__device__ __forceinline__ void load_q_fragments(const uint16_t* qb, int64_t q_stride_t, int i, int Sb, int wq, int l32,
+                                                 int half, bf16x8 (&qf)[D / 16]) {
+    int qr = 32 * wq + l32;
+    if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
+    const uint16_t* qrow = qb + (int64_t)qr * q_stride_t + 8 * half;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
+}
+
+// causal mask inside the diagonal block: register r of the 32-key chunk that starts at key
+// `first_key` of the block holds key first_key + 16*(r>>3) + 8*half + (r&7)
+__device__ __forceinline__ void mask_diagonal_chunk(f32x16& s, int first_key, int wq, int half, int q_in_blk) {
+    if (first_key + 31 > 32 * wq) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kpos = first_key + 16 * (r >> 3) + 8 * half + (r & 7);
+            if (kpos > q_in_blk) s[r] = -INFINITY;
+        }
+    }
+}
+
+// Running softmax of a wavefront: a lane pair (lane, lane ^ 32) owns one query.
+// Weights are w = 2^(x*c - mcb) with mcb = m_run*c, m_run a reference logit (raw).  The reference
+// need not be the running maximum: a common factor 2^-mcb cancels between numerator and
+// denominator, and bf16 weights and fp32 sums keep their relative precision at any magnitude.
+// All it has to do is keep the numbers inside the fp32 range, so it is only moved when the
+// running denominator (which bounds every weight so far) passes kRescaleAt.
+constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
+template <int DT>
+struct RunningSoftmax {
+    f32x16 oacc[DT];             // O^T tiles, unnormalised
+    float m_run, mcb;
+    float l_run;                 // this lane's half of the running denominator (sum of bf16 weights)
+    float c;                     // softmax scale * log2 e
+
+    __device__ __forceinline__ explicit RunningSoftmax(float scale)
+        : m_run(-INFINITY), mcb(0.f), l_run(0.f), c(scale * 1.44269504088896340736f) {
+#pragma unroll
+        for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
+    }
+    __device__ __forceinline__ void weights(const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) const {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        f32x8 e0, e1;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
+            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
+        }
+        p0 = __builtin_convertvector(e0, bf16x8);
+        p1 = __builtin_convertvector(e1, bf16x8);
+        lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
+        }
+    }
+    // Slow path: move the reference so that the chunk `s` has weights <= 1 and the denominator so
+    // far is about 1 or less, rescale what has been accumulated and recompute the chunk's weights.
+    // Always taken on the first chunk, almost never after; wave-uniform.
+    __device__ __forceinline__ void raise_reference(const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
+        mx = fmaxf(mx, other_half(mx));
+        const float lq = l_run + other_half(l_run);          // this query's denominator so far
+        const float lift = lq > 1.0f ? __log2f(lq) / c : 0.0f;
+        const float m_new = fmaxf(m_run + lift, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        m_run = m_new;
+        mcb = m_new * c;
+        l_run *= alpha;
+#pragma unroll
+        for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
+        weights(s, p0, p1, lsum);
+    }
+    // End of a step whose weights pn (of the logits s_cur) brought the denominator to l_new.  The
+    // weights are positive, so the running denominator bounds every one of them: while it stays
+    // below kRescaleAt no weight, and no sum of weights times values, can leave the fp32 range.
+    // Beyond it (or inf / NaN) the chunk has outgrown the reference by far.
+    __device__ __forceinline__ void settle(float l_new, const f32x16& s_cur, bf16x8& pn0, bf16x8& pn1) {
+        if (__any(!(l_new < kRescaleAt))) {
+            float lsum;
+            raise_reference(s_cur, pn0, pn1, lsum);
+            l_new = l_run + lsum;
+        }
+        l_run = l_new;
+    }
+    // normalise and store the wavefront's 32 query rows (orow: this lane's row), LSE by the lower half;
+    // valid = false: a token past the end of a partial last block, nothing is stored
+    template <int D>
+    __device__ __forceinline__ void store(bool valid, uint16_t* orow, float* lse_or_null, int half) const {
+        const float l_tot = l_run + other_half(l_run);
+        const float inv = 1.0f / l_tot;
+        if (!valid) return;
+#pragma unroll
+        for (int dc = 0; dc < DT; ++dc)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 o4;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) o4[x] = oacc[dc][4 * rq + x] * inv;
+                *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
+            }
+        if (lse_or_null != nullptr && half == 0) *lse_or_null = mcb * (0.69314718055994530942f) + __logf(l_tot);
+    }
+};
+
+// Instruction group g of a pipeline step (a step = one 32-key chunk = NG = D / 8 groups, one MFMA each).
+// The MFMA: even groups add slice g / 2 of the logits of chunk n + 2 (A operand `a` = 32 K rows x 16
+// dims), odd groups add V^T (32 d rows x 16 keys) times the weights pc of chunk n into O^T.
+template <int g, int D>
+__device__ __forceinline__ void group_mfma(const bf16x8& a, const bf16x8 (&qf)[D / 16], f32x16& s_nxt,
+                                           f32x16 (&oacc)[D / 32], const bf16x8& pc0, const bf16x8& pc1) {
+    constexpr int NG = D / 8, DT = D / 32;
+    if constexpr (g % 2 == 0) {
+        if constexpr (g == 0) {
+            f32x16 zero;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+            s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[g / 2], zero, 0, 0, 0);
+        } else {
+            s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[g / 2], s_nxt, 0, 0, 0);
+        }
+    } else {
+        constexpr int dc = (g / 2) % DT;
+        if constexpr (g < NG / 2) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pc0, oacc[dc], 0, 0, 0);
+        else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pc1, oacc[dc], 0, 0, 0);
+    }
+}
+// The group's share of the softmax arithmetic of chunk n + 1: its 16 logits s_cur form two halves of
+// 8 (keys 0-15 / 16-31), each turned into weights pn over NG / 2 consecutive groups: scaled
+// differences (8 fma), powers of two (8 exp2), conversion to bf16, denominator.
+template <int g, int D>
+__device__ __forceinline__ void group_weights(const f32x16& s_cur, float c, float mcb, f32x8& e, bf16x8& pn0, bf16x8& pn1,
+                                              float& l_new) {
+    constexpr int NG = D / 8;
+    constexpr int HG = NG / 2;               // groups per half of the chunk's 16 logits
+    constexpr int hb = (g / HG) * 8;         // which half
+    constexpr int gg = g % HG;
+    constexpr bool first_half = g < HG;
+    auto scale_sub = [&](int x0, int n) {
+#pragma unroll
+        for (int x = x0; x < x0 + n; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
+    };
+    auto exps = [&](int x0, int n) {
+#pragma unroll
+        for (int x = x0; x < x0 + n; ++x) e[x] = __builtin_amdgcn_exp2f(e[x]);
+    };
+    auto convert = [&]() {
+        if constexpr (first_half) pn0 = __builtin_convertvector(e, bf16x8);
+        else pn1 = __builtin_convertvector(e, bf16x8);
+    };
+    auto sum_and_test = [&]() {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        const bf16x8 pw = first_half ? pn0 : pn1;
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
+        if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
+    };
+    if constexpr (HG == 8) {                 // head_dim 128: 8 groups per half
+        if constexpr (gg < 2) scale_sub(4 * gg, 4);
+        else if constexpr (gg < 6) exps(2 * (gg - 2), 2);
+        else if constexpr (gg == 6) convert();
+        else sum_and_test();
+    } else {                                 // head_dim 64: 4 groups per half
+        static_assert(HG == 4 || HG == 8, "head_dim 64 or 128");
+        if constexpr (gg == 0) scale_sub(0, 8);
+        else if constexpr (gg == 1) exps(0, 4);
+        else if constexpr (gg == 2) exps(4, 4);
+        else { convert(); sum_and_test(); }
+    }
+}
+
 // NH: query heads of one KV group served by one workgroup (BS / 32 wavefronts each).  NH = 2 is for
 // lists shared by the group (one list per KV head): the heads then walk the same key blocks, and
 // two of them take every K and V^T sub-tile from one staged copy, which halves the tile traffic
@@ -190,62 +442,26 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][TILE];   // K sub-tile t in buffer t % 2
     __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][TILE];   // V^T likewise
 
-    // Workgroup -> (b, kv head, query block, head in group).  In time, the whole chip works
-    // through one KV head after the other, so that the K and V^T of the current head (tens of MB)
-    // stay in the memory-side cache; in space, see RowDeal.  All G heads of a group follow each
-    // other, they share most of their key blocks.
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int head_slot = slot / deal.seq_len;            // b * Hkv + kv head
-    const int within = slot % deal.seq_len;
-    const int GH = G / NH;                                // workgroups per row position
-    const int pos = within / GH;                          // position in this XCD's row sequence
-    const int n_single = (deal.n_dense + 7) >> 3;
-    int i;
-    if (pos < n_single) {
-        const int hidx = pos * 8 + xcd;
-        if (hidx >= deal.n_dense) return;                 // the whole workgroup leaves, before any barrier
-        i = NB - 1 - hidx;
-    } else {
-        const int rr = pos - n_single;
-        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
-        if (ridx >= NB - deal.n_dense) return;
-        i = NB - deal.n_dense - 1 - ridx;
-    }
+    RowOfWorkgroup row;
+    if (!row_of_workgroup<BS, NH>(deal, Hq, G, NB, S, Skv_max, seq_lens, row)) return;
+    const int i = row.i, b = row.b, kvh = row.kvh, Sb = row.Sb, Skv = row.Skv;
     const int Hkv = Hq / G;
-    const int kvh = head_slot % Hkv;
-    const int b = head_slot / Hkv;
-    // ragged batch: this entry's own length; query blocks past it leave (the whole workgroup, before any barrier)
-    const int Sb = entry_len(seq_lens, b, S);
-    if (i * BS >= Sb) return;
-    const int Skv = Skv_max - S + Sb;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int wq = wave % NWH;                            // which 32 queries of the block
-    const int h = kvh * G + (within % GH) * NH + wave / NWH;   // this wavefront's query head
+    const int h = kvh * G + row.first_head + wave / NWH;  // this wavefront's query head
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
     const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * vt_bph) * D * BS;   // K, V, V^T may carry a prefix
     // block lists are per query head, or per KV head when the group shares its selection
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
-    const int32_t* sel = idx + row_id * T;
-    // Lists are the caller's: a count outside [1, T] or a block outside the entry's own key blocks
-    // [0, ceil(Skv / BS)) is clamped so that a malformed list can never make the kernel read outside
-    // the tensors (the row's output is then unspecified).  The bound is the entry's, not the padded
-    // NBk: in a ragged batch a block past the entry's last token would make the partial-block path
-    // below compute a negative last row.  Skv >= 1 here.  Scalar work, once per list entry.
-    int n_sel = cnt[row_id];
-    n_sel = n_sel < 1 ? 1 : (n_sel > T ? T : n_sel);
+    const BlockList list(idx, cnt, row_id, T, Skv, BS, NBk);
+    const int n_sel = list.n_sel;
     const int n_st = n_sel * NSUB;
-    const int blk_last = (Skv - 1) / BS < NBk - 1 ? (Skv - 1) / BS : NBk - 1;
-    auto block_at = [&](int e) {
-        const int blk = sel[e];
-        return blk < 0 ? 0 : (blk > blk_last ? blk_last : blk);
-    };
 
     // Direct global->LDS loads: instruction `inst` of a sub-tile fills 1 KB of LDS in lane order
     // (4 K rows of 256 B or 8 of 128 B, 8 V^T rows of 128 B); the lane picks the global 16-byte chunk whose
@@ -296,25 +512,14 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
             lds_dma16<BUF * TILE_B + X * 1024>(v_dst, v_offb[X], vtt);
         });
     };
-    auto blk_of = [&](int st) {        // key block of sub-tile st (clamped: never read past the list)
-        const int e = st / NSUB;
-        return block_at(e < n_sel ? e : n_sel - 1);
-    };
+    auto blk_of = [&](int st) { return list.at_or_last(st / NSUB); };   // key block of sub-tile st
 
-    issue_k(IC<0>{}, 0, block_at(0));
-    issue_v(IC<0>{}, 0, block_at(0));
+    issue_k(IC<0>{}, 0, list.at(0));
+    issue_v(IC<0>{}, 0, list.at(0));
     if (n_st > 1) issue_k(IC<1>{}, 1, blk_of(1));
 
-    // Q^T fragments (B operand): query row 32*wq + l32, dims 16s + 8*half .. +7
     bf16x8 qf[DS];
-    {
-        // rows past the end of a partial last block read the last token (their results are never stored)
-        int qr = 32 * wq + l32;
-        if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;
-        const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
-#pragma unroll
-        for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
-    }
+    load_q_fragments<BS, D>(qb, qs.t, i, Sb, wq, l32, half, qf);
     // Per-lane LDS byte offsets.  K (A operand of S^T = K Q^T): the lane's key row of chunk 0 and
     // its 8-dim slice s; chunk 1 and the buffer add constants.  The row assignment swaps bits 2
     // and 3, see the file header.  V^T (A operand of O^T += V^T P^T): d row l32 (+32 per d tile, a
@@ -331,72 +536,9 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     const char* const ldsV = reinterpret_cast<const char*>(&smemV[0][0]);
     auto lds16 = [](const char* p) { return *reinterpret_cast<const bf16x8*>(p); };
 
-    f32x16 oacc[DT];
-#pragma unroll
-    for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
-    // Weights are w = 2^(x*c - mcb) with mcb = m_run*c, m_run a reference logit (raw).  The reference
-    // need not be the running maximum: a common factor 2^-mcb cancels between numerator and
-    // denominator, and bf16 weights and fp32 sums keep their relative precision at any magnitude.
-    // All it has to do is keep the numbers inside the fp32 range, so it is only moved when the
-    // running denominator (which bounds every weight so far) passes kRescaleAt.
-    float m_run = -INFINITY;
-    float mcb = 0.f;
-    float l_run = 0.f;           // this lane's half of the running denominator (sum of bf16 weights)
-    const float c = scale * 1.44269504088896340736f;
+    RunningSoftmax<DT> sm(scale);
     const int q_in_blk = 32 * wq + l32;
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
-
-    // causal mask inside the diagonal block: register r of a chunk holds key
-    // 64*sub + 32*kc + 16*(r>>3) + 8*half + (r&7) of the block
-    auto mask_diag = [&](f32x16& s, int sub, int kc) {
-        if (KT * sub + 32 * kc + 31 > 32 * wq) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kpos = KT * sub + 32 * kc + 16 * (r >> 3) + 8 * half + (r & 7);
-                if (kpos > q_in_blk) s[r] = -INFINITY;
-            }
-        }
-    };
-    auto weights = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
-        f32x8 e0, e1;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
-            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
-        }
-        p0 = __builtin_convertvector(e0, bf16x8);
-        p1 = __builtin_convertvector(e1, bf16x8);
-        lsum = 0.f;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
-        }
-    };
-    // Slow path: move the reference so that the chunk `s` has weights <= 1 and the denominator so
-    // far is about 1 or less, rescale what has been accumulated and recompute the chunk's weights.
-    // Always taken on the first chunk, almost never after; wave-uniform.
-    auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
-        float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = fmaxf(mx, other_half(mx));
-        const float lq = l_run + other_half(l_run);          // this query's denominator so far
-        const float lift = lq > 1.0f ? __log2f(lq) / c : 0.0f;
-        const float m_new = fmaxf(m_run + lift, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        m_run = m_new;
-        mcb = m_new * c;
-        l_run *= alpha;
-#pragma unroll
-        for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
-        weights(s, p0, p1, lsum);
-    };
+    auto mask_diag = [&](f32x16& s, int sub, int kc) { mask_diagonal_chunk(s, KT * sub + 32 * kc, wq, half, q_in_blk); };
 
     // The pipeline step n (chunk n = 32 keys) runs three independent chains side by side:
     //   MFMA   s_nxt = logits of chunk n+2 (same chunk position KC of the next sub-tile, K buffer KB)
@@ -410,7 +552,6 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     auto step = [&](auto kb_tag, auto vb_tag, auto kc_tag, const f32x16& s_cur, f32x16& s_nxt, const bf16x8& pc0,
                     const bf16x8& pc1, bf16x8& pn0, bf16x8& pn1, bf16x8 (&f)[4]) {
         constexpr int KB = decltype(kb_tag)::value, VB = decltype(vb_tag)::value, KC = decltype(kc_tag)::value;
-        const char* const kbase = ldsK + KB * TILE_B + KC * CHUNK_B;
         const char* const vbase = ldsV + VB * TILE_B;
         auto operand = [&](auto j_tag) {            // operand j of this step (j < NG) or of the next one
             constexpr int J = decltype(j_tag)::value;
@@ -420,76 +561,20 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
             if constexpr (j % 2 == 0) return lds16(kb2 + kofs[j / 2]);
             else return lds16(vbase + vofs[2 * kc + (j / 2) / DT] + ((j / 2) % DT) * DTILE_B);
         };
-        (void)kbase;
-        f32x16 zero;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
         f32x8 e;
-        float l_new = l_run;
+        float l_new = sm.l_run;
         // Group g holds MFMA g of the step, the LDS read of operand g + 3 and a share of the softmax
-        // arithmetic of the chunk's logits: its 16 logits form two halves of 8 (keys 0-15 / 16-31),
-        // each turned into weights over NG / 2 consecutive groups: scaled differences (8 fma), powers
-        // of two (8 exp2), conversion to bf16, denominator.
+        // arithmetic of the chunk's logits.
         auto group = [&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
-            if constexpr (g % 2 == 0) {
-                if constexpr (g == 0) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], zero, 0, 0, 0);
-                else s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], s_nxt, 0, 0, 0);
-            } else {
-                constexpr int dc = (g / 2) % DT;
-                if constexpr (g < NG / 2) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc0, oacc[dc], 0, 0, 0);
-                else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc1, oacc[dc], 0, 0, 0);
-            }
+            group_mfma<g, D>(f[g % 4], qf, s_nxt, sm.oacc, pc0, pc1);
             if constexpr (g + 3 < NG || KC == 0) f[(g + 3) % 4] = operand(IC<g + 3>{});
-            constexpr int HG = NG / 2;               // groups per half of the chunk's 16 logits
-            constexpr int hb = (g / HG) * 8;         // which half
-            constexpr int gg = g % HG;
-            constexpr bool first_half = g < HG;
-            auto scale_sub = [&](int x0, int n) {
-#pragma unroll
-                for (int x = x0; x < x0 + n; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
-            };
-            auto exps = [&](int x0, int n) {
-#pragma unroll
-                for (int x = x0; x < x0 + n; ++x) e[x] = __builtin_amdgcn_exp2f(e[x]);
-            };
-            auto convert = [&]() {
-                if constexpr (first_half) pn0 = __builtin_convertvector(e, bf16x8);
-                else pn1 = __builtin_convertvector(e, bf16x8);
-            };
-            auto sum_and_test = [&]() {
-                const bf16x8 pw = first_half ? pn0 : pn1;
-#pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
-                if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
-            };
-            if constexpr (HG == 8) {                 // head_dim 128: 8 groups per half
-                if constexpr (gg < 2) scale_sub(4 * gg, 4);
-                else if constexpr (gg < 6) exps(2 * (gg - 2), 2);
-                else if constexpr (gg == 6) convert();
-                else sum_and_test();
-            } else {                                 // head_dim 64: 4 groups per half
-                static_assert(HG == 4 || HG == 8, "head_dim 64 or 128");
-                if constexpr (gg == 0) scale_sub(0, 8);
-                else if constexpr (gg == 1) exps(0, 4);
-                else if constexpr (gg == 2) exps(4, 4);
-                else { convert(); sum_and_test(); }
-            }
+            group_weights<g, D>(s_cur, sm.c, sm.mcb, e, pn0, pn1, l_new);
             SPA_FENCE();
         };
         SPA_FENCE();
         static_for<NG>([&](auto g_tag) { group(g_tag); });
-        // The weights are positive, so the running denominator bounds every one of them: while it
-        // stays below kRescaleAt no weight, and no sum of weights times values, can leave the fp32
-        // range, and bf16 / fp32 keep their relative precision at any magnitude.  Beyond it (or
-        // inf / NaN) the chunk has outgrown the reference maximum by far.
-        if (__any(!(l_new < kRescaleAt))) {
-            float lsum;
-            raise_reference(s_cur, pn0, pn1, lsum);
-            l_new = l_run + lsum;
-        }
-        l_run = l_new;
+        sm.settle(l_new, s_cur, pn0, pn1);
     };
 
     // ---- prologue: logits of the two chunks of sub-tile 0, weights of chunk 0 -----------
@@ -507,8 +592,8 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     {
         if (n_st <= NSUB) mask_diag(sA, 0, 0);     // the only block is the diagonal one
         float lsum;
-        raise_reference(sA, pA0, pA1, lsum);
-        l_run = lsum;
+        sm.raise_reference(sA, pA0, pA1, lsum);
+        sm.l_run = lsum;
     }
     int blk1 = blk_of(1), blk2 = blk_of(2);        // key blocks of sub-tiles t+1 and t+2
 
@@ -559,21 +644,8 @@ __global__ __launch_bounds__(BS * 2 * NH, NH == 1 ? BS / 64 : (BS == 64 ? 2 : 1)
     }
 
     // ---- epilogue ----------------------------------------------------------------
-    const float l_tot = l_run + other_half(l_run);
-    const float inv = 1.0f / l_tot;
-    if (i * BS + q_in_blk >= Sb) return;                  // token past the end of a partial last block
-    uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
-#pragma unroll
-    for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            f32x4 o4;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) o4[x] = oacc[dc][4 * rq + x] * inv;
-            *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
-        }
-    if (lse != nullptr && half == 0)
-        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
+    sm.template store<D>(i * BS + q_in_blk < Sb, out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t,
+                         lse != nullptr ? lse + ((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk : nullptr, half);
 }
 
 // ---------------------------------------------------------------------------
@@ -607,54 +679,25 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
     __shared__ __attribute__((aligned(1024))) uint16_t smemK[2][STG];   // K chunk n in stage n % 2
     __shared__ __attribute__((aligned(1024))) uint16_t smemV[2][STG];   // V^T chunk n likewise
 
-    // workgroup -> (b, kv head, query block, head in group): as in the kernel above
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int head_slot = slot / deal.seq_len;
-    const int within = slot % deal.seq_len;
-    const int GH = G / NH;
-    const int pos = within / GH;
-    const int n_single = (deal.n_dense + 7) >> 3;
-    int i;
-    if (pos < n_single) {
-        const int hidx = pos * 8 + xcd;
-        if (hidx >= deal.n_dense) return;                 // the whole workgroup leaves, before any barrier
-        i = NB - 1 - hidx;
-    } else {
-        const int rr = pos - n_single;
-        const int ridx = ((rr / deal.run) * 8 + xcd) * deal.run + rr % deal.run;
-        if (ridx >= NB - deal.n_dense) return;
-        i = NB - deal.n_dense - 1 - ridx;
-    }
+    RowOfWorkgroup row;
+    if (!row_of_workgroup<BS, NH>(deal, Hq, G, NB, S, Skv_max, seq_lens, row)) return;
+    const int i = row.i, b = row.b, kvh = row.kvh, Sb = row.Sb, Skv = row.Skv;
     const int Hkv = Hq / G;
-    const int kvh = head_slot % Hkv;
-    const int b = head_slot / Hkv;
-    const int Sb = entry_len(seq_lens, b, S);
-    if (i * BS >= Sb) return;
-    const int Skv = Skv_max - S + Sb;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int wq = wave % NWH;
-    const int h = kvh * G + (within % GH) * NH + wave / NWH;
+    const int h = kvh * G + row.first_head + wave / NWH;
 
     const uint16_t* qb = q + b * qs.b + h * qs.h + (int64_t)i * BS * qs.t;
     const uint16_t* kb = k + b * ks.b + kvh * ks.h;
     const uint16_t* vtb = vt + ((int64_t)(b * Hkv + kvh) * vt_bph) * D * BS;
     const int64_t row_id = shared ? ((int64_t)b * Hkv + kvh) * NB + i : ((int64_t)b * Hq + h) * NB + i;
-    const int32_t* sel = idx + row_id * T;
-    // count and entries are clamped as in the kernel above: a malformed list cannot leave the tensors
-    int n_sel = cnt[row_id];
-    n_sel = n_sel < 1 ? 1 : (n_sel > T ? T : n_sel);
-    const int n_ch = n_sel * CPB;                         // chunks (= steps) of the row
-    const int blk_last = (Skv - 1) / BS < NBk - 1 ? (Skv - 1) / BS : NBk - 1;
-    auto blk_of = [&](int n) {                            // key block of chunk n; past the list: its last entry
-        const int e = n / CPB;
-        const int blk = sel[e < n_sel ? e : n_sel - 1];
-        return blk < 0 ? 0 : (blk > blk_last ? blk_last : blk);
-    };
+    const BlockList list(idx, cnt, row_id, T, Skv, BS, NBk);
+    const int n_ch = list.n_sel * CPB;                    // chunks (= steps) of the row
+    auto blk_of = [&](int n) { return list.at_or_last(n / CPB); };      // key block of chunk n
 
     // direct global->LDS loads, 1 KB per instruction in lane order: 4 K rows of 256 B (8 of 128 B), or
     // 16 rows of 64 B of a V^T chunk; the XOR swizzle is applied on the global side
@@ -706,13 +749,9 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
     issue_v(IC<0>{}, 0, blk_of(0));
 
     bf16x8 qf[DS];
-    {
-        int qr = 32 * wq + l32;
-        if (i * BS + qr > Sb - 1) qr = Sb - 1 - i * BS;  // rows past the end read the last token; never stored
-        const uint16_t* qrow = qb + (int64_t)qr * qs.t + 8 * half;
-#pragma unroll
-        for (int s = 0; s < DS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
-    }
+    load_q_fragments<BS, D>(qb, qs.t, i, Sb, wq, l32, half, qf);
+    // per-lane LDS byte offsets of the A operands inside a stage: K row (bits 2 and 3 swapped) and 8-dim
+    // slice s; V^T d row l32 (+32 per d tile) and 8-key slice x
     int kofs[DS], vofs[2];
     {
         const int row = swap_bits23(l32);
@@ -725,64 +764,9 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
     const char* const ldsV = reinterpret_cast<const char*>(&smemV[0][0]);
     auto lds16 = [](const char* p) { return *reinterpret_cast<const bf16x8*>(p); };
 
-    f32x16 oacc[DT];
-#pragma unroll
-    for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dc][r] = 0.f;
-    float m_run = -INFINITY;
-    float mcb = 0.f;
-    float l_run = 0.f;
-    const float c = scale * 1.44269504088896340736f;
+    RunningSoftmax<DT> sm(scale);
     const int q_in_blk = 32 * wq + l32;
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    constexpr float kRescaleAt = 1.099511627776e12f;      // 2^40
-
-    // causal mask inside the diagonal block: register r of chunk cib holds key 32*cib + 16*(r>>3) + 8*half + (r&7)
-    auto mask_diag = [&](f32x16& s, int cib) {
-        if (32 * cib + 31 > 32 * wq) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kpos = 32 * cib + 16 * (r >> 3) + 8 * half + (r & 7);
-                if (kpos > q_in_blk) s[r] = -INFINITY;
-            }
-        }
-    };
-    auto weights = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
-        f32x8 e0, e1;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            e0[x] = __builtin_amdgcn_exp2f(fmaf(s[x], c, -mcb));
-            e1[x] = __builtin_amdgcn_exp2f(fmaf(s[8 + x], c, -mcb));
-        }
-        p0 = __builtin_convertvector(e0, bf16x8);
-        p1 = __builtin_convertvector(e1, bf16x8);
-        lsum = 0.f;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p0[2 * x], p0[2 * x + 1]}, ones, lsum, false);
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{p1[2 * x], p1[2 * x + 1]}, ones, lsum, false);
-        }
-    };
-    // moves the reference logit (see the kernel above); always on the first chunk, almost never after
-    auto raise_reference = [&](const f32x16& s, bf16x8& p0, bf16x8& p1, float& lsum) {
-        float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = fmaxf(mx, other_half(mx));
-        const float lq = l_run + other_half(l_run);
-        const float lift = lq > 1.0f ? __log2f(lq) / c : 0.0f;
-        const float m_new = fmaxf(m_run + lift, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        m_run = m_new;
-        mcb = m_new * c;
-        l_run *= alpha;
-#pragma unroll
-        for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[dc][r] *= alpha;
-        weights(s, p0, p1, lsum);
-    };
+    auto mask_diag = [&](f32x16& s, int cib) { mask_diagonal_chunk(s, 32 * cib, wq, half, q_in_blk); };
 
     int blk_v = blk_of(1), blk_k = blk_of(3);             // key blocks of the next V^T and K chunk to request
 
@@ -809,67 +793,18 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
         if (PLAIN || n + 3 < n_ch) issue_k(IC<1 - P>{}, n + 3, blk_k);
         blk_v = blk_of(n + 2);
         blk_k = blk_of(n + 4);
-        f32x16 zero;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
         f32x8 e;
-        float l_new = l_run;
+        float l_new = sm.l_run;
         auto group = [&](auto g_tag) {
             constexpr int g = decltype(g_tag)::value;
-            if constexpr (g % 2 == 0) {
-                if constexpr (g == 0) s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], zero, 0, 0, 0);
-                else s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], qf[g / 2], s_nxt, 0, 0, 0);
-            } else {
-                constexpr int dc = (g / 2) % DT;
-                if constexpr (g < NG / 2) oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc0, oacc[dc], 0, 0, 0);
-                else oacc[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g % 4], pc1, oacc[dc], 0, 0, 0);
-            }
+            group_mfma<g, D>(f[g % 4], qf, s_nxt, sm.oacc, pc0, pc1);
             if constexpr (g + 3 < NG) f[(g + 3) % 4] = operand(IC<g + 3>{});
-            constexpr int HG = NG / 2;               // groups per half of the chunk's 16 logits
-            constexpr int hb = (g / HG) * 8;
-            constexpr int gg = g % HG;
-            constexpr bool first_half = g < HG;
-            auto scale_sub = [&](int x0, int cnt_x) {
-#pragma unroll
-                for (int x = x0; x < x0 + cnt_x; ++x) e[x] = fmaf(s_cur[hb + x], c, -mcb);
-            };
-            auto exps = [&](int x0, int cnt_x) {
-#pragma unroll
-                for (int x = x0; x < x0 + cnt_x; ++x) e[x] = __builtin_amdgcn_exp2f(e[x]);
-            };
-            auto convert = [&]() {
-                if constexpr (first_half) pn0 = __builtin_convertvector(e, bf16x8);
-                else pn1 = __builtin_convertvector(e, bf16x8);
-            };
-            auto sum_and_test = [&]() {
-                const bf16x8 pw = first_half ? pn0 : pn1;
-#pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    l_new = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pw[2 * x], pw[2 * x + 1]}, ones, l_new, false);
-                if constexpr (g == NG - 1) asm volatile("" : "+v"(l_new));   // keep the sums inside their groups
-            };
-            if constexpr (HG == 8) {                 // head_dim 128
-                if constexpr (gg < 2) scale_sub(4 * gg, 4);
-                else if constexpr (gg < 6) exps(2 * (gg - 2), 2);
-                else if constexpr (gg == 6) convert();
-                else sum_and_test();
-            } else {                                 // head_dim 64
-                static_assert(HG == 4 || HG == 8, "head_dim 64 or 128");
-                if constexpr (gg == 0) scale_sub(0, 8);
-                else if constexpr (gg == 1) exps(0, 4);
-                else if constexpr (gg == 2) exps(4, 4);
-                else { convert(); sum_and_test(); }
-            }
+            group_weights<g, D>(s_cur, sm.c, sm.mcb, e, pn0, pn1, l_new);
             SPA_FENCE();
         };
         SPA_FENCE();
         static_for<NG>([&](auto g_tag) { group(g_tag); });
-        if (__any(!(l_new < kRescaleAt))) {
-            float lsum;
-            raise_reference(s_cur, pn0, pn1, lsum);
-            l_new = l_run + lsum;
-        }
-        l_run = l_new;
+        sm.settle(l_new, s_cur, pn0, pn1);
         if constexpr (!PLAIN) {                      // the logits just produced: chunk n + 2
             if (n + 2 >= n_ch) {
 #pragma unroll
@@ -898,8 +833,8 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
     bf16x8 pA0, pA1, pB0, pB1;                     // weights of even / odd chunks
     {
         float lsum;
-        raise_reference(sA, pA0, pA1, lsum);
-        l_run = lsum;
+        sm.raise_reference(sA, pA0, pA1, lsum);
+        sm.l_run = lsum;
     }
     __syncthreads();                               // K chunks 0 and 1 have been read by every wave
     if (n_ch > 2) issue_k(IC<0>{}, 2, blk_of(2));
@@ -919,21 +854,8 @@ __global__ __launch_bounds__(BS * 2 * NH, 2) void attn_chunked_kernel(
     }
 
     // ---- epilogue ----------------------------------------------------------------
-    const float l_tot = l_run + other_half(l_run);
-    const float inv = 1.0f / l_tot;
-    if (i * BS + q_in_blk >= Sb) return;                  // token past the end of a partial last block
-    uint16_t* orow = out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t;
-#pragma unroll
-    for (int dc = 0; dc < DT; ++dc)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            f32x4 o4;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) o4[x] = oacc[dc][4 * rq + x] * inv;
-            *reinterpret_cast<bf16x4*>(orow + 32 * dc + 8 * rq + 4 * half) = __builtin_convertvector(o4, bf16x4);
-        }
-    if (lse != nullptr && half == 0)
-        lse[((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk] = mcb * (0.69314718055994530942f) + __logf(l_tot);
+    sm.template store<D>(i * BS + q_in_blk < Sb, out + b * os.b + h * os.h + ((int64_t)i * BS + q_in_blk) * os.t,
+                         lse != nullptr ? lse + ((int64_t)b * Hq + h) * S + (int64_t)i * BS + q_in_blk : nullptr, half);
 }
 
 // One wavefront per list row: counts the rows that break the rules the attention kernel relies on

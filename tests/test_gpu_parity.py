@@ -1207,12 +1207,14 @@ def test_ragged_batch_equals_single_sequence_calls(spa, oracle, lens, P, Hq, Hkv
     assert (idx.cpu() == o_idx).float().mean().item() > 0.97
 
 
-def test_fused_call_replays_from_a_hip_graph(spa, oracle):
+@pytest.mark.parametrize("Bs", [128, 64])
+def test_fused_call_replays_from_a_hip_graph(spa, oracle, Bs):
     """The calls only enqueue kernels on the caller's stream (no allocation, no synchronisation,
     no memset), so a fused call can be captured once and replayed; every replay, with eager work
-    and synchronisations between them, must reproduce the eager result bit for bit."""
+    and synchronisations between them, must reproduce the eager result bit for bit.  Both block sizes:
+    they run different attention kernels."""
     from paper_2602_21233_amd import binding
-    B, Hq, Hkv, NB, D, Bs, ns, nl, k = 1, 4, 2, 40, 128, 128, 1, 2, 6
+    B, Hq, Hkv, NB, D, ns, nl, k = 1, 4, 2, 40, 128, 1, 2, 6
     q, kk, v = _qkv(B, Hq, Hkv, NB * Bs, D, 41)
     dq, dk, dv = q.cuda(), kk.cuda(), v.cuda()
     eager, e_lse, e_idx, e_cnt = spa.fused(dq, dk, dv, Bs, ns, nl, k, return_lse=True, return_lists=True)
