@@ -611,7 +611,8 @@ def _unit_values(v):
     return (v.float() * s).to(torch.bfloat16)
 
 
-def test_attn_scale_and_large_logits(spa, oracle):
+@pytest.mark.parametrize("Bs", [128, 64])
+def test_attn_scale_and_large_logits(spa, oracle, Bs):
     """Peaked softmax (logit std ~5.7): a row's output is then close to a single value vector, i.e. as
     large as the largest |v| instead of an average of many.  The weights of the second product and
     the denominator both use the bf16-rounded weights, so what is left is the rounding of the weights
@@ -620,9 +621,9 @@ def test_attn_scale_and_large_logits(spa, oracle):
     q, kk, v = _qkv(1, 2, 1, 4 * 128, 128, 41)
     q = (q.float() * 4).to(torch.bfloat16)
     v = _unit_values(v)
-    idx, cnt = _oracle_lists(oracle, q, kk, 128, 1, 1, 1)
-    want, want_lse = oracle.attn(q, kk, v, idx, cnt, 128, scale=0.125)
-    out, lse = spa.attn(q.cuda(), kk.cuda(), v.cuda(), idx.cuda(), cnt.cuda(), 128, softmax_scale=0.125,
+    idx, cnt = _oracle_lists(oracle, q, kk, Bs, 1, 1, 1)
+    want, want_lse = oracle.attn(q, kk, v, idx, cnt, Bs, scale=0.125)
+    out, lse = spa.attn(q.cuda(), kk.cuda(), v.cuda(), idx.cuda(), cnt.cuda(), Bs, softmax_scale=0.125,
                         return_lse=True)
     assert want.abs().max().item() > 0.5                 # the premise: outputs as large as single values
     _assert_attn_close(out, want)
